@@ -1,0 +1,166 @@
+/* qadagrad.h -- C ABI of libqadagrad: the data-parallel hot path of QCMD adagrad and QRDA
+ * adagrad (arXiv 2208.05631, "Quantized Adaptive Subgradient Algorithms and Their
+ * Applications") on one AMD MI355X (gfx950).
+ *
+ * One training step of Algorithm 1, with the M workers and the parameter server living as
+ * slices of one GPU's memory:
+ *
+ *   worker m : g_m  = minibatch gradient of the logistic loss            qa_local_grad
+ *              (codes_m, s_m) = threshold quantizer + 2-bit encoding      qa_quantize_pack
+ *   server   : SynQ = (1/M) sum_m s_m * codes_m                           qa_aggregate_unpack
+ *              q = SynQ, or q = Q(SynQ) (second quantization)             } fused into
+ *   workers  : G += q^2, H = delta + sqrt(G), QCMD or QRDA update of x    } qa_step_qcmd / qa_step_qrda
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps device memory, and keeps no state between calls
+ *     (x, G, z and the step counter t live with the caller).
+ *   - Calls are asynchronous: kernels are enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns without synchronising.
+ *   - The qa_layout struct and every scalar are HOST values.
+ *   - Return value: QA_OK (0) or a negative QA_ERR_* code; nothing is launched when an
+ *     argument check fails.  The library never aborts and never throws.
+ *   - Buffers that are read or written with 128-bit accesses (g, x, G, z, gbar) must be
+ *     16-byte aligned; codes, scales, thresholds 4-byte aligned; workspace 256-byte aligned.
+ *
+ * Arithmetic (identical to what the CPU checker under oracle/ states)
+ *   - state, gradients, scales and thresholds are binary32; each element-wise formula is
+ *     evaluated one correctly rounded binary32 operation at a time in the order given in
+ *     the comments below, without fused multiply-add;
+ *   - every sum over many terms (over a bucket, over the workers, over a row or a
+ *     minibatch) is accumulated in binary64 and rounded once to binary32.
+ */
+#ifndef QADAGRAD_H
+#define QADAGRAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QA_VERSION 100 /* 0.1.0 */
+
+/* error codes */
+#define QA_OK 0
+#define QA_ERR_INVALID_ARG (-1) /* NULL required pointer, size/stride/scalar out of range   */
+#define QA_ERR_ALIGNMENT (-2)   /* a buffer does not have the alignment stated above         */
+#define QA_ERR_WORKSPACE (-3)   /* workspace NULL or smaller than qa_workspace_bytes says    */
+#define QA_ERR_LAUNCH (-4)      /* the HIP runtime refused a launch (hipGetLastError != 0)   */
+#define QA_ERR_UNSUPPORTED (-5) /* valid request this build does not implement               */
+
+/* second-quantization mode of the fused steps ("q_t = Q(SynQ_t)", Section 3.2, equation Qt;
+ * the methods marked with a dagger in Section 4.1 skip it) */
+#define QA_REQUANT_NONE 0   /* q = SynQ                                                      */
+#define QA_REQUANT_BUCKET 1 /* q = Q(SynQ) with one threshold/scale per bucket of the layout */
+#define QA_REQUANT_GLOBAL 2 /* q = Q(SynQ) with one threshold/scale for the whole vector     */
+
+/* flags of qa_quantize_pack */
+#define QA_THRESH_GIVEN 1u /* thresholds[] is an INPUT; only scales and codes are computed   */
+
+/* operations for qa_workspace_bytes */
+#define QA_OP_QUANTIZE 1
+#define QA_OP_STEP 2
+#define QA_OP_GRAD_CSR 3
+#define QA_OP_GRAD_DENSE 4
+
+/* data formats of qa_local_grad */
+#define QA_DENSE 0
+#define QA_CSR 1
+
+/* Shape of one step's messages (all HOST values).
+ *
+ * Encoding ("Encode" paragraph of Section 3.5: two bits per component plus one float):
+ *   component i of worker m sits in bits [2*(i%16), 2*(i%16)+1] of the 32-bit word
+ *   codes[m*code_stride + i/16];  00 = 0, 01 = +1, 11 = -1 (two's complement), 10 is never
+ *   written and is read as 0; unused bits of the last word are 0.
+ *   Its scale is scales[m*scale_stride + i/bucket] (bucket == 0: scales[m*scale_stride]).
+ */
+typedef struct {
+  int64_t d;            /* number of coordinates, 1 <= d < 2^40                               */
+  int32_t M;            /* number of workers, 1 <= M <= 4096                                  */
+  int32_t bucket;       /* elements per threshold/scale: a power of two >= 64, or 0 = one per
+                           vector (the paper's single float per message)                      */
+  float thr_coef;       /* threshold = thr_coef * mean|v| ; 0.75 in Section 3.5               */
+  int64_t code_stride;  /* 32-bit words between consecutive workers, >= ceil(d/16)            */
+  int64_t scale_stride; /* floats between consecutive workers in scales/thresholds, >= number
+                           of buckets = ceil(d/bucket) (1 if bucket == 0)                     */
+} qa_layout;
+
+int qa_version(void);
+const char* qa_strerror(int code);
+
+/* Bytes of device workspace that `op` needs for this layout (0 if none).  For
+ * QA_OP_GRAD_CSR / QA_OP_GRAD_DENSE only layout->d is used.  Returns 0 for a NULL or invalid
+ * layout. */
+size_t qa_workspace_bytes(const qa_layout* layout, int op);
+
+/* Minibatch gradient of one worker for the logistic loss log(1 + exp(-y a.x)), y in {-1,+1}
+ * (stochastic gradient of Section 3.1 for the L1-regularised logistic regression of
+ * Section 4.1; the regulariser is handled by the update, not here):
+ *     p_b    = a_{r_b} . x                        (sum in binary64, rounded to binary32)
+ *     coef_b = -y_{r_b} / (1 + exp(y_{r_b} p_b)) / B     (binary64, rounded to binary32)
+ *     g_j    = sum_b coef_b * a_{r_b, j}          (sum in binary64, rounded to binary32)
+ *     loss   = (1/B) sum_b log(1 + exp(-y_{r_b} p_b))
+ * format QA_DENSE: A_or_vals = A[n_rows][d] row-major, indptr = indices = NULL.
+ * format QA_CSR  : A_or_vals = vals[nnz], indptr[n_rows+1] (int64), indices[nnz] (int32,
+ *                  0 <= index < d; duplicate indices in a row add up).
+ * batch_rows[B] holds row ids in [0, n_rows) and may repeat.  g_out[d] is fully overwritten
+ * (zero where no batch row has an entry).  loss_out (one float, device) may be NULL.
+ * ws: qa_workspace_bytes(layout with d, QA_OP_GRAD_CSR or QA_OP_GRAD_DENSE) bytes; its
+ * contents on entry do not matter. */
+int qa_local_grad(int format, const float* A_or_vals, const int64_t* indptr, const int32_t* indices,
+                  int64_t n_rows, int64_t d, const float* y, const int32_t* batch_rows, int32_t B,
+                  const float* x, float* g_out, float* loss_out, void* ws, size_t ws_bytes,
+                  void* stream);
+
+/* Threshold quantizer of Sections 3.4-3.5 and 2-bit encoding for M gradients
+ * g[m*g_stride + i], m < M, i < d, bucket by bucket (bucket k = [k*b, min((k+1)*b, d)),
+ * n = its true length):
+ *     Delta = thr_coef * (sum |v_i|) / n                        (Section 3.5)
+ *     code_i = +1 if v_i > Delta, -1 if v_i < -Delta, else 0     (definition of Q_Delta)
+ *     s = (sum_{|v_i| > Delta} |v_i|) / #{|v_i| > Delta}, or 0 if that set is empty (s*_Delta)
+ * Writes codes[m*code_stride + w] for every w < ceil(d/16), scales[m*scale_stride + k] and,
+ * if thresholds != NULL and QA_THRESH_GIVEN is not set, thresholds[m*scale_stride + k].
+ * With QA_THRESH_GIVEN thresholds must be non-NULL and is read instead of computed.
+ * g_stride >= d and a multiple of 4.  ws: qa_workspace_bytes(layout, QA_OP_QUANTIZE). */
+int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, uint32_t* codes,
+                     float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/* Server average (equation SynQ_t of Section 3.1; "Average the quantized gradients" in
+ * Algorithm 1), materialised:  gbar_out[i] = (1/M) sum_m scales[m][i/bucket] * code[m][i],
+ * sum and division in binary64, rounded once. */
+int qa_aggregate_unpack(const qa_layout* layout, const uint32_t* codes, const float* scales,
+                        float* gbar_out, void* stream);
+
+/* One fused QCMD adagrad step (equations SynQ_t, Qt, Hq and QCMD; Algorithm 1 server and
+ * final worker block).  Per coordinate, with q from the average as selected by `requant`:
+ *     G = G + q*q ;  H = delta + sqrt(G)
+ *     u = x - (eta*q)/H ;  tau = (lambda*eta)/H ;  r = |u| - tau
+ *     x = r > 0 ? copysign(r, u) : +0
+ *     if z_or_null: z = z + q            (keeps the running sum for a later QRDA step)
+ * x, G (and z) are read and written in place.  eta > 0, lambda >= 0, delta > 0.
+ * ws: qa_workspace_bytes(layout, QA_OP_STEP); only used when the second quantization cannot
+ * be done in one pass (QA_REQUANT_GLOBAL, or QA_REQUANT_BUCKET with bucket > 4096); may be
+ * NULL with ws_bytes 0 otherwise. */
+int qa_step_qcmd(const qa_layout* layout, const uint32_t* codes, const float* scales, float* x,
+                 float* G, float* z_or_null, float eta, float lambda, float delta, int requant,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* One fused QRDA adagrad step (equations SynQ_t, Qt, Hq and QRDA).  Per coordinate:
+ *     G = G + q*q ;  H = delta + sqrt(G) ;  z = z + q
+ *     r = |z| - (float)t*lambda
+ *     x = r > 0 ? -copysign((eta*r)/H, z) : +0
+ * which is the printed sign(-z) (t eta / H) [ |z/t| - lambda ]_+ multiplied through by t.
+ * t >= 1 is the 1-based index of this step (z holds t gradients after the call).
+ * x is write-only; G and z are updated in place. */
+int qa_step_qrda(const qa_layout* layout, const uint32_t* codes, const float* scales, float* x,
+                 float* G, float* z, int64_t t, float eta, float lambda, float delta, int requant,
+                 void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QADAGRAD_H */

@@ -1,0 +1,12 @@
+"""libqadagrad: MI355X-native hot path of QCMD adagrad / QRDA adagrad (arXiv 2208.05631).
+
+The package is a thin binding over the C ABI declared in include/qadagrad.h.  Every step of
+the path runs in the HIP kernels of libqadagrad.so; torch is used for device memory and
+streams only.  Importing `binding` fails loudly if the shared library has not been built.
+"""
+from .binding import (  # noqa: F401
+    QA_CSR, QA_DENSE, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE, QA_OP_QUANTIZE, QA_OP_STEP,
+    QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL, QA_REQUANT_NONE, QA_THRESH_GIVEN, Layout, QaError,
+    lib_path, qa_aggregate_unpack, qa_local_grad, qa_quantize_pack, qa_step_qcmd, qa_step_qrda,
+    qa_strerror, qa_version, qa_workspace_bytes,
+)

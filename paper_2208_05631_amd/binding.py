@@ -1,0 +1,136 @@
+"""ctypes binding of libqadagrad.so: argument marshalling only.
+
+Each function has the name and the argument order of its C entry point in
+include/qadagrad.h and takes torch tensors (device memory) where the C call takes device
+pointers.  Nothing is computed here and there is no fallback: if the library is missing the
+import raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+QA_OK = 0
+QA_REQUANT_NONE, QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL = 0, 1, 2
+QA_THRESH_GIVEN = 1
+QA_OP_QUANTIZE, QA_OP_STEP, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE = 1, 2, 3, 4
+QA_DENSE, QA_CSR = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libqadagrad.so")
+
+
+class QaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {qa_strerror(code)} ({code})")
+
+
+class Layout(C.Structure):
+    """Mirror of qa_layout."""
+    _fields_ = [("d", C.c_int64), ("M", C.c_int32), ("bucket", C.c_int32),
+                ("thr_coef", C.c_float), ("code_stride", C.c_int64), ("scale_stride", C.c_int64)]
+
+    @staticmethod
+    def make(d, M, bucket=4096, thr_coef=0.75, code_stride=None, scale_stride=None):
+        W = (d + 15) // 16
+        nb = (d + bucket - 1) // bucket if bucket else 1
+        return Layout(d, M, bucket, thr_coef, code_stride or W, scale_stride or nb)
+
+    @property
+    def words(self):
+        return (self.d + 15) // 16
+
+    @property
+    def n_buckets(self):
+        return (self.d + self.bucket - 1) // self.bucket if self.bucket else 1
+
+
+if not os.path.exists(lib_path()):
+    raise ImportError(
+        f"{lib_path()} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+
+_lib = C.CDLL(lib_path())
+_vp, _sz = C.c_void_p, C.c_size_t
+_lib.qa_version.restype = C.c_int
+_lib.qa_strerror.restype = C.c_char_p
+_lib.qa_strerror.argtypes = [C.c_int]
+_lib.qa_workspace_bytes.restype = _sz
+_lib.qa_workspace_bytes.argtypes = [C.POINTER(Layout), C.c_int]
+_lib.qa_local_grad.argtypes = [C.c_int, _vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _vp, C.c_int32,
+                               _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.qa_quantize_pack.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp, C.c_uint32,
+                                  _vp, _sz, _vp]
+_lib.qa_aggregate_unpack.argtypes = [C.POINTER(Layout), _vp, _vp, _vp, _vp]
+_lib.qa_step_qcmd.argtypes = [C.POINTER(Layout), _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float,
+                              C.c_float, C.c_int, _vp, _sz, _vp]
+_lib.qa_step_qrda.argtypes = [C.POINTER(Layout), _vp, _vp, _vp, _vp, _vp, C.c_int64, C.c_float,
+                              C.c_float, C.c_float, C.c_int, _vp, _sz, _vp]
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _check(rc, where):
+    if rc != QA_OK:
+        raise QaError(rc, where)
+
+
+def qa_version() -> int:
+    return _lib.qa_version()
+
+
+def qa_strerror(code: int) -> str:
+    return _lib.qa_strerror(code).decode()
+
+
+def qa_workspace_bytes(layout: Layout, op: int) -> int:
+    return int(_lib.qa_workspace_bytes(C.byref(layout), op))
+
+
+def qa_local_grad(fmt, A_or_vals, indptr, indices, n_rows, d, y, batch_rows, B, x, g_out, loss_out,
+                  ws, stream=None):
+    _check(_lib.qa_local_grad(fmt, _p(A_or_vals), _p(indptr), _p(indices), n_rows, d, _p(y),
+                              _p(batch_rows), B, _p(x), _p(g_out), _p(loss_out), _p(ws), _nbytes(ws),
+                              _stream(stream)), "qa_local_grad")
+
+
+def qa_quantize_pack(layout, g, g_stride, codes, scales, thresholds, flags, ws, stream=None):
+    _check(_lib.qa_quantize_pack(C.byref(layout), _p(g), g_stride, _p(codes), _p(scales),
+                                 _p(thresholds), flags, _p(ws), _nbytes(ws), _stream(stream)),
+           "qa_quantize_pack")
+
+
+def qa_aggregate_unpack(layout, codes, scales, gbar_out, stream=None):
+    _check(_lib.qa_aggregate_unpack(C.byref(layout), _p(codes), _p(scales), _p(gbar_out),
+                                    _stream(stream)), "qa_aggregate_unpack")
+
+
+def qa_step_qcmd(layout, codes, scales, x, G, z_or_null, eta, lam, delta, requant, ws, stream=None):
+    _check(_lib.qa_step_qcmd(C.byref(layout), _p(codes), _p(scales), _p(x), _p(G), _p(z_or_null),
+                             eta, lam, delta, requant, _p(ws), _nbytes(ws), _stream(stream)),
+           "qa_step_qcmd")
+
+
+def qa_step_qrda(layout, codes, scales, x, G, z, t, eta, lam, delta, requant, ws, stream=None):
+    _check(_lib.qa_step_qrda(C.byref(layout), _p(codes), _p(scales), _p(x), _p(G), _p(z), t, eta,
+                             lam, delta, requant, _p(ws), _nbytes(ws), _stream(stream)),
+           "qa_step_qrda")

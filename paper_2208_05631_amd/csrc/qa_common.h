@@ -1,0 +1,103 @@
+// Internal helpers of libqadagrad (gfx950 only).  Not part of the public interface.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qadagrad.h"
+
+namespace qa {
+
+constexpr int kThreads = 256;          // work-group size of every tile kernel: 4 wave64
+constexpr int kWave = 64;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kTile = 4096;            // coordinates per work-group tile = 256 code words
+constexpr int kTileWords = kTile / 16;
+
+// ---- host-side argument checks ---------------------------------------------------------
+
+inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+inline int ilog2(int64_t v) { int l = 0; while ((int64_t(1) << l) < v) ++l; return l; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline int64_t words_of(int64_t d) { return (d + 15) / 16; }
+inline int64_t tiles_of(int64_t d) { return (d + kTile - 1) / kTile; }
+inline int64_t buckets_of(int64_t d, int64_t bucket) {
+  return bucket > 0 ? (d + bucket - 1) / bucket : 1;
+}
+
+// Layout rules shared by every entry point that takes a qa_layout.
+inline int check_layout(const qa_layout* L) {
+  if (!L) return QA_ERR_INVALID_ARG;
+  if (L->d < 1 || L->d >= (int64_t(1) << 40)) return QA_ERR_INVALID_ARG;
+  if (L->M < 1 || L->M > 4096) return QA_ERR_INVALID_ARG;
+  if (L->bucket != 0 && (L->bucket < 64 || !is_pow2(L->bucket))) return QA_ERR_INVALID_ARG;
+  if (!(L->thr_coef > 0.0f) || !(L->thr_coef < 1e30f)) return QA_ERR_INVALID_ARG;
+  if (L->code_stride < words_of(L->d)) return QA_ERR_INVALID_ARG;
+  if (L->scale_stride < buckets_of(L->d, L->bucket)) return QA_ERR_INVALID_ARG;
+  return QA_OK;
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? QA_OK : QA_ERR_LAUNCH; }
+
+// ---- device-side reductions (binary64, fixed order: run-to-run deterministic) -----------
+
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+  return __shfl_xor(v, mask, kWave);
+}
+
+// Sum of `v` over aligned segments of `seg` consecutive threads (seg a power of two,
+// 1 <= seg <= 256); every thread receives the sum of its own segment.  `lds` points to at
+// least kWaves doubles of shared memory that no one else uses across the call.
+// Contains barriers when seg > 64: every thread of the work-group must call it.
+__device__ __forceinline__ double segment_sum(double v, int seg, double* lds) {
+  const int lim = seg < kWave ? seg : kWave;
+  for (int off = 1; off < lim; off <<= 1) v += shfl_xor_f64(v, off);
+  if (seg > kWave) {
+    const int wave = threadIdx.x / kWave;
+    __syncthreads();
+    if ((threadIdx.x % kWave) == 0) lds[wave] = v;
+    __syncthreads();
+    const int wps = seg / kWave;              // waves per segment: 2 or 4
+    const int w0 = wave & ~(wps - 1);
+    double t = lds[w0];
+    for (int k = 1; k < wps; ++k) t += lds[w0 + k];
+    v = t;
+  }
+  return v;
+}
+
+__device__ __forceinline__ uint32_t segment_sum_u32(uint32_t v, int seg, uint32_t* lds) {
+  const int lim = seg < kWave ? seg : kWave;
+  for (int off = 1; off < lim; off <<= 1) v += __shfl_xor(v, off, kWave);
+  if (seg > kWave) {
+    const int wave = threadIdx.x / kWave;
+    __syncthreads();
+    if ((threadIdx.x % kWave) == 0) lds[wave] = v;
+    __syncthreads();
+    const int wps = seg / kWave;
+    const int w0 = wave & ~(wps - 1);
+    uint32_t t = lds[w0];
+    for (int k = 1; k < wps; ++k) t += lds[w0 + k];
+    v = t;
+  }
+  return v;
+}
+
+// Threshold and scale from the binary64 sums, rounded once (Sections 3.4-3.5).
+__device__ __forceinline__ float threshold_from_sum(double S1, float thr_coef, int64_t n) {
+  return (float)(((double)thr_coef * S1) / (double)n);
+}
+__device__ __forceinline__ float scale_from_sum(double S2, uint64_t cnt) {
+  return cnt ? (float)(S2 / (double)cnt) : 0.0f;
+}
+
+// Ternary code as the 2-bit field 00 / 01 / 11; NaN compares false on both sides -> 00.
+__device__ __forceinline__ uint32_t ternary_field(float v, float Delta) {
+  return v > Delta ? 1u : (v < -Delta ? 3u : 0u);
+}
+
+#endif  // __HIPCC__
+
+}  // namespace qa

@@ -1,0 +1,180 @@
+// Minibatch gradient of the logistic loss for one worker (stochastic gradient of Section 3.1
+// for the L1-regularised logistic regression of Section 4.1, arXiv 2208.05631), dense rows or
+// CSR rows, for gfx950.
+//
+//   margins  : p_b = a_{r_b}.x in binary64 (work-group per row for dense, wave per row for CSR),
+//              then coef_b = -y/(1+exp(y p_b))/B and the row's loss, in binary64.
+//   gradient : dense -- one thread per 4 columns walks the batch in order, binary64 accumulator;
+//              CSR   -- hardware binary64 atomic adds into a d-long accumulator that is cleared
+//                       only at the batch's columns, then rounded into the zero-filled g.
+//   Every product coef*a is exact in binary64, so only the order of the binary64 additions can
+//   differ from a sequential evaluation.
+#include "qa_common.h"
+
+namespace qa {
+
+constexpr int kMaxBatch = 65536;
+
+struct GradArgs {
+  const float* A;            // dense matrix or CSR values
+  const int64_t* indptr;
+  const int32_t* indices;
+  int64_t n_rows, d;
+  const float* y;
+  const int32_t* rows;
+  int B;
+  const float* x;
+  float* g;
+  float* loss_out;
+  float* coef;               // [B]   workspace
+  double* loss_part;         // [B]   workspace
+  double* acc;               // [d]   workspace (CSR)
+};
+
+// coef and loss of one sample from its binary32 margin term p = a.x
+__device__ __forceinline__ void logistic_terms(float p, float y, int B, float* coef, double* loss) {
+  const double m = (double)y * (double)p;
+  const double e = exp(-fabs(m));
+  *loss = log1p(e) + (m < 0.0 ? -m : 0.0);
+  const double sig = m >= 0.0 ? e / (1.0 + e) : 1.0 / (1.0 + e);
+  *coef = (float)((-(double)y * sig) / (double)B);
+}
+
+__global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a) {
+  __shared__ double lds_d[kWaves];
+  const int b = blockIdx.x;
+  const int64_t r = a.rows[b];
+  const bool ok = r >= 0 && r < a.n_rows;
+  double s = 0.0;
+  if (ok) {
+    const float* row = a.A + r * a.d;
+    for (int64_t j = threadIdx.x; j < a.d; j += kThreads) s = fma((double)row[j], (double)a.x[j], s);
+  }
+  s = segment_sum(s, kThreads, lds_d);
+  if (threadIdx.x == 0) {
+    float c = 0.0f; double l = 0.0;
+    if (ok) logistic_terms((float)s, a.y[r], a.B, &c, &l);
+    a.coef[b] = c; a.loss_part[b] = l;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void dense_colsum_kernel(GradArgs a) {
+  const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= a.d) return;
+  double acc = 0.0;
+  for (int b = 0; b < a.B; ++b) {
+    const int64_t r = a.rows[b];
+    if (r < 0 || r >= a.n_rows) continue;
+    acc = fma((double)a.coef[b], (double)a.A[r * a.d + j], acc);
+  }
+  a.g[j] = (float)acc;
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* p, int64_t n) {
+  const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+  if (i + 3 < n) *reinterpret_cast<float4*>(p + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+  else for (int e = 0; e < 4; ++e) if (i + e < n) p[i + e] = 0.0f;
+}
+
+// one wave per batch row: margin, coef, loss; also clears the accumulator at the row's columns
+__global__ __launch_bounds__(kThreads) void csr_margin_kernel(GradArgs a) {
+  const int b = blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (b >= a.B) return;
+  const int lane = threadIdx.x % kWave;
+  const int64_t r = a.rows[b];
+  const bool ok = r >= 0 && r < a.n_rows;
+  double s = 0.0;
+  if (ok) {
+    const int64_t k0 = a.indptr[r], k1 = a.indptr[r + 1];
+    for (int64_t k = k0 + lane; k < k1; k += kWave) {
+      const uint32_t c = (uint32_t)a.indices[k];
+      if (c < (uint64_t)a.d) {
+        s = fma((double)a.A[k], (double)a.x[c], s);
+        a.acc[c] = 0.0;
+      }
+    }
+  }
+  for (int off = 1; off < kWave; off <<= 1) s += shfl_xor_f64(s, off);
+  if (lane == 0) {
+    float c = 0.0f; double l = 0.0;
+    if (ok) logistic_terms((float)s, a.y[r], a.B, &c, &l);
+    a.coef[b] = c; a.loss_part[b] = l;
+  }
+}
+
+template <bool FINALIZE>
+__global__ __launch_bounds__(kThreads) void csr_scatter_kernel(GradArgs a) {
+  const int b = blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (b >= a.B) return;
+  const int lane = threadIdx.x % kWave;
+  const int64_t r = a.rows[b];
+  if (r < 0 || r >= a.n_rows) return;
+  const double cf = (double)a.coef[b];
+  const int64_t k0 = a.indptr[r], k1 = a.indptr[r + 1];
+  for (int64_t k = k0 + lane; k < k1; k += kWave) {
+    const uint32_t c = (uint32_t)a.indices[k];
+    if (c >= (uint64_t)a.d) continue;
+    if (FINALIZE) a.g[c] = (float)a.acc[c];
+    else unsafeAtomicAdd(&a.acc[c], cf * (double)a.A[k]);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void loss_finalize_kernel(GradArgs a) {
+  __shared__ double lds_d[kWaves];
+  double s = 0.0;
+  for (int b = threadIdx.x; b < a.B; b += kThreads) s += a.loss_part[b];
+  s = segment_sum(s, kThreads, lds_d);
+  if (threadIdx.x == 0) *a.loss_out = (float)(s / (double)a.B);
+}
+
+static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+size_t grad_workspace_bytes(int64_t d, bool csr) {
+  return align256((size_t)kMaxBatch * sizeof(float)) + align256((size_t)kMaxBatch * sizeof(double)) +
+         (csr ? align256((size_t)d * sizeof(double)) : 0);
+}
+
+}  // namespace qa
+
+extern "C" int qa_local_grad(int format, const float* A_or_vals, const int64_t* indptr,
+                             const int32_t* indices, int64_t n_rows, int64_t d, const float* y,
+                             const int32_t* batch_rows, int32_t B, const float* x, float* g_out,
+                             float* loss_out, void* ws, size_t ws_bytes, void* stream_) {
+  using namespace qa;
+  if (format != QA_DENSE && format != QA_CSR) return QA_ERR_INVALID_ARG;
+  if (!A_or_vals || !y || !batch_rows || !x || !g_out) return QA_ERR_INVALID_ARG;
+  if (format == QA_CSR && (!indptr || !indices)) return QA_ERR_INVALID_ARG;
+  if (n_rows < 1 || d < 1 || d >= (int64_t(1) << 31) || B < 1 || B > kMaxBatch)
+    return QA_ERR_INVALID_ARG;
+  if (!aligned(g_out, 16) || !aligned(A_or_vals, 4) || !aligned(x, 4) || !aligned(indptr, 8) ||
+      !aligned(indices, 4) || !aligned(batch_rows, 4) || !aligned(loss_out, 4))
+    return QA_ERR_ALIGNMENT;
+  const bool csr = format == QA_CSR;
+  if (!ws || ws_bytes < grad_workspace_bytes(d, csr)) return QA_ERR_WORKSPACE;
+  if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+  GradArgs a{};
+  a.A = A_or_vals; a.indptr = indptr; a.indices = indices; a.n_rows = n_rows; a.d = d;
+  a.y = y; a.rows = batch_rows; a.B = B; a.x = x; a.g = g_out; a.loss_out = loss_out;
+  char* p = static_cast<char*>(ws);
+  a.coef = reinterpret_cast<float*>(p);        p += align256((size_t)kMaxBatch * sizeof(float));
+  a.loss_part = reinterpret_cast<double*>(p);  p += align256((size_t)kMaxBatch * sizeof(double));
+  a.acc = reinterpret_cast<double*>(p);
+
+  const dim3 block(kThreads);
+  if (!csr) {
+    hipLaunchKernelGGL(dense_margin_kernel, dim3(B), block, 0, stream, a);
+    hipLaunchKernelGGL(dense_colsum_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads)), block, 0,
+                       stream, a);
+  } else {
+    const dim3 grid_rows((B + kWaves - 1) / kWaves);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((d + 4 * kThreads - 1) / (4 * kThreads))),
+                       block, 0, stream, g_out, d);
+    hipLaunchKernelGGL(csr_margin_kernel, grid_rows, block, 0, stream, a);
+    hipLaunchKernelGGL((csr_scatter_kernel<false>), grid_rows, block, 0, stream, a);
+    hipLaunchKernelGGL((csr_scatter_kernel<true>), grid_rows, block, 0, stream, a);
+  }
+  if (loss_out) hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), block, 0, stream, a);
+  return launch_status();
+}

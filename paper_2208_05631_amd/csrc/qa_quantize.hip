@@ -1,0 +1,329 @@
+// Threshold quantizer + 2-bit encoding (Sections 3.4-3.5 of arXiv 2208.05631) for gfx950.
+//
+// Tile = 4096 elements of one worker's gradient per 256-thread work-group.  Thread t holds
+// four float4 groups f = j*256 + t (j = 0..3), i.e. elements 4f..4f+3 of the tile, so that
+// every global load instruction of a wave reads 1 KiB of consecutive memory.
+//
+//   bucket <= 4096 : one kernel; sums, threshold, scale and codes of a tile's buckets are
+//                    formed in registers/LDS; the gradient is read once (4 B/elem + 0.25 B out).
+//   bucket  > 4096 or 0 (whole vector): tile partial sums -> finalize threshold -> codes and
+//                    tile partial (count, sum) -> finalize scale; the gradient is read twice.
+#include "qa_common.h"
+
+namespace qa {
+
+struct QuantArgs {
+  const float* g;
+  int64_t g_stride;
+  int64_t d;
+  int64_t W;               // ceil(d/16)
+  uint32_t* codes;
+  int64_t code_stride;
+  float* scales;
+  float* thresholds;       // user array, may be null
+  int64_t scale_stride;
+  int log2b;               // log2(bucket); unused when bucket == 0
+  float thr_coef;
+  int thresh_given;
+  // two-pass path
+  double* part_sum;        // [M][ntiles]
+  uint32_t* part_cnt;      // [M][ntiles]
+  float* thr_ws;           // [M][nb]
+  int64_t ntiles;
+  int64_t tiles_per_bucket;  // ntiles when bucket == 0
+  int64_t nb;
+  int64_t bucket_len;        // elements per bucket (d when bucket == 0)
+};
+
+// Load the thread's 4 float4 groups of tile `tile`; elements at or beyond d read as +0.
+__device__ __forceinline__ void load_tile(const float* __restrict__ g, int64_t d, int64_t tile,
+                                          float v[4][4]) {
+  const int64_t base = tile * kTile;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int64_t i = base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
+    if (i + 3 < d) {
+      const float4 q = *reinterpret_cast<const float4*>(g + i);
+      v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[j][e] = (i + e < d) ? g[i + e] : 0.0f;
+    }
+  }
+}
+
+// Ternary fields of the thread's 16 elements -> the four code words of its quad (group j of
+// lanes 4q..4q+3 is code word j*64 + t/4 of the tile); lane (t & 3) == j stores word j.
+__device__ __forceinline__ void pack_and_store(const float v[4][4], const float Delta[4],
+                                               uint32_t* __restrict__ codes_m, int64_t tile,
+                                               int64_t W) {
+  const int t = threadIdx.x;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t b = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) b |= ternary_field(v[j][e], Delta[j]) << (2 * e);
+    uint32_t w = b << (8 * (t & 3));
+    w |= __shfl_xor(w, 1, kWave);
+    w |= __shfl_xor(w, 2, kWave);
+    if ((t & 3) == j) mine = w;
+  }
+  const int64_t widx = tile * kTileWords + (t & 3) * 64 + (t >> 2);
+  if (widx < W) codes_m[widx] = mine;
+}
+
+__device__ __forceinline__ void kept_sums(const float v[4], float Delta, double* s_out,
+                                          uint32_t* c_out) {
+  double s = 0.0;
+  uint32_t c = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float av = fabsf(v[e]);
+    if (av > Delta) { s += (double)av; ++c; }
+  }
+  *s_out = s; *c_out = c;
+}
+
+// ---- bucket <= 4096 : single pass ----------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void quantize_small_bucket_kernel(QuantArgs a) {
+  __shared__ double lds_d[kWaves];
+  __shared__ uint32_t lds_u[kWaves];
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const float* g = a.g + (int64_t)m * a.g_stride;
+  const int t = threadIdx.x;
+  const int b = 1 << a.log2b;
+
+  float v[4][4];
+  load_tile(g, a.d, tile, v);
+
+  // threads per bucket inside one j-slice (a slice is 1024 consecutive elements)
+  const int seg = b >= 1024 ? kThreads : b / 4;
+  float Delta[4];
+  int64_t kidx[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    kidx[j] = (tile * kTile + (int64_t)(j * kThreads + t) * 4) >> a.log2b;
+
+  if (!a.thresh_given) {
+    double S1[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      double s = 0.0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
+      S1[j] = segment_sum(s, seg, lds_d);
+    }
+    if (b == 2048) {
+      const double s01 = S1[0] + S1[1], s23 = S1[2] + S1[3];
+      S1[0] = S1[1] = s01; S1[2] = S1[3] = s23;
+    } else if (b == 4096) {
+      const double s = (S1[0] + S1[1]) + (S1[2] + S1[3]);
+      S1[0] = S1[1] = S1[2] = S1[3] = s;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t lo = kidx[j] << a.log2b;
+      const int64_t n = (a.d - lo) < (int64_t)b ? (a.d - lo) : (int64_t)b;   // true length
+      Delta[j] = n > 0 ? threshold_from_sum(S1[j], a.thr_coef, n) : 0.0f;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      Delta[j] = kidx[j] < a.nb ? a.thresholds[(int64_t)m * a.scale_stride + kidx[j]] : 0.0f;
+  }
+
+  double S2[4];
+  uint32_t C[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    double s; uint32_t c;
+    kept_sums(v[j], Delta[j], &s, &c);
+    S2[j] = segment_sum(s, seg, lds_d);
+    C[j] = segment_sum_u32(c, seg, lds_u);
+  }
+  if (b == 2048) {
+    const double s01 = S2[0] + S2[1], s23 = S2[2] + S2[3];
+    S2[0] = S2[1] = s01; S2[2] = S2[3] = s23;
+    const uint32_t c01 = C[0] + C[1], c23 = C[2] + C[3];
+    C[0] = C[1] = c01; C[2] = C[3] = c23;
+  } else if (b == 4096) {
+    const double s = (S2[0] + S2[1]) + (S2[2] + S2[3]);
+    S2[0] = S2[1] = S2[2] = S2[3] = s;
+    const uint32_t c = C[0] + C[1] + C[2] + C[3];
+    C[0] = C[1] = C[2] = C[3] = c;
+  }
+
+  // the thread holding a bucket's first element writes its scale and threshold
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int64_t first_elem = kidx[j] << a.log2b;
+    const int64_t my_elem = tile * kTile + (int64_t)(j * kThreads + t) * 4;
+    if (my_elem == first_elem && kidx[j] < a.nb) {
+      a.scales[(int64_t)m * a.scale_stride + kidx[j]] = scale_from_sum(S2[j], C[j]);
+      if (a.thresholds && !a.thresh_given)
+        a.thresholds[(int64_t)m * a.scale_stride + kidx[j]] = Delta[j];
+    }
+  }
+  pack_and_store(v, Delta, a.codes + (int64_t)m * a.code_stride, tile, a.W);
+}
+
+// ---- bucket > 4096 or whole vector : two passes -----------------------------------------------
+
+// pass 1: part_sum[m][tile] = sum |v| over the tile
+__global__ __launch_bounds__(kThreads) void quantize_abs_partial_kernel(QuantArgs a) {
+  __shared__ double lds_d[kWaves];
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  float v[4][4];
+  load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+  double s = 0.0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
+  s = segment_sum(s, kThreads, lds_d);
+  if (threadIdx.x == 0) a.part_sum[(int64_t)m * a.ntiles + tile] = s;
+}
+
+// finalize 1: one work-group per (bucket, worker): threshold from the tile partials
+__global__ __launch_bounds__(kThreads) void quantize_threshold_finalize_kernel(QuantArgs a) {
+  __shared__ double lds_d[kWaves];
+  const int64_t k = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t t0 = k * a.tiles_per_bucket;
+  const int64_t t1 = (t0 + a.tiles_per_bucket) < a.ntiles ? (t0 + a.tiles_per_bucket) : a.ntiles;
+  double s = 0.0;
+  for (int64_t i = t0 + threadIdx.x; i < t1; i += kThreads) s += a.part_sum[(int64_t)m * a.ntiles + i];
+  s = segment_sum(s, kThreads, lds_d);
+  if (threadIdx.x == 0) {
+    const int64_t lo = k * a.bucket_len;
+    const int64_t n = (a.d - lo) < a.bucket_len ? (a.d - lo) : a.bucket_len;
+    const float Delta = threshold_from_sum(s, a.thr_coef, n);
+    a.thr_ws[(int64_t)m * a.nb + k] = Delta;
+    if (a.thresholds) a.thresholds[(int64_t)m * a.scale_stride + k] = Delta;
+  }
+}
+
+// pass 2: codes of the tile and its partial (count, sum) of kept magnitudes
+__global__ __launch_bounds__(kThreads) void quantize_codes_partial_kernel(QuantArgs a) {
+  __shared__ double lds_d[kWaves];
+  __shared__ uint32_t lds_u[kWaves];
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t k = tile / a.tiles_per_bucket;
+  const float D = a.thresh_given ? a.thresholds[(int64_t)m * a.scale_stride + k]
+                                 : a.thr_ws[(int64_t)m * a.nb + k];
+  float v[4][4];
+  load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+  double s = 0.0;
+  uint32_t c = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    double sj; uint32_t cj;
+    kept_sums(v[j], D, &sj, &cj);
+    s += sj; c += cj;
+  }
+  s = segment_sum(s, kThreads, lds_d);
+  c = segment_sum_u32(c, kThreads, lds_u);
+  if (threadIdx.x == 0) {
+    a.part_sum[(int64_t)m * a.ntiles + tile] = s;
+    a.part_cnt[(int64_t)m * a.ntiles + tile] = c;
+  }
+  const float Delta[4] = {D, D, D, D};
+  pack_and_store(v, Delta, a.codes + (int64_t)m * a.code_stride, tile, a.W);
+}
+
+// finalize 2: scale of each (bucket, worker)
+__global__ __launch_bounds__(kThreads) void quantize_scale_finalize_kernel(QuantArgs a) {
+  __shared__ double lds_d[kWaves];
+  __shared__ double lds_c[kWaves];
+  const int64_t k = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t t0 = k * a.tiles_per_bucket;
+  const int64_t t1 = (t0 + a.tiles_per_bucket) < a.ntiles ? (t0 + a.tiles_per_bucket) : a.ntiles;
+  double s = 0.0, c = 0.0;   // counts are integers < 2^53: exact in binary64
+  for (int64_t i = t0 + threadIdx.x; i < t1; i += kThreads) {
+    s += a.part_sum[(int64_t)m * a.ntiles + i];
+    c += (double)a.part_cnt[(int64_t)m * a.ntiles + i];
+  }
+  s = segment_sum(s, kThreads, lds_d);
+  c = segment_sum(c, kThreads, lds_c);
+  if (threadIdx.x == 0)
+    a.scales[(int64_t)m * a.scale_stride + k] = scale_from_sum(s, (uint64_t)c);
+}
+
+// ---- host side -------------------------------------------------------------------------------
+
+static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+size_t quantize_workspace_bytes(const qa_layout* L) {
+  if (L->bucket != 0 && L->bucket <= kTile) return 0;
+  const int64_t nt = tiles_of(L->d), nb = buckets_of(L->d, L->bucket);
+  return align256((size_t)L->M * nt * sizeof(double)) + align256((size_t)L->M * nt * sizeof(uint32_t)) +
+         align256((size_t)L->M * nb * sizeof(float));
+}
+
+int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32_t* codes,
+                    float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
+                    hipStream_t stream) {
+  QuantArgs a{};
+  a.g = g; a.g_stride = g_stride; a.d = L->d; a.W = words_of(L->d);
+  a.codes = codes; a.code_stride = L->code_stride;
+  a.scales = scales; a.thresholds = thresholds; a.scale_stride = L->scale_stride;
+  a.thr_coef = L->thr_coef;
+  a.thresh_given = (flags & QA_THRESH_GIVEN) ? 1 : 0;
+  a.ntiles = tiles_of(L->d);
+  a.nb = buckets_of(L->d, L->bucket);
+  const dim3 block(kThreads);
+  if (a.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+  const dim3 grid_tiles((unsigned)a.ntiles, (unsigned)L->M);
+
+  if (L->bucket != 0 && L->bucket <= kTile) {
+    a.log2b = ilog2(L->bucket);
+    a.bucket_len = L->bucket;
+    hipLaunchKernelGGL(quantize_small_bucket_kernel, grid_tiles, block, 0, stream, a);
+    return launch_status();
+  }
+
+  const size_t need = quantize_workspace_bytes(L);
+  if (!ws || ws_bytes < need) return QA_ERR_WORKSPACE;
+  if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+  char* p = static_cast<char*>(ws);
+  a.part_sum = reinterpret_cast<double*>(p);
+  p += align256((size_t)L->M * a.ntiles * sizeof(double));
+  a.part_cnt = reinterpret_cast<uint32_t*>(p);
+  p += align256((size_t)L->M * a.ntiles * sizeof(uint32_t));
+  a.thr_ws = reinterpret_cast<float*>(p);
+  a.bucket_len = L->bucket ? L->bucket : L->d;
+  a.tiles_per_bucket = L->bucket ? L->bucket / kTile : a.ntiles;
+  a.log2b = L->bucket ? ilog2(L->bucket) : 0;
+  const dim3 grid_buckets((unsigned)a.nb, (unsigned)L->M);
+
+  if (!a.thresh_given) {
+    hipLaunchKernelGGL(quantize_abs_partial_kernel, grid_tiles, block, 0, stream, a);
+    hipLaunchKernelGGL(quantize_threshold_finalize_kernel, grid_buckets, block, 0, stream, a);
+  }
+  hipLaunchKernelGGL(quantize_codes_partial_kernel, grid_tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(quantize_scale_finalize_kernel, grid_buckets, block, 0, stream, a);
+  return launch_status();
+}
+
+}  // namespace qa
+
+extern "C" int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride,
+                                uint32_t* codes, float* scales, float* thresholds, uint32_t flags,
+                                void* ws, size_t ws_bytes, void* stream) {
+  using namespace qa;
+  int rc = check_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!g || !codes || !scales) return QA_ERR_INVALID_ARG;
+  if (flags & ~QA_THRESH_GIVEN) return QA_ERR_INVALID_ARG;
+  if ((flags & QA_THRESH_GIVEN) && !thresholds) return QA_ERR_INVALID_ARG;
+  if (g_stride < layout->d || (g_stride % 4) != 0) return QA_ERR_INVALID_ARG;
+  if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(thresholds, 4))
+    return QA_ERR_ALIGNMENT;
+  return quantize_launch(layout, g, g_stride, codes, scales, thresholds, flags, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}

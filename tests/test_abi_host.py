@@ -1,0 +1,102 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes workspaces, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+qa = pytest.importorskip("paper_2208_05631_amd", reason="libqadagrad.so not built")
+from paper_2208_05631_amd import binding as B  # noqa: E402
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "qadagrad.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(qa_[a-z_]+)\s*\(", hdr))
+    assert {"qa_local_grad", "qa_quantize_pack", "qa_aggregate_unpack", "qa_step_qcmd",
+            "qa_step_qrda", "qa_workspace_bytes", "qa_strerror", "qa_version"} <= names
+    lib = C.CDLL(B.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+    assert qa.qa_version() == 100
+
+
+def test_binding_mirrors_the_header_names():
+    for n in ("qa_local_grad", "qa_quantize_pack", "qa_aggregate_unpack", "qa_step_qcmd",
+              "qa_step_qrda", "qa_workspace_bytes", "qa_strerror", "qa_version"):
+        assert callable(getattr(qa, n))
+
+
+def test_error_strings():
+    for code in range(0, -6, -1):
+        assert "unknown" not in qa.qa_strerror(code)
+    assert "unknown" in qa.qa_strerror(-99)
+
+
+def test_workspace_sizes():
+    L = qa.Layout.make(10**6, 8, 4096)
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE) == 0          # single pass, no scratch
+    Lg = qa.Layout.make(10**6, 8, 0)
+    nt = (10**6 + 4095) // 4096
+    assert qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE) >= 8 * nt * 12
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_STEP) >= 4 * 10**6       # averaged vector for GLOBAL
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR) >= 8 * 10**6
+    assert 0 < qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_DENSE) < 8 * 10**6
+    bad = qa.Layout.make(10**6, 8, 100)                               # not a power of two
+    assert qa.qa_workspace_bytes(bad, qa.QA_OP_STEP) == 0
+
+
+FAKE = 0x10000        # non-null, 16-byte aligned, never dereferenced: checks fail first
+
+
+def _step(L, codes=FAKE, scales=FAKE, x=FAKE, G=FAKE, z=None, eta=0.1, lam=0.0, delta=1e-8,
+          requant=0, ws=None, wsb=0):
+    return B._lib.qa_step_qcmd(C.byref(L), codes, scales, x, G, z, eta, lam, delta, requant, ws, wsb,
+                               None)
+
+
+def test_step_argument_checks():
+    ok = qa.Layout.make(1000, 4, 0)
+    assert _step(ok, codes=None) == -1
+    assert _step(ok, x=None) == -1
+    assert _step(ok, eta=0.0) == -1
+    assert _step(ok, lam=-1.0) == -1
+    assert _step(ok, delta=0.0) == -1
+    assert _step(ok, requant=7) == -1
+    assert _step(ok, requant=qa.QA_REQUANT_BUCKET) == -1             # no buckets in this layout
+    assert _step(ok, x=FAKE + 4) == -2
+    assert _step(ok, requant=qa.QA_REQUANT_GLOBAL) == -3             # needs a workspace
+    assert _step(ok, requant=qa.QA_REQUANT_GLOBAL, ws=FAKE, wsb=16) == -3
+    for bad in (qa.Layout.make(0, 4, 0), qa.Layout.make(1000, 0, 0), qa.Layout.make(1000, 4, 100),
+                qa.Layout.make(1000, 4, 32), qa.Layout.make(1000, 4, 0, code_stride=10),
+                qa.Layout.make(1000, 4, 64, scale_stride=3), qa.Layout.make(1000, 4, 0, thr_coef=0.0)):
+        assert _step(bad) == -1
+    assert B._lib.qa_step_qrda(C.byref(ok), FAKE, FAKE, FAKE, FAKE, None, 1, 0.1, 0.0, 1e-8, 0, None,
+                               0, None) == -1                        # z is required
+    assert B._lib.qa_step_qrda(C.byref(ok), FAKE, FAKE, FAKE, FAKE, FAKE, 0, 0.1, 0.0, 1e-8, 0, None,
+                               0, None) == -1                        # t >= 1
+
+
+def test_quantize_and_aggregate_argument_checks():
+    ok = qa.Layout.make(1000, 4, 0)
+    q = B._lib.qa_quantize_pack
+    assert q(C.byref(ok), None, 1000, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -1
+    assert q(C.byref(ok), FAKE, 999, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -1    # stride < d
+    assert q(C.byref(ok), FAKE, 1002, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -1   # not % 4
+    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 1, FAKE, 1 << 20, None) == -1   # given, null
+    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 2, FAKE, 1 << 20, None) == -1   # unknown flag
+    assert q(C.byref(ok), FAKE + 4, 1000, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -2
+    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 0, None, 0, None) == -3
+    assert B._lib.qa_aggregate_unpack(C.byref(ok), FAKE, FAKE, None, None) == -1
+    assert B._lib.qa_aggregate_unpack(C.byref(ok), FAKE, FAKE, FAKE + 8, None) == -2
+
+
+def test_local_grad_argument_checks():
+    f = B._lib.qa_local_grad
+    assert f(5, FAKE, None, None, 10, 10, FAKE, FAKE, 4, FAKE, FAKE, None, FAKE, 1 << 30, None) == -1
+    assert f(1, FAKE, None, None, 10, 10, FAKE, FAKE, 4, FAKE, FAKE, None, FAKE, 1 << 30, None) == -1
+    assert f(0, FAKE, None, None, 10, 10, FAKE, FAKE, 0, FAKE, FAKE, None, FAKE, 1 << 30, None) == -1
+    assert f(0, FAKE, None, None, 10, 10, FAKE, FAKE, 4, FAKE, FAKE, None, None, 0, None) == -3
+    assert f(0, FAKE, None, None, 10, 10, FAKE, FAKE, 4, FAKE, FAKE + 4, None, FAKE, 1 << 30, None) == -2

@@ -1,0 +1,262 @@
+"""Parity of each HIP kernel with the CPU oracle on identical seeded inputs, element by
+element, through the C ABI.  Integer work (codes, zero sets) must be bit-exact; binary32
+state is expected bit-exact too (both sides follow the same arithmetic contract) and is
+asserted within the stated tolerance of 1e-5 max relative error, with exactness reported."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2208_05631_amd as qa
+    from gpu_util import DEV, GpuState, dev, gpu_quantize_pack, host, workspace
+
+RTOL = 1e-5
+
+
+def make_grad(kind, M, d, seed):
+    rng = np.random.default_rng(seed)
+    if kind == "gauss":
+        g = rng.standard_normal((M, d)) * 1e-2 + rng.standard_normal((M, 1)) * 3e-3
+    elif kind == "laplace_sparse":
+        g = rng.laplace(0, 1e-3, (M, d)) * (rng.random((M, d)) < 0.05)
+    elif kind == "student":
+        g = rng.standard_t(3, (M, d)) * 1e-2 * (rng.random((M, d)) < 0.1)
+    elif kind == "mixed_scale":
+        g = rng.standard_normal((M, d)) * (10.0 ** rng.integers(-6, 3, (M, 1)))
+    elif kind == "zeros":
+        g = np.zeros((M, d))
+    else:
+        raise ValueError(kind)
+    return g.astype(np.float32)
+
+
+def assert_close(a, b, what):
+    assert a.shape == b.shape, what
+    if np.array_equal(a, b):
+        return
+    denom = np.maximum(np.abs(b), 1e-30)
+    err = np.max(np.abs(a.astype(np.float64) - b) / denom)
+    assert err <= RTOL, f"{what}: max rel err {err}"
+
+
+# ------------------------------------------------------------------ quantize + pack
+
+QP_CASES = [
+    # d, M, bucket
+    (1, 1, 0), (15, 2, 0), (16, 1, 64), (17, 3, 64), (1000, 4, 0), (1000, 2, 256),
+    (4096, 2, 4096), (4097, 2, 4096), (10000, 3, 1024), (10000, 3, 2048), (12289, 2, 512),
+    (70001, 2, 4096), (70001, 2, 8192), (70001, 2, 65536), (70001, 3, 0), (300000, 2, 128),
+]
+
+
+@pytest.mark.parametrize("d,M,bucket", QP_CASES)
+@pytest.mark.parametrize("kind", ["gauss", "laplace_sparse"])
+def test_quantize_pack_matches_oracle(d, M, bucket, kind):
+    g = make_grad(kind, M, d, seed=d * 7 + M)
+    oc, osc, oth = oracle.quantize_pack(g, bucket=bucket)
+    codes, scales, th, L = gpu_quantize_pack(g, bucket)
+    nb = L.n_buckets
+    assert np.array_equal(th[:, :nb], oth[:, :nb]), "thresholds differ"
+    assert np.array_equal(codes[:, :L.words], oc[:, :L.words]), "codes differ"
+    assert np.array_equal(scales[:, :nb], osc[:, :nb]), "scales differ"
+
+
+def test_quantize_pack_strides_and_untouched_padding():
+    d, M, b = 5000, 3, 1024
+    g = make_grad("gauss", M, d, 5)
+    codes, scales, th, L = gpu_quantize_pack(g, b, code_stride=400, scale_stride=9, g_stride=5008)
+    oc, osc, oth = oracle.quantize_pack(g, bucket=b, code_stride=400, scale_stride=9)
+    W, nb = L.words, L.n_buckets
+    assert np.array_equal(codes[:, :W], oc[:, :W]) and np.array_equal(scales[:, :nb], osc[:, :nb])
+    assert np.all(codes[:, W:] == 0xFFFFFFFF) and np.all(scales[:, nb:] == -7.0)   # not written
+
+
+@pytest.mark.parametrize("bucket", [0, 256, 4096, 16384])
+def test_quantize_pack_with_given_thresholds(bucket):
+    d, M = 40000, 2
+    g = make_grad("gauss", M, d, 11)
+    nb = oracle.n_buckets(d, bucket)
+    rng = np.random.default_rng(1)
+    thr = (rng.random((M, nb)) * 1e-2).astype(np.float32)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=bucket, thresholds=thr)
+    codes, scales, th, L = gpu_quantize_pack(g, bucket, thresholds=thr)
+    assert np.array_equal(codes, oc) and np.array_equal(scales[:, :nb], osc[:, :nb])
+    assert np.array_equal(th[:, :nb], thr)                                          # left as given
+
+
+@pytest.mark.parametrize("bucket", [0, 64, 4096])
+def test_quantize_degenerate_inputs(bucket):
+    d, M = 9000, 2
+    g = make_grad("zeros", M, d, 0)
+    g[1, 100] = np.nan            # poisons its bucket only: threshold NaN, codes 0, scale 0
+    g[1, 8000:] = 0.5
+    oc, osc, oth = oracle.quantize_pack(g, bucket=bucket)
+    codes, scales, th, L = gpu_quantize_pack(g, bucket)
+    nb = L.n_buckets
+    assert np.array_equal(codes, oc)
+    assert np.array_equal(scales[:, :nb], osc[:, :nb])
+    assert np.array_equal(np.isnan(th[:, :nb]), np.isnan(oth[:, :nb]))
+    assert np.array_equal(np.nan_to_num(th[:, :nb]), np.nan_to_num(oth[:, :nb]))
+    assert not codes[0].any() and not scales[0, :nb].any()
+
+
+# ------------------------------------------------------------------ aggregate
+
+@pytest.mark.parametrize("d,M,bucket", [(1, 1, 0), (1000, 4, 0), (5000, 3, 64), (70001, 6, 4096),
+                                        (70001, 64, 4096), (33333, 7, 16384), (20000, 33, 1024)])
+def test_aggregate_matches_oracle(d, M, bucket):
+    g = make_grad("mixed_scale" if M <= 7 else "gauss", M, d, seed=M + d)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
+    L = qa.Layout.make(d, M, bucket)
+    out = torch.full((d,), 9.0, dtype=torch.float32, device=DEV)
+    qa.qa_aggregate_unpack(L, dev(oc.view(np.int32)), dev(osc), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out), oracle.aggregate(oc, osc, d, bucket=bucket))
+
+
+def test_aggregate_reads_reserved_pattern_as_zero_and_ignores_tail_bits():
+    d, M = 40, 2
+    rng = np.random.default_rng(3)
+    words = rng.integers(0, 2 ** 32, (M, 3), dtype=np.uint64).astype(np.uint32)   # all 4 patterns
+    scales = np.array([[0.5], [0.25]], np.float32)
+    L = qa.Layout.make(d, M, 0)
+    out = torch.zeros(d, dtype=torch.float32, device=DEV)
+    qa.qa_aggregate_unpack(L, dev(words.view(np.int32)), dev(scales), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out), oracle.aggregate(words, scales, d, bucket=0))
+
+
+# ------------------------------------------------------------------ fused steps
+
+STEP_CASES = [
+    # d, M, bucket, requant
+    (1, 1, 0, 0), (1000, 4, 0, 0), (1000, 4, 0, 2), (4096, 8, 4096, 0), (4097, 8, 4096, 1),
+    (10000, 3, 64, 1), (10000, 5, 256, 1), (10000, 16, 1024, 1), (10000, 2, 2048, 1),
+    (70001, 64, 4096, 0), (70001, 32, 4096, 1), (70001, 6, 4096, 2), (70001, 4, 16384, 1),
+    (70001, 4, 16384, 0), (300001, 8, 4096, 0),
+]
+
+
+@pytest.mark.parametrize("d,M,bucket,requant", STEP_CASES)
+def test_fused_steps_match_oracle_over_several_steps(d, M, bucket, requant):
+    eta, lam, delta = 0.1, 2e-4, 1e-8
+    rng = np.random.default_rng(d + M)
+    x0 = (rng.standard_normal(d) * 1e-2 * (rng.random(d) < 0.5)).astype(np.float32)
+    ox, oG, oz = x0.copy(), np.zeros(d, np.float32), np.zeros(d, np.float32)
+    L = qa.Layout.make(d, M, bucket)
+    st = None
+    T = 6
+    for t in range(1, T + 1):
+        g = make_grad("gauss" if t % 2 else "laplace_sparse", M, d, seed=1000 * t + d)
+        oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
+        if st is None:
+            st = GpuState(L, oc, osc, ox, oG, oz)
+        else:
+            st.codes.copy_(dev(oc.view(np.int32)))
+            st.scales.copy_(dev(osc))
+        if t % 3 == 0:                       # QRDA steps overwrite x from (z, G, t)
+            oracle.step_qrda(oc, osc, d, bucket, ox, oG, oz, t, eta, lam, delta, requant)
+            st.qrda(t, eta, lam, delta, requant)
+        else:                                # QCMD steps keep z current
+            oracle.step_qcmd(oc, osc, d, bucket, ox, oG, oz, eta, lam, delta, requant)
+            st.qcmd(eta, lam, delta, requant, track_z=True)
+        x, G, z = st.get()
+        assert np.array_equal(x == 0, ox == 0), f"zero set differs at step {t}"
+        assert_close(G, oG, f"G step {t}")
+        assert_close(z, oz, f"z step {t}")
+        assert_close(x, ox, f"x step {t}")
+    assert np.array_equal(x, ox) and np.array_equal(G, oG) and np.array_equal(z, oz), \
+        "within tolerance but not bit-identical"
+
+
+def test_qcmd_without_z_leaves_z_alone():
+    d, M, b = 9000, 4, 4096
+    g = make_grad("gauss", M, d, 77)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=b)
+    ox, oG = np.zeros(d, np.float32), np.zeros(d, np.float32)
+    z0 = np.full(d, 3.0, np.float32)
+    st = GpuState(qa.Layout.make(d, M, b), oc, osc, ox, oG, z0)
+    oracle.step_qcmd(oc, osc, d, b, ox, oG, None, 0.1, 1e-4, 1e-8)
+    st.qcmd(0.1, 1e-4, 1e-8, 0, track_z=False)
+    x, G, z = st.get()
+    assert np.array_equal(x, ox) and np.array_equal(G, oG) and np.array_equal(z, z0)
+
+
+def test_checkpoint_resume_is_bit_identical():
+    """State is three tensors and t: T steps in one go == T/2, copy out, copy in, T/2."""
+    d, M, b = 20000, 4, 4096
+    L = qa.Layout.make(d, M, b)
+    msgs = [oracle.quantize_pack(make_grad("gauss", M, d, 300 + t), bucket=b)[:2] for t in range(6)]
+    zero = np.zeros(d, np.float32)
+
+    def run(st, ts):
+        for t in ts:
+            st.codes.copy_(dev(msgs[t - 1][0].view(np.int32)))
+            st.scales.copy_(dev(msgs[t - 1][1]))
+            st.qrda(t, 0.1, 1e-4, 1e-8) if t % 2 == 0 else st.qcmd(0.1, 1e-4, 1e-8)
+        return st.get()
+
+    full = run(GpuState(L, msgs[0][0], msgs[0][1], zero, zero, zero), range(1, 7))
+    half = run(GpuState(L, msgs[0][0], msgs[0][1], zero, zero, zero), range(1, 4))
+    resumed = run(GpuState(L, msgs[0][0], msgs[0][1], *half), range(4, 7))
+    for a, c in zip(full, resumed):
+        assert np.array_equal(a, c)
+
+
+# ------------------------------------------------------------------ local gradient
+
+def test_local_grad_dense_matches_oracle():
+    rng = np.random.default_rng(5)
+    n, d, B = 512, 1000, 64
+    A = rng.standard_normal((n, d)).astype(np.float32)
+    y = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    rows = rng.integers(0, n, B).astype(np.int32)
+    x = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    og, ol = oracle.local_grad_dense(A, y, rows, x)
+    L = qa.Layout.make(d, 1, 0)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_DENSE))
+    g = torch.full((d,), 5.0, dtype=torch.float32, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    qa.qa_local_grad(qa.QA_DENSE, dev(A), None, None, n, d, dev(y), dev(rows), B, dev(x), g, loss, ws)
+    torch.cuda.synchronize()
+    gg = host(g)
+    assert np.allclose(gg, og, rtol=1e-6, atol=1e-12)
+    assert host(loss)[0] == pytest.approx(ol, rel=1e-6)
+    print("dense grad bit-identical entries:", (gg == og).mean())
+    assert (gg == og).mean() > 0.999
+
+
+def _random_csr(rng, n, d, k):
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.int32)
+    vals = rng.standard_normal((n, k)).astype(np.float32)
+    indptr = (np.arange(n + 1) * k).astype(np.int64)
+    return vals.reshape(-1), indptr, idx.reshape(-1)
+
+
+def test_local_grad_csr_matches_oracle():
+    rng = np.random.default_rng(6)
+    n, d, k, B = 300, 5000, 40, 128          # many column collisions -> atomics are exercised
+    vals, indptr, idx = _random_csr(rng, n, d, k)
+    idx = (idx % 200).astype(np.int32)       # hot columns (duplicates inside a row are summed too)
+    y = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    rows = rng.integers(0, n, B).astype(np.int32)
+    x = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    og, ol = oracle.local_grad_csr(vals, indptr, idx, d, y, rows, x)
+    L = qa.Layout.make(d, 1, 0)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR))
+    ws.fill_(0xAB)                            # contents on entry must not matter
+    g = torch.full((d,), 5.0, dtype=torch.float32, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    for _ in range(2):                        # second call reuses the dirty workspace
+        qa.qa_local_grad(qa.QA_CSR, dev(vals), dev(indptr), dev(idx), n, d, dev(y), dev(rows), B,
+                         dev(x), g, loss, ws)
+    torch.cuda.synchronize()
+    gg = host(g)
+    assert np.array_equal(gg != 0, og != 0), "CSR indexing: non-zero set differs"
+    assert np.allclose(gg, og, rtol=1e-6, atol=1e-12)
+    assert host(loss)[0] == pytest.approx(ol, rel=1e-6)
+    assert (gg == og).mean() > 0.999
