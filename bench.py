@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused QCMD/QRDA adagrad step on one MI355X.
+
+Default workload ("largest"): d = 2^30 fp32 parameters, M = 64 workers whose gradients are
+generated on the device (Laplace(0,1e-3), 95 % exact zeros), quantized bucket by bucket (4096)
+and kept only as packed 2-bit codes + scales; steps alternate QCMD (tracking z) and QRDA on
+shared state.  The generator and the quantizer run before the timed region (the quantizer's
+own rate is reported separately); a timed step is one fused unpack+average+accumulate+update
+pass over all d coordinates.
+
+Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+
+WORKLOADS = {
+    # name: d, M, bucket, generator, lambda, bytes/coord as {kernel: B}
+    "largest": dict(d=1 << 30, M=64, bucket=4096, gen="laplace", lam=1e-6,
+                    schedule="alternate"),
+    "opt_qcmd": dict(d=10 ** 8, M=8, bucket=4096, gen="student", lam=1e-5, schedule="qcmd"),
+    "opt_qrda": dict(d=250_000_000, M=32, bucket=4096, gen="gauss", lam=1e-5, schedule="qrda"),
+    "small": dict(d=1 << 22, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
+}
+
+
+def algorithmic_bytes_per_coord(kind, M):
+    """Bytes the method itself must move per coordinate and step: 2-bit codes of M workers
+    plus the fp32 state each kernel reads and writes (scales add 4*M/4096, ignored)."""
+    return {"qcmd": 16 + M / 4, "qcmd_z": 24 + M / 4, "qrda": 20 + M / 4}[kind]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="largest", choices=sorted(WORKLOADS))
+    ap.add_argument("--code-pad-words", type=int, default=0,
+                    help="extra 32-bit words between workers' code streams")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (workers and server are slices of "
+              "one GPU's memory); --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2208_05631_amd as qa
+    from paper_2208_05631_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = WORKLOADS[args.workload]
+    d, M, bucket, lam = wl["d"], wl["M"], wl["bucket"], wl["lam"]
+    eta, delta = 0.1, 1e-8
+    W = (d + 15) // 16
+    L = qa.Layout.make(d, M, bucket, code_stride=W + args.code_pad_words)
+    gen = {"laplace": synth.grad_laplace_sparse, "student": synth.grad_student_t_sparse,
+           "gauss": synth.grad_gaussian_biased}[wl["gen"]]
+
+    # ---- inputs: generate each worker's gradient on the device, quantize, keep only codes ----
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    scales = torch.zeros((M, L.scale_stride), dtype=torch.float32, device=dev)
+    L1 = qa.Layout.make(d, 1, bucket, code_stride=L.code_stride, scale_stride=L.scale_stride)
+    gbuf = torch.empty(d, dtype=torch.float32, device=dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    q_ms = []
+    for m in range(M):
+        gen(d, m, 1, device=dev, out=gbuf)
+        ev0.record()
+        qa.qa_quantize_pack(L1, gbuf, d, codes[m], scales[m], None, 0, None)
+        ev1.record()
+        torch.cuda.synchronize()
+        q_ms.append(ev0.elapsed_time(ev1))
+    del gbuf
+    torch.cuda.empty_cache()
+    quant_ms = float(np.median(q_ms[1:] if M > 1 else q_ms))
+    nz_frac = None
+
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    G = torch.zeros(d, dtype=torch.float32, device=dev)
+    z = torch.zeros(d, dtype=torch.float32, device=dev)
+
+    def kind_of(t):
+        if wl["schedule"] == "alternate":
+            return "qcmd_z" if t % 2 == 1 else "qrda"
+        return wl["schedule"]
+
+    def step(t):
+        k = kind_of(t)
+        if k == "qrda":
+            qa.qa_step_qrda(L, codes, scales, x, G, z, t, eta, lam, delta, qa.QA_REQUANT_NONE, None)
+        else:
+            qa.qa_step_qcmd(L, codes, scales, x, G, z if k == "qcmd_z" else None, eta, lam, delta,
+                            qa.QA_REQUANT_NONE, None)
+        return k
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        step(t)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, inputs resident in HBM ----
+    events = []
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        t += 1
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()                      # the kernels run on torch's current stream
+        k = step(t)
+        e1.record()
+        events.append((k, e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+
+    per_kind = {}
+    for k, e0, e1 in events:
+        per_kind.setdefault(k, []).append(e0.elapsed_time(e1))
+    kernels = {}
+    for k, ms in per_kind.items():
+        avg = float(np.mean(ms))
+        bpc = algorithmic_bytes_per_coord(k, M)
+        kernels[k] = {"avg_ms": avg, "launches": len(ms), "bytes_per_coord": bpc,
+                      "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
+    dk = kernels[dominant]
+    nnz_x = int((x != 0).sum().item())
+
+    out = {
+        "metric": "fused QCMD/QRDA step: coordinates/s and achieved HBM GB/s (% peak), 1 MI355X",
+        "value": d * args.steps / wall,
+        "unit": "coordinates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: d={d}, M={M}, bucket={bucket}, "
+                               f"{wl['gen']} gradients as packed 2-bit codes, schedule={wl['schedule']}, "
+                               f"requant=none", "d": d, "M": M, "bucket": bucket,
+                   "code_pad_words": args.code_pad_words},
+        "roofline": {"bound": "hbm", "kernel": f"step_kernel[{dominant}]",
+                     "achieved": dk["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dk["achieved_GBps"] / HBM_PEAK_GBPS, "traffic": None},
+        "kernels": kernels,
+        "quantize_pack": {"ms_per_worker": quant_ms, "worker_coords_per_s": d / (quant_ms * 1e-3),
+                          "achieved_GBps": 4.25 * d / (quant_ms * 1e-3) / 1e9,
+                          "frac": 4.25 * d / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "nnz_x_after": nnz_x,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, one host thread, on a bounded sample ----
+    if not args.no_cpu_baseline:
+        import oracle
+        ds = min(d, 1 << 22)                      # sampled coordinates: the first ds
+        Ws, nbs = ds // 16, ds // bucket
+        c_s = codes[:, :Ws].cpu().numpy().view(np.uint32).copy()
+        s_s = scales[:, :nbs].cpu().numpy().copy()
+        ox, oG, oz = (np.zeros(ds, np.float32) for _ in range(3))
+        n_cpu = 10
+        oracle.lib()
+        c0 = time.perf_counter()
+        for tt in range(1, n_cpu + 1):
+            if kind_of(tt) == "qrda":
+                oracle.step_qrda(c_s, s_s, ds, bucket, ox, oG, oz, tt, eta, lam, delta)
+            else:
+                oracle.step_qcmd(c_s, s_s, ds, bucket, ox, oG, oz if kind_of(tt) == "qcmd_z" else None,
+                                 eta, lam, delta)
+        cpu_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": ds * n_cpu / cpu_s, "unit": "coordinates/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"first {ds} coordinates (all {M} workers), {n_cpu} steps, "
+                                         f"{cpu_s:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

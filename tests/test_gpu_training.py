@@ -1,0 +1,174 @@
+"""End-to-end parity of the whole path (local gradient -> quantize+pack -> fused step) over T
+steps of Algorithm 1, GPU through the C ABI against the CPU oracle, on the synthetic stand-ins
+for the paper's sparse linear-model experiments.
+
+Per step: packed codes and the zero set of x must be identical; x, G, z within 1e-5 max
+relative error; the objective curve (mean logistic loss on an evaluation set + lambda*|x|_1)
+within 1e-4.  Each side computes its own gradients from its own parameters."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2208_05631_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2208_05631_amd as qa
+    from gpu_util import DEV, dev, host, workspace
+
+RTOL_STATE = 1e-5
+TOL_LOSS = 1e-4
+
+
+def max_rel(a, b):
+    if np.array_equal(a, b):
+        return 0.0
+    nz = (a != 0) | (b != 0)
+    return float(np.max(np.abs(a[nz].astype(np.float64) - b[nz]) / np.maximum(np.abs(b[nz]), 1e-30)))
+
+
+class GpuTrainer:
+    def __init__(self, prob, d, M, bucket, csr):
+        self.d, self.M, self.csr = d, M, csr
+        self.L = qa.Layout.make(d, M, bucket)
+        self.gs = ((d + 3) // 4) * 4
+        if csr:
+            self.A, self.indptr, self.indices = dev(prob.vals), dev(prob.indptr), dev(prob.indices)
+            self.n = prob.n
+        else:
+            self.A, self.indptr, self.indices = dev(prob.A), None, None
+            self.n = prob.A.shape[0]
+        self.y = dev(prob.y)
+        self.x, self.G, self.z = (torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(3))
+        self.g = torch.zeros((M, self.gs), dtype=torch.float32, device=DEV)
+        self.codes = torch.zeros((M, self.L.code_stride), dtype=torch.int32, device=DEV)
+        self.scales = torch.zeros((M, self.L.scale_stride), dtype=torch.float32, device=DEV)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        op = qa.QA_OP_GRAD_CSR if csr else qa.QA_OP_GRAD_DENSE
+        self.ws_g = workspace(qa.qa_workspace_bytes(self.L, op))
+        self.ws_q = workspace(qa.qa_workspace_bytes(self.L, qa.QA_OP_QUANTIZE))
+        self.ws_s = workspace(qa.qa_workspace_bytes(self.L, qa.QA_OP_STEP))
+        self.gtmp = torch.zeros(self.gs, dtype=torch.float32, device=DEV)
+
+    def grad(self, rows_dev, B, out, loss):
+        fmt = qa.QA_CSR if self.csr else qa.QA_DENSE
+        qa.qa_local_grad(fmt, self.A, self.indptr, self.indices, self.n, self.d, self.y, rows_dev, B,
+                         self.x, out, loss, self.ws_g)
+
+    def step(self, rows, method, t, eta, lam, delta, requant):
+        rd = dev(rows)
+        for m in range(self.M):
+            self.grad(rd[m], rows.shape[1], self.g[m], None)
+        qa.qa_quantize_pack(self.L, self.g, self.gs, self.codes, self.scales, None, 0, self.ws_q)
+        if method == "qcmd":
+            qa.qa_step_qcmd(self.L, self.codes, self.scales, self.x, self.G, self.z, eta, lam, delta,
+                            requant, self.ws_s)
+        else:
+            qa.qa_step_qrda(self.L, self.codes, self.scales, self.x, self.G, self.z, t, eta, lam,
+                            delta, requant, self.ws_s)
+
+    def objective(self, eval_rows_dev, lam):
+        self.grad(eval_rows_dev, eval_rows_dev.numel(), self.gtmp, self.loss)
+        torch.cuda.synchronize()
+        x = host(self.x)
+        return float(host(self.loss)[0]) + lam * float(np.abs(x.astype(np.float64)).sum())
+
+
+class OracleTrainer:
+    def __init__(self, prob, d, M, bucket, csr):
+        self.p, self.d, self.M, self.b, self.csr = prob, d, M, bucket, csr
+        self.x, self.G, self.z = (np.zeros(d, np.float32) for _ in range(3))
+
+    def grad(self, rows):
+        p = self.p
+        if self.csr:
+            return oracle.local_grad_csr(p.vals, p.indptr, p.indices, self.d, p.y, rows, self.x)
+        return oracle.local_grad_dense(p.A, p.y, rows, self.x)
+
+    def step(self, rows, method, t, eta, lam, delta, requant):
+        g = np.stack([self.grad(rows[m])[0] for m in range(self.M)])
+        self.g = g
+        self.codes, self.scales, _ = oracle.quantize_pack(g, bucket=self.b)
+        if method == "qcmd":
+            oracle.step_qcmd(self.codes, self.scales, self.d, self.b, self.x, self.G, self.z, eta, lam,
+                             delta, requant)
+        else:
+            oracle.step_qrda(self.codes, self.scales, self.d, self.b, self.x, self.G, self.z, t, eta,
+                             lam, delta, requant)
+
+    def objective(self, eval_rows, lam):
+        _, loss = self.grad(eval_rows)
+        return float(loss) + lam * float(np.abs(self.x.astype(np.float64)).sum())
+
+
+def run_parity(prob, d, M, B, bucket, csr, method, T, eta, lam, delta, requant, seed, eval_rows):
+    gt = GpuTrainer(prob, d, M, bucket, csr)
+    ot = OracleTrainer(prob, d, M, bucket, csr)
+    n = prob.n if csr else prob.A.shape[0]
+    er_dev = dev(eval_rows)
+    worst = 0.0
+    exact_steps = 0
+    curve_g, curve_o = [], []
+    for t in range(1, T + 1):
+        rows = synth.minibatch_rows(n, M, B, t, seed)
+        gt.step(rows, method, t, eta, lam, delta, requant)
+        ot.step(rows, method, t, eta, lam, delta, requant)
+        torch.cuda.synchronize()
+        codes = host(gt.codes).view(np.uint32)
+        assert np.array_equal(codes[:, :gt.L.words], ot.codes[:, :gt.L.words]), f"codes differ, step {t}"
+        gg = host(gt.g)[:, :d]
+        assert np.array_equal(gg != 0, ot.g != 0), f"gradient sparsity pattern differs, step {t}"
+        x, G, z = host(gt.x), host(gt.G), host(gt.z)
+        assert np.array_equal(x == 0, ot.x == 0), f"zero set of x differs, step {t}"
+        e = max(max_rel(x, ot.x), max_rel(G, ot.G), max_rel(z, ot.z))
+        assert e <= RTOL_STATE, f"state rel err {e} at step {t}"
+        worst = max(worst, e)
+        exact_steps += int(e == 0.0 and np.array_equal(host(gt.scales), ot.scales))
+        if t % 5 == 0 or t == T:
+            curve_g.append(gt.objective(er_dev, lam))
+            curve_o.append(ot.objective(eval_rows, lam))
+            assert abs(curve_g[-1] - curve_o[-1]) <= TOL_LOSS, f"objective differs at step {t}"
+    assert curve_o[-1] < curve_o[0] or T < 10, "the oracle run does not descend"
+    print(f"{method}: worst state rel err {worst:.2e}; {exact_steps}/{T} steps bit-identical; "
+          f"objective {curve_o[0]:.4f} -> {curve_o[-1]:.4f}; nnz(x) = {(ot.x != 0).sum()} of {d}")
+    return ot
+
+
+@pytest.fixture(scope="module")
+def tiny_problem():
+    return synth.dense_problem(n=4096, d=1000, M=4, seed=0)
+
+
+@pytest.mark.parametrize("method", ["qcmd", "qrda"])
+@pytest.mark.parametrize("requant", [0, 2])
+def test_tiny_dense_logistic_regression(tiny_problem, method, requant):
+    """d=1000 dense N(0,1) features, n=4096, M=4 workers x batch 64, lambda=1e-3, eta=0.1,
+    delta=1e-8, T=100, one scale per message (d < 4096), seed 0."""
+    p = tiny_problem
+    ot = run_parity(p, 1000, 4, 64, 0, False, method, 100, 0.1, 1e-3, 1e-8, requant, seed=0,
+                    eval_rows=np.arange(4096, dtype=np.int32))
+    assert (ot.x == 0).any() or method == "qcmd"
+
+
+@pytest.fixture(scope="module")
+def sparse_problem():
+    full = os.environ.get("QA_FULL_CONFIG2", "0") == "1"
+    return synth.csr_problem(n=(1 << 18) if full else (1 << 15), d=1 << 20, nnz_per_row=100,
+                             zipf_s=1.1, M=16, seed=1)
+
+
+@pytest.mark.parametrize("method", ["qcmd", "qrda"])
+def test_sparse_highdim_logistic_regression(sparse_problem, method):
+    """d=2^20, CSR rows with 100 Zipf(1.1) columns, M=16 workers x batch 256, lambda=1e-4,
+    bucket 4096.  T=500 and n=2^18 with QA_FULL_CONFIG2=1, otherwise T=40 and n=2^15 (same
+    kernel shapes: the row count only changes which rows a batch can draw)."""
+    p = sparse_problem
+    T = 500 if os.environ.get("QA_FULL_CONFIG2", "0") == "1" else 40
+    rng = np.random.default_rng(99)
+    eval_rows = rng.integers(0, p.n, 4096).astype(np.int32)
+    run_parity(p, p.d, 16, 256, 4096, True, method, T, 0.1, 1e-4, 1e-8, 0, seed=1,
+               eval_rows=eval_rows)
