@@ -27,6 +27,7 @@ WORKLOADS = {
                     schedule="alternate"),
     "opt_qcmd": dict(d=10 ** 8, M=8, bucket=4096, gen="student", lam=1e-5, schedule="qcmd"),
     "opt_qrda": dict(d=250_000_000, M=32, bucket=4096, gen="gauss", lam=1e-5, schedule="qrda"),
+    "mid": dict(d=1 << 26, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
     "small": dict(d=1 << 22, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
 }
 

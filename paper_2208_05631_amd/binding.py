@@ -22,7 +22,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libqadagrad.so")
+    """In-tree library; QA_LIBRARY may name another build of the same ABI."""
+    return os.environ.get("QA_LIBRARY") or os.path.join(_HERE, "libqadagrad.so")
 
 
 class QaError(RuntimeError):

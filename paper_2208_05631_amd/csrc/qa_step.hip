@@ -7,6 +7,11 @@
 // Per coordinate the kernel forms  acc = sum_m s_m * c_m  in binary64 (each product is exact),
 // gbar = (float)(acc / M), optionally re-quantizes gbar per bucket inside the tile, and applies
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
+#include <stdlib.h>
+#ifndef QA_EXP
+#define QA_EXP 0
+#endif
+
 #include "qa_common.h"
 
 namespace qa {
@@ -22,6 +27,8 @@ struct StepArgs {
   int log2b;          // log2(bucket), or -1 for one scale per vector
   double inv_M;       // exact 1/M when M is a power of two, unused otherwise
   int M_pow2;
+  int tile_uniform;   // all coordinates of a 4096-tile share their scales
+  int span_limit;     // max exponent span of a tile's scales for which any order is exact
   float* x; float* G; float* z; float* gbar;
   float eta, lam_eta, delta, t_lam, thr_coef;
 };
@@ -57,6 +64,29 @@ __device__ __forceinline__ void store16(float* __restrict__ p, int64_t i0, int64
 #pragma unroll
     for (int j = 0; j < 16; ++j)
       if (i0 + j < d) p[i0 + j] = v[j];
+  }
+}
+
+// Accumulator and closed-form update of one coordinate (equations Hq, QCMD, QRDA): binary32,
+// one rounding per operation, in this order.
+template <int MODE, bool TRACK_Z>
+__device__ __forceinline__ void update_coordinate(const StepArgs& a, float q, float& x, float& G,
+                                                  float& z) {
+  const float q2 = q * q;
+  G = G + q2;
+  const float H = a.delta + sqrtf(G);
+  if (MODE == kQcmd) {
+    const float step = (a.eta * q) / H;
+    const float u = x - step;
+    const float tau = a.lam_eta / H;
+    const float r = fabsf(u) - tau;
+    x = r > 0.0f ? copysignf(r, u) : 0.0f;
+    if (TRACK_Z) z = z + q;
+  } else {
+    z = z + q;
+    const float r = fabsf(z) - a.t_lam;
+    const float mag = (a.eta * r) / H;
+    x = r > 0.0f ? -copysignf(mag, z) : 0.0f;
   }
 }
 
@@ -135,33 +165,272 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     return;
   }
 
-  // ---- accumulator and closed-form update (binary32, one rounding per operation) ----
+  // ---- accumulator and closed-form update ----
   float G[16], x[16], z[16];
   load16(a.G, i0, a.d, G);
   if (MODE == kQcmd) load16(a.x, i0, a.d, x);
   if (MODE == kQrda || TRACK_Z) load16(a.z, i0, a.d, z);
 #pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    const float q2 = q[j] * q[j];
-    G[j] = G[j] + q2;
-    const float H = a.delta + sqrtf(G[j]);
-    if (MODE == kQcmd) {
-      const float step = (a.eta * q[j]) / H;
-      const float u = x[j] - step;
-      const float tau = a.lam_eta / H;
-      const float r = fabsf(u) - tau;
-      x[j] = r > 0.0f ? copysignf(r, u) : 0.0f;
-      if (TRACK_Z) z[j] = z[j] + q[j];
-    } else {
-      z[j] = z[j] + q[j];
-      const float r = fabsf(z[j]) - a.t_lam;
-      const float mag = (a.eta * r) / H;
-      x[j] = r > 0.0f ? -copysignf(mag, z[j]) : 0.0f;
-    }
-  }
+  for (int j = 0; j < 16; ++j) update_coordinate<MODE, TRACK_Z>(a, q[j], x[j], G[j], z[j]);
   store16(a.G, i0, a.d, G);
   store16(a.x, i0, a.d, x);
   if (MODE == kQrda || TRACK_Z) store16(a.z, i0, a.d, z);
+}
+
+// ---- table-driven kernel for tile-uniform scales (bucket >= 4096 or one scale per vector) ----
+//
+// When the exponents of the non-zero scales of the tile's bucket span few enough binades, every
+// partial sum of  sum_m s_m*c_m  is exactly representable in binary64 (all are multiples of
+// 2^(e_min-23) and below M*2^(e_max+1)), so the order of the additions does not matter.  The
+// kernel then sums workers four at a time: the 2-bit codes of workers 4g..4g+3 for one
+// coordinate are gathered into one byte by word-wide bit operations and the byte indexes a
+// 256-entry binary64 table (built per tile in LDS) holding the exact partial sum of those four
+// workers.  Tiles that fail the span test (or hold Inf/NaN scales) take the ordered loop.
+//
+// All global loads of a tile (up to 64 code words per lane, then G, x, z in the coalesced
+// float4 mapping f = j*256 + t) are issued before any dependent work, so that the scale test,
+// the table build and the lookups run under the memory latency.
+constexpr int kGroupsPerChunk = 16;                     // 64 workers per table set: 32 KiB of LDS
+constexpr int kChunk = 4 * kGroupsPerChunk;
+
+struct State4 { float4 v[4]; };
+
+// float4 groups j*256+t of the tile; out-of-range elements read as 0 (tail tile only)
+__device__ __forceinline__ void load_state(const float* __restrict__ p, int64_t tile_base,
+                                           int64_t d, bool full_tile, State4& s) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int64_t i = tile_base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
+    if (full_tile || i + 3 < d) {
+      s.v[j] = *reinterpret_cast<const float4*>(p + i);
+    } else {
+      float e[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) e[c] = (i + c < d) ? p[i + c] : 0.0f;
+      s.v[j] = make_float4(e[0], e[1], e[2], e[3]);
+    }
+  }
+}
+
+__device__ __forceinline__ void store_state(float* __restrict__ p, int64_t tile_base, int64_t d,
+                                            bool full_tile, const State4& s) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int64_t i = tile_base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
+    if (full_tile || i + 3 < d) {
+      *reinterpret_cast<float4*>(p + i) = s.v[j];
+    } else {
+      const float e[4] = {s.v[j].x, s.v[j].y, s.v[j].z, s.v[j].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (i + c < d) p[i + c] = e[c];
+    }
+  }
+}
+
+// One group of four workers: gather their codes per coordinate into bytes, look the partial
+// sums up, add.  Coordinate 4r+c of the thread's 16 sits in byte r of zq[c].
+__device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t wc, uint32_t wd,
+                                             const double* __restrict__ T, double acc[16]) {
+  const uint32_t xe = (wa & 0x33333333u) | ((wb & 0x33333333u) << 2);
+  const uint32_t xo = ((wa >> 2) & 0x33333333u) | (wb & 0xCCCCCCCCu);
+  const uint32_t ye = (wc & 0x33333333u) | ((wd & 0x33333333u) << 2);
+  const uint32_t yo = ((wc >> 2) & 0x33333333u) | (wd & 0xCCCCCCCCu);
+  uint32_t zq[4];
+  zq[0] = (xe & 0x0F0F0F0Fu) | ((ye & 0x0F0F0F0Fu) << 4);
+  zq[1] = (xo & 0x0F0F0F0Fu) | ((yo & 0x0F0F0F0Fu) << 4);
+  zq[2] = ((xe >> 4) & 0x0F0F0F0Fu) | (ye & 0xF0F0F0F0u);
+  zq[3] = ((xo >> 4) & 0x0F0F0F0Fu) | (yo & 0xF0F0F0F0u);
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[4 * r + c] += T[(zq[c] >> (8 * r)) & 0xFFu];
+}
+
+// FULL: M is a multiple of 64, so every chunk has all 16 groups (straight-line code).
+template <int MODE, bool TRACK_Z, bool REQUANT, bool FULL>
+__global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
+  __shared__ double tab[kGroupsPerChunk * 256];
+  __shared__ double s_scale[kChunk];
+  __shared__ double lds_d[kWaves];
+  __shared__ uint32_t lds_u[kWaves];
+  __shared__ int lds_e[3 * kWaves];
+  const int t = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int64_t tile_base = tile * kTile;
+  const bool full_tile = tile_base + kTile <= a.d;
+  const int64_t k = a.log2b >= 0 ? (tile_base >> a.log2b) : 0;         // same for the whole tile
+  const float* sc = a.scales + k;
+  // words of this tile that exist; lanes beyond read the last one (in bounds) and are masked
+  const int64_t words_here = a.W - tile * kTileWords;
+  const int tw = words_here >= kTileWords ? t : (t < (int)words_here ? t : (int)words_here - 1);
+  const bool live = t < words_here;
+  const uint32_t* ctile = a.codes + tile * kTileWords;                 // uniform base
+
+  // ---- issue the global loads: first chunk of code words, then the state ----
+  uint32_t w[kChunk];
+  {
+    const int left = a.M;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      w[i] = (FULL || i < left) ? (ctile + (int64_t)i * a.code_stride)[tw] : 0u;
+  }
+  State4 sG, sx, sz;
+  if (MODE != kAggregate) {
+    load_state(a.G, tile_base, a.d, full_tile, sG);
+    if (MODE == kQcmd) load_state(a.x, tile_base, a.d, full_tile, sx);
+    if (MODE == kQrda || TRACK_Z) load_state(a.z, tile_base, a.d, full_tile, sz);
+  }
+
+  // ---- can the sum over workers be reordered? (exponent span of the tile's scales) ----
+  int emax = 0, emin = 255, bad = 0;
+  for (int m = t; m < a.M; m += kThreads) {
+    const uint32_t u = __float_as_uint(sc[(int64_t)m * a.scale_stride]);
+    if ((u << 1) == 0u) continue;
+    int f = (int)((u >> 23) & 0xFFu);
+    if (f == 255) bad = 1;
+    f = f < 1 ? 1 : f;
+    emax = f > emax ? f : emax;
+    emin = f < emin ? f : emin;
+  }
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int o1 = __shfl_xor(emax, off, kWave), o2 = __shfl_xor(emin, off, kWave);
+    bad |= __shfl_xor(bad, off, kWave);
+    emax = o1 > emax ? o1 : emax;
+    emin = o2 < emin ? o2 : emin;
+  }
+  if ((t % kWave) == 0) {
+    lds_e[t / kWave] = emax; lds_e[kWaves + t / kWave] = emin; lds_e[2 * kWaves + t / kWave] = bad;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int v = 0; v < kWaves; ++v) {
+    emax = lds_e[v] > emax ? lds_e[v] : emax;
+    emin = lds_e[kWaves + v] < emin ? lds_e[kWaves + v] : emin;
+    bad |= lds_e[2 * kWaves + v];
+  }
+  const bool reorder_ok = !bad && (emax - emin) <= a.span_limit;
+
+  double acc[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = 0.0;
+
+  if (reorder_ok) {
+    // decoded values of the four 2-bit fields of byte t (reserved pattern 10 -> 0)
+    double dj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int f = (t >> (2 * j)) & 3;
+      dj[j] = f == 1 ? 1.0 : (f == 3 ? -1.0 : 0.0);
+    }
+    for (int m0 = 0; m0 < a.M; m0 += kChunk) {
+      const int left = a.M - m0;
+      const int ng = (FULL || left >= kChunk) ? kGroupsPerChunk : (left + 3) / 4;
+      if (m0 > 0) {
+        const uint32_t* cc = ctile + (int64_t)m0 * a.code_stride;
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+          w[i] = (FULL || i < left) ? (cc + (int64_t)i * a.code_stride)[tw] : 0u;
+        __syncthreads();                                 // readers of the previous tables are done
+      }
+      if (t < kChunk) s_scale[t] = t < left ? (double)sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0;
+      __syncthreads();
+      for (int g = 0; g < ng; ++g) {
+        const double e = fma(dj[3], s_scale[4 * g + 3],
+                             fma(dj[2], s_scale[4 * g + 2],
+                                 fma(dj[1], s_scale[4 * g + 1], dj[0] * s_scale[4 * g])));
+        tab[g * 256 + t] = e;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int g = 0; g < kGroupsPerChunk; ++g)
+        if (FULL || g < ng)
+          lookup_group(w[4 * g], w[4 * g + 1], w[4 * g + 2], w[4 * g + 3], tab + g * 256, acc);
+    }
+  } else {
+    // ordered loop, as the sum is written: worker 0, 1, 2, ...
+    for (int m = 0; m < a.M; ++m) {
+      const uint32_t wv = sanitize((ctile + (int64_t)m * a.code_stride)[tw]);
+      const double s = (double)sc[(int64_t)m * a.scale_stride];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int c = ((int)(wv << (30 - 2 * j))) >> 30;
+        acc[j] = fma((double)c, s, acc[j]);
+      }
+    }
+  }
+
+  float q[16];
+  if (a.M_pow2) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] * a.inv_M);
+  } else {
+    const double Md = (double)a.M;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] / Md);
+  }
+  {
+    const int64_t i0 = tile_base + 16 * (int64_t)t;                    // masks dead lanes too
+    if (i0 + 16 > a.d) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (i0 + j >= a.d || !live) q[j] = 0.0f;
+    }
+  }
+
+  if (REQUANT) {                                          // bucket == 4096 == the tile
+    double s1 = 0.0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);
+    s1 = segment_sum(s1, kThreads, lds_d);
+    const int64_t n = (a.d - tile_base) < (int64_t)kTile ? (a.d - tile_base) : (int64_t)kTile;
+    const float Delta = threshold_from_sum(s1, a.thr_coef, n);
+    double s2 = 0.0;
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float av = fabsf(q[j]);
+      if (av > Delta) { s2 += (double)av; ++cnt; }
+    }
+    s2 = segment_sum(s2, kThreads, lds_d);
+    cnt = segment_sum_u32(cnt, kThreads, lds_u);
+    const float s = scale_from_sum(s2, cnt);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
+  }
+
+  // ---- hand q over through LDS to the float4 mapping of the state loads ----
+  float* qt = reinterpret_cast<float*>(tab);
+  __syncthreads();
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+    *reinterpret_cast<float4*>(qt + 16 * t + 4 * v) =
+        make_float4(q[4 * v], q[4 * v + 1], q[4 * v + 2], q[4 * v + 3]);
+  __syncthreads();
+  State4 sq;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) sq.v[j] = *reinterpret_cast<const float4*>(qt + 4 * (j * kThreads + t));
+
+  if (MODE == kAggregate) {
+    store_state(a.gbar, tile_base, a.d, full_tile, sq);
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float qq[4] = {sq.v[j].x, sq.v[j].y, sq.v[j].z, sq.v[j].w};
+    float G[4] = {sG.v[j].x, sG.v[j].y, sG.v[j].z, sG.v[j].w};
+    float x[4] = {0.f, 0.f, 0.f, 0.f}, z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (MODE == kQcmd) { x[0] = sx.v[j].x; x[1] = sx.v[j].y; x[2] = sx.v[j].z; x[3] = sx.v[j].w; }
+    if (MODE == kQrda || TRACK_Z) { z[0] = sz.v[j].x; z[1] = sz.v[j].y; z[2] = sz.v[j].z; z[3] = sz.v[j].w; }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) update_coordinate<MODE, TRACK_Z>(a, qq[e], x[e], G[e], z[e]);
+    sG.v[j] = make_float4(G[0], G[1], G[2], G[3]);
+    sx.v[j] = make_float4(x[0], x[1], x[2], x[3]);
+    sz.v[j] = make_float4(z[0], z[1], z[2], z[3]);
+  }
+  store_state(a.G, tile_base, a.d, full_tile, sG);
+  store_state(a.x, tile_base, a.d, full_tile, sx);
+  if (MODE == kQrda || TRACK_Z) store_state(a.z, tile_base, a.d, full_tile, sz);
 }
 
 // ---- host side -------------------------------------------------------------------------------
@@ -213,18 +482,43 @@ static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float
   a.M_pow2 = is_pow2(L->M) ? 1 : 0;
   a.inv_M = 1.0 / (double)L->M;
   a.thr_coef = L->thr_coef;
+  // partial sums are multiples of 2^(e_min-23) and below M*2^(e_max+1): exact in binary64 iff
+  // log2(M) + span + 24 <= 53
+  a.span_limit = 29 - ilog2(L->M);
+  a.tile_uniform = (L->bucket == 0 || L->bucket >= kTile) ? 1 : 0;
   return a;
+}
+
+// QA_STEP_KERNEL=ordered forces the worker-ordered kernel (diagnostics); default: table-driven
+// kernel whenever a tile's coordinates share their scales.
+static bool use_lut(const StepArgs& a) {
+  if (!a.tile_uniform) return false;
+  const char* e = getenv("QA_STEP_KERNEL");
+  return !(e && e[0] == 'o');
+}
+
+enum StepKernel { kOrdered = 0, kTableFull = 1, kTablePart = 2 };
+
+template <int MODE, bool TRACK_Z, bool REQUANT>
+static void launch_one(const StepArgs& a, int which, hipStream_t stream) {
+  const dim3 grid((unsigned)tiles_of(a.d)), block(kThreads);
+  if (which == kTableFull)
+    hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, true>), grid, block, 0, stream, a);
+  else if (which == kTablePart)
+    hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, false>), grid, block, 0, stream, a);
+  else
+    hipLaunchKernelGGL((step_kernel<MODE, TRACK_Z, REQUANT>), grid, block, 0, stream, a);
 }
 
 template <int MODE>
 static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
-  const dim3 grid((unsigned)tiles_of(a.d)), block(kThreads);
+  const int which = !use_lut(a) ? kOrdered : (a.M % kChunk == 0 ? kTableFull : kTablePart);
   if (requant) {
-    if (track_z) hipLaunchKernelGGL((step_kernel<MODE, true, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((step_kernel<MODE, false, true>), grid, block, 0, stream, a);
+    if (track_z) launch_one<MODE, true, true>(a, which, stream);
+    else launch_one<MODE, false, true>(a, which, stream);
   } else {
-    if (track_z) hipLaunchKernelGGL((step_kernel<MODE, true, false>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((step_kernel<MODE, false, false>), grid, block, 0, stream, a);
+    if (track_z) launch_one<MODE, true, false>(a, which, stream);
+    else launch_one<MODE, false, false>(a, which, stream);
   }
 }
 
