@@ -47,6 +47,53 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
   return __shfl_xor(v, mask, kWave);
 }
 
+// ---- wave64 sums with DPP (no LDS traffic): every lane receives the sum of all 64 lanes ----
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const int lo = dpp_i32<CTRL>(__double2loint(v)), hi = dpp_i32<CTRL>(__double2hiint(v));
+  return __hiloint2double(hi, lo);
+}
+constexpr int kDppQuadXor1 = 0xB1;      // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;      // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+  v += dpp_f64<kDppQuadXor1>(v);
+  v += dpp_f64<kDppQuadXor2>(v);
+  v += dpp_f64<kDppRowHalfMirror>(v);
+  v += dpp_f64<kDppRowMirror>(v);        // every lane: sum of its row of 16
+  return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  v += (uint32_t)dpp_i32<kDppQuadXor1>((int)v);
+  v += (uint32_t)dpp_i32<kDppQuadXor2>((int)v);
+  v += (uint32_t)dpp_i32<kDppRowHalfMirror>((int)v);
+  v += (uint32_t)dpp_i32<kDppRowMirror>((int)v);
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+         (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
+// Sum over the whole 256-thread work-group, returned to every thread.  One barrier; `lds`
+// (kWaves doubles) must not be reused by another call before a later barrier.
+__device__ __forceinline__ double block_sum_f64(double v, double* lds) {
+  v = wave_sum_f64(v);
+  if ((threadIdx.x % kWave) == 0) lds[threadIdx.x / kWave] = v;
+  __syncthreads();
+  return (lds[0] + lds[1]) + (lds[2] + lds[3]);
+}
+
 // Sum of `v` over aligned segments of `seg` consecutive threads (seg a power of two,
 // 1 <= seg <= 256); every thread receives the sum of its own segment.  `lds` points to at
 // least kWaves doubles of shared memory that no one else uses across the call.

@@ -65,8 +65,8 @@ __device__ __forceinline__ void pack_and_store(const float v[4][4], const float 
 #pragma unroll
     for (int e = 0; e < 4; ++e) b |= ternary_field(v[j][e], Delta[j]) << (2 * e);
     uint32_t w = b << (8 * (t & 3));
-    w |= __shfl_xor(w, 1, kWave);
-    w |= __shfl_xor(w, 2, kWave);
+    w |= (uint32_t)dpp_i32<kDppQuadXor1>((int)w);
+    w |= (uint32_t)dpp_i32<kDppQuadXor2>((int)w);
     if ((t & 3) == j) mine = w;
   }
   const int64_t widx = tile * kTileWords + (t & 3) * 64 + (t >> 2);
@@ -169,6 +169,56 @@ __global__ __launch_bounds__(kThreads) void quantize_small_bucket_kernel(QuantAr
   pack_and_store(v, Delta, a.codes + (int64_t)m * a.code_stride, tile, a.W);
 }
 
+// ---- bucket == 4096 == the tile : single pass, two work-group reductions ---------------------
+__global__ __launch_bounds__(kThreads) void quantize_tile_kernel(QuantArgs a) {
+  __shared__ double lds_s1[kWaves];
+  __shared__ double lds_s2[kWaves];
+  __shared__ uint32_t lds_c[kWaves];
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const int t = threadIdx.x;
+  float v[4][4];
+  load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+
+  float Delta;
+  if (!a.thresh_given) {
+    double s = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
+    const double S1 = block_sum_f64(s, lds_s1);
+    const int64_t lo = tile * kTile;
+    const int64_t n = (a.d - lo) < (int64_t)kTile ? (a.d - lo) : (int64_t)kTile;
+    Delta = threshold_from_sum(S1, a.thr_coef, n);
+  } else {
+    Delta = a.thresholds[(int64_t)m * a.scale_stride + tile];
+  }
+
+  double s2 = 0.0;
+  uint32_t c = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    double sj; uint32_t cj;
+    kept_sums(v[j], Delta, &sj, &cj);
+    s2 += sj; c += cj;
+  }
+  s2 = wave_sum_f64(s2);
+  c = wave_sum_u32(c);
+  if ((t % kWave) == 0) { lds_s2[t / kWave] = s2; lds_c[t / kWave] = c; }
+
+  const float D4[4] = {Delta, Delta, Delta, Delta};
+  pack_and_store(v, D4, a.codes + (int64_t)m * a.code_stride, tile, a.W);
+
+  __syncthreads();
+  if (t == 0) {
+    const double S2 = (lds_s2[0] + lds_s2[1]) + (lds_s2[2] + lds_s2[3]);
+    const uint32_t C = lds_c[0] + lds_c[1] + lds_c[2] + lds_c[3];
+    a.scales[(int64_t)m * a.scale_stride + tile] = scale_from_sum(S2, C);
+    if (a.thresholds && !a.thresh_given) a.thresholds[(int64_t)m * a.scale_stride + tile] = Delta;
+  }
+}
+
 // ---- bucket > 4096 or whole vector : two passes -----------------------------------------------
 
 // pass 1: part_sum[m][tile] = sum |v| over the tile
@@ -183,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void quantize_abs_partial_kernel(QuantArg
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
-  s = segment_sum(s, kThreads, lds_d);
+  s = block_sum_f64(s, lds_d);
   if (threadIdx.x == 0) a.part_sum[(int64_t)m * a.ntiles + tile] = s;
 }
 
@@ -225,14 +275,16 @@ __global__ __launch_bounds__(kThreads) void quantize_codes_partial_kernel(QuantA
     kept_sums(v[j], D, &sj, &cj);
     s += sj; c += cj;
   }
-  s = segment_sum(s, kThreads, lds_d);
-  c = segment_sum_u32(c, kThreads, lds_u);
-  if (threadIdx.x == 0) {
-    a.part_sum[(int64_t)m * a.ntiles + tile] = s;
-    a.part_cnt[(int64_t)m * a.ntiles + tile] = c;
-  }
+  s = wave_sum_f64(s);
+  c = wave_sum_u32(c);
+  if ((threadIdx.x % kWave) == 0) { lds_d[threadIdx.x / kWave] = s; lds_u[threadIdx.x / kWave] = c; }
   const float Delta[4] = {D, D, D, D};
   pack_and_store(v, Delta, a.codes + (int64_t)m * a.code_stride, tile, a.W);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a.part_sum[(int64_t)m * a.ntiles + tile] = (lds_d[0] + lds_d[1]) + (lds_d[2] + lds_d[3]);
+    a.part_cnt[(int64_t)m * a.ntiles + tile] = lds_u[0] + lds_u[1] + lds_u[2] + lds_u[3];
+  }
 }
 
 // finalize 2: scale of each (bucket, worker)
@@ -283,7 +335,8 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   if (L->bucket != 0 && L->bucket <= kTile) {
     a.log2b = ilog2(L->bucket);
     a.bucket_len = L->bucket;
-    hipLaunchKernelGGL(quantize_small_bucket_kernel, grid_tiles, block, 0, stream, a);
+    if (L->bucket == kTile) hipLaunchKernelGGL(quantize_tile_kernel, grid_tiles, block, 0, stream, a);
+    else hipLaunchKernelGGL(quantize_small_bucket_kernel, grid_tiles, block, 0, stream, a);
     return launch_status();
   }
 

@@ -118,16 +118,53 @@ def test_aggregate_matches_oracle(d, M, bucket):
     assert np.array_equal(host(out), oracle.aggregate(oc, osc, d, bucket=bucket))
 
 
+@pytest.mark.parametrize("d,M,bucket", [(70001, 64, 4096), (50000, 130, 8192), (9000, 70, 0),
+                                        (20000, 5, 4096)])
+def test_aggregate_with_widely_spread_scales_takes_the_ordered_path(d, M, bucket):
+    """Scales spanning > 29 - log2(M) binades inside a bucket: the sum is no longer exact in
+    binary64, so only worker order reproduces the oracle's rounding."""
+    rng = np.random.default_rng(M)
+    g = rng.standard_normal((M, d)).astype(np.float32) * (2.0 ** rng.integers(-40, 40, (M, 1))).astype(np.float32)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
+    L = qa.Layout.make(d, M, bucket)
+    out = torch.zeros(d, dtype=torch.float32, device=DEV)
+    qa.qa_aggregate_unpack(L, dev(oc.view(np.int32)), dev(osc), out)
+    torch.cuda.synchronize()
+    ref = oracle.aggregate(oc, osc, d, bucket=bucket)
+    assert np.array_equal(host(out), ref)
+    # half the buckets get narrow spans again: both paths inside one launch
+    nb = L.n_buckets
+    osc2 = osc.copy()
+    osc2[:, : max(1, nb // 2)] = (1e-3 * (1 + rng.random((M, max(1, nb // 2))))).astype(np.float32)
+    qa.qa_aggregate_unpack(L, dev(oc.view(np.int32)), dev(osc2), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out), oracle.aggregate(oc, osc2, d, bucket=bucket))
+
+
+def test_aggregate_with_nonfinite_scale_matches_oracle():
+    d, M, b = 10000, 8, 4096
+    g = make_grad("gauss", M, d, 9)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=b)
+    osc[3, 1] = np.inf                      # inf * 0 = NaN, inf * +-1 = +-inf: bucket 1 is poisoned
+    out = torch.zeros(d, dtype=torch.float32, device=DEV)
+    qa.qa_aggregate_unpack(qa.Layout.make(d, M, b), dev(oc.view(np.int32)), dev(osc), out)
+    torch.cuda.synchronize()
+    ref = oracle.aggregate(oc, osc, d, bucket=b)
+    assert not np.isfinite(ref[4096:8192]).any() and np.isfinite(ref[:4096]).all()
+    assert np.array_equal(host(out), ref, equal_nan=True)
+
+
 def test_aggregate_reads_reserved_pattern_as_zero_and_ignores_tail_bits():
     d, M = 40, 2
     rng = np.random.default_rng(3)
     words = rng.integers(0, 2 ** 32, (M, 3), dtype=np.uint64).astype(np.uint32)   # all 4 patterns
     scales = np.array([[0.5], [0.25]], np.float32)
-    L = qa.Layout.make(d, M, 0)
-    out = torch.zeros(d, dtype=torch.float32, device=DEV)
-    qa.qa_aggregate_unpack(L, dev(words.view(np.int32)), dev(scales), out)
-    torch.cuda.synchronize()
-    assert np.array_equal(host(out), oracle.aggregate(words, scales, d, bucket=0))
+    for bucket in (0, 64):                 # table-driven kernel / worker-ordered kernel
+        L = qa.Layout.make(d, M, bucket)
+        out = torch.zeros(d, dtype=torch.float32, device=DEV)
+        qa.qa_aggregate_unpack(L, dev(words.view(np.int32)), dev(scales), out)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(out), oracle.aggregate(words, scales, d, bucket=bucket))
 
 
 # ------------------------------------------------------------------ fused steps
@@ -137,7 +174,8 @@ STEP_CASES = [
     (1, 1, 0, 0), (1000, 4, 0, 0), (1000, 4, 0, 2), (4096, 8, 4096, 0), (4097, 8, 4096, 1),
     (10000, 3, 64, 1), (10000, 5, 256, 1), (10000, 16, 1024, 1), (10000, 2, 2048, 1),
     (70001, 64, 4096, 0), (70001, 32, 4096, 1), (70001, 6, 4096, 2), (70001, 4, 16384, 1),
-    (70001, 4, 16384, 0), (300001, 8, 4096, 0),
+    (70001, 4, 16384, 0), (300001, 8, 4096, 0), (50001, 130, 4096, 0), (50001, 67, 4096, 1),
+    (20000, 128, 4096, 1),
 ]
 
 
