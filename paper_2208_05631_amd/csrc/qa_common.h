@@ -50,7 +50,7 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
 // ---- wave64 sums with DPP (no LDS traffic): every lane receives the sum of all 64 lanes ----
 template <int CTRL>
 __device__ __forceinline__ int dpp_i32(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);   // every lane has a source
 }
 template <int CTRL>
 __device__ __forceinline__ double dpp_f64(double v) {

@@ -170,6 +170,31 @@ __global__ __launch_bounds__(kThreads) void quantize_small_bucket_kernel(QuantAr
 }
 
 // ---- bucket == 4096 == the tile : single pass, two work-group reductions ---------------------
+
+// Kept-magnitude sum, kept count (wave-wide, from the compare masks on the scalar unit) and the
+// 2-bit fields of one float4 group.  For Delta >= 0 (always, unless a caller hands in a negative
+// threshold)  v > Delta or v < -Delta  <=>  |v| > Delta, and the field is 01 | sign << 1.
+__device__ __forceinline__ uint32_t quantize4(const float v[4], float Delta, bool plain_compare,
+                                              double& s2, uint32_t& wave_cnt) {
+  uint32_t b = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float av = fabsf(v[e]);
+    const bool keep = av > Delta;
+    wave_cnt += (uint32_t)__popcll(__ballot(keep));
+    s2 += (double)(keep ? av : 0.0f);
+    uint32_t f;
+    if (plain_compare) {
+      f = ternary_field(v[e], Delta);
+    } else {
+      const uint32_t pat = 1u | ((__float_as_uint(v[e]) >> 30) & 2u);
+      f = keep ? pat : 0u;
+    }
+    b |= f << (2 * e);
+  }
+  return b;
+}
+
 __global__ __launch_bounds__(kThreads) void quantize_tile_kernel(QuantArgs a) {
   __shared__ double lds_s1[kWaves];
   __shared__ double lds_s2[kWaves];
@@ -177,39 +202,52 @@ __global__ __launch_bounds__(kThreads) void quantize_tile_kernel(QuantArgs a) {
   const int64_t tile = blockIdx.x;
   const int m = blockIdx.y;
   const int t = threadIdx.x;
+  const int64_t lo = tile * kTile;
+  const float* g = a.g + (int64_t)m * a.g_stride;
   float v[4][4];
-  load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+  if (lo + kTile <= a.d) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 q = *reinterpret_cast<const float4*>(g + lo + (j * kThreads + t) * 4);
+      v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    }
+  } else {
+    load_tile(g, a.d, tile, v);
+  }
 
   float Delta;
   if (!a.thresh_given) {
-    double s = 0.0;
+    double sj[4];                                        // four independent chains
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 4; ++j) {
+      sj[j] = (double)fabsf(v[j][0]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
-    const double S1 = block_sum_f64(s, lds_s1);
-    const int64_t lo = tile * kTile;
+      for (int e = 1; e < 4; ++e) sj[j] += (double)fabsf(v[j][e]);
+    }
+    const double S1 = block_sum_f64((sj[0] + sj[1]) + (sj[2] + sj[3]), lds_s1);
     const int64_t n = (a.d - lo) < (int64_t)kTile ? (a.d - lo) : (int64_t)kTile;
     Delta = threshold_from_sum(S1, a.thr_coef, n);
   } else {
     Delta = a.thresholds[(int64_t)m * a.scale_stride + tile];
   }
+  const bool plain_compare = Delta < 0.0f;               // uniform; only with a given threshold
 
-  double s2 = 0.0;
-  uint32_t c = 0;
+  double s2j[4] = {0.0, 0.0, 0.0, 0.0};
+  uint32_t wave_cnt = 0;
+  uint32_t mine = 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    double sj; uint32_t cj;
-    kept_sums(v[j], Delta, &sj, &cj);
-    s2 += sj; c += cj;
+    const uint32_t b = quantize4(v[j], Delta, plain_compare, s2j[j], wave_cnt);
+    uint32_t w = b << (8 * (t & 3));
+    w |= (uint32_t)dpp_i32<kDppQuadXor1>((int)w);
+    w |= (uint32_t)dpp_i32<kDppQuadXor2>((int)w);
+    if ((t & 3) == j) mine = w;
   }
-  s2 = wave_sum_f64(s2);
-  c = wave_sum_u32(c);
-  if ((t % kWave) == 0) { lds_s2[t / kWave] = s2; lds_c[t / kWave] = c; }
+  const int64_t widx = tile * kTileWords + (t & 3) * 64 + (t >> 2);
+  if (widx < a.W) (a.codes + (int64_t)m * a.code_stride)[widx] = mine;
 
-  const float D4[4] = {Delta, Delta, Delta, Delta};
-  pack_and_store(v, D4, a.codes + (int64_t)m * a.code_stride, tile, a.W);
-
+  const double s2 = wave_sum_f64((s2j[0] + s2j[1]) + (s2j[2] + s2j[3]));
+  if ((t % kWave) == 0) { lds_s2[t / kWave] = s2; lds_c[t / kWave] = wave_cnt; }
   __syncthreads();
   if (t == 0) {
     const double S2 = (lds_s2[0] + lds_s2[1]) + (lds_s2[2] + lds_s2[3]);
