@@ -190,10 +190,20 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 // All global loads of a tile (up to 64 code words per lane, then G, x, z in the coalesced
 // float4 mapping f = j*256 + t) are issued before any dependent work, so that the scale test,
 // the table build and the lookups run under the memory latency.
-constexpr int kGroupsPerChunk = 16;                     // 64 workers per table set: 32 KiB of LDS
-constexpr int kChunk = 4 * kGroupsPerChunk;
+constexpr int kMaxGroups = 16;                          // 64 workers per table set: 32 KiB of LDS
 
 struct State4 { float4 v[4]; };
+
+// Codes are read exactly once and the state is not touched again before the next step:
+// both bypass the caches' retention (nontemporal), which measurably raises HBM throughput here.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t stream_load(const uint32_t* p) {
+  return __builtin_nontemporal_load(p);
+}
+__device__ __forceinline__ void stream_store4(float* p, const float4& v) {
+  floatx4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<floatx4*>(p));
+}
 
 // float4 groups j*256+t of the tile; out-of-range elements read as 0 (tail tile only)
 __device__ __forceinline__ void load_state(const float* __restrict__ p, int64_t tile_base,
@@ -218,7 +228,7 @@ __device__ __forceinline__ void store_state(float* __restrict__ p, int64_t tile_
   for (int j = 0; j < 4; ++j) {
     const int64_t i = tile_base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
     if (full_tile || i + 3 < d) {
-      *reinterpret_cast<float4*>(p + i) = s.v[j];
+      stream_store4(p + i, s.v[j]);
     } else {
       const float e[4] = {s.v[j].x, s.v[j].y, s.v[j].z, s.v[j].w};
 #pragma unroll
@@ -251,10 +261,16 @@ __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t 
     for (int c = 0; c < 4; ++c) acc[4 * r + c] += T[(zq[c] >> (8 * r)) & 0xFFu];
 }
 
-// FULL: M is a multiple of 64, so every chunk has all 16 groups (straight-line code).
-template <int MODE, bool TRACK_Z, bool REQUANT, bool FULL>
+// NGT > 0: M is a multiple of 4*NGT, workers are taken 4*NGT at a time and every chunk has all
+// NGT groups (straight-line code, registers and LDS sized for NGT).  NGT == 0: any M, chunks of
+// 64 workers with run-time guards.
+template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
 __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
-  __shared__ double tab[kGroupsPerChunk * 256];
+  constexpr bool FULL = NGT > 0;
+  constexpr int kGroupsPerChunk = FULL ? NGT : kMaxGroups;
+  constexpr int kChunk = 4 * kGroupsPerChunk;
+  constexpr int kTabEntries = kGroupsPerChunk * 256 > kTile / 2 ? kGroupsPerChunk * 256 : kTile / 2;
+  __shared__ double tab[kTabEntries];                   // also carries q (4096 floats) at the end
   __shared__ double s_scale[kChunk];
   __shared__ double lds_d[kWaves];
   __shared__ uint32_t lds_u[kWaves];
@@ -280,7 +296,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 #if QA_EXP == 2
       w[i] = (uint32_t)(tile * 977 + i * 31 + t) & 0x11111111u;
 #else
-      w[i] = (FULL || i < left) ? (ctile + (int64_t)i * a.code_stride)[tw] : 0u;
+      w[i] = (FULL || i < left) ? stream_load(ctile + (int64_t)i * a.code_stride + tw) : 0u;
 #endif
   }
   State4 sG, sx, sz;
@@ -338,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
         const uint32_t* cc = ctile + (int64_t)m0 * a.code_stride;
 #pragma unroll
         for (int i = 0; i < kChunk; ++i)
-          w[i] = (FULL || i < left) ? (cc + (int64_t)i * a.code_stride)[tw] : 0u;
+          w[i] = (FULL || i < left) ? stream_load(cc + (int64_t)i * a.code_stride + tw) : 0u;
         __syncthreads();                                 // readers of the previous tables are done
       }
       if (t < kChunk) s_scale[t] = t < left ? (double)sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0;
@@ -505,22 +521,25 @@ static bool use_lut(const StepArgs& a) {
   return !(e && e[0] == 'o');
 }
 
-enum StepKernel { kOrdered = 0, kTableFull = 1, kTablePart = 2 };
-
+// which: -1 = worker-ordered kernel, otherwise the NGT of the table-driven kernel
 template <int MODE, bool TRACK_Z, bool REQUANT>
 static void launch_one(const StepArgs& a, int which, hipStream_t stream) {
   const dim3 grid((unsigned)tiles_of(a.d)), block(kThreads);
-  if (which == kTableFull)
-    hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, true>), grid, block, 0, stream, a);
-  else if (which == kTablePart)
-    hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, false>), grid, block, 0, stream, a);
-  else
-    hipLaunchKernelGGL((step_kernel<MODE, TRACK_Z, REQUANT>), grid, block, 0, stream, a);
+  switch (which) {
+    case 16: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 16>), grid, block, 0, stream, a); break;
+    case 8: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 8>), grid, block, 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 4>), grid, block, 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 2>), grid, block, 0, stream, a); break;
+    case 0: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 0>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((step_kernel<MODE, TRACK_Z, REQUANT>), grid, block, 0, stream, a); break;
+  }
 }
 
 template <int MODE>
 static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
-  const int which = !use_lut(a) ? kOrdered : (a.M % kChunk == 0 ? kTableFull : kTablePart);
+  int which = -1;
+  if (use_lut(a))
+    which = a.M % 64 == 0 ? 16 : a.M % 32 == 0 ? 8 : a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2 : 0;
   if (requant) {
     if (track_z) launch_one<MODE, true, true>(a, which, stream);
     else launch_one<MODE, false, true>(a, which, stream);
