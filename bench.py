@@ -21,6 +21,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see
+# profiles/step_kernel_largest_traffic.txt for the runs and the calibration against a plain
+# elementwise kernel of known size: FETCH_SIZE reads half the true KiB on this chip, WRITE_SIZE
+# reads true KiB).  Keyed by (workload, kernel kind); null for workloads not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("largest", "qcmd_z"): 30.60e9 + 12.885e9,
+    ("largest", "qrda"): 26.31e9 + 12.885e9,
+}
+
 WORKLOADS = {
     # name: d, M, bucket, generator, lambda, bytes/coord as {kernel: B}
     "largest": dict(d=1 << 30, M=64, bucket=4096, gen="laplace", lam=1e-6,
@@ -87,7 +96,6 @@ def main():
     del gbuf
     torch.cuda.empty_cache()
     quant_ms = float(np.median(q_ms[1:] if M > 1 else q_ms))
-    nz_frac = None
 
     x = torch.zeros(d, dtype=torch.float32, device=dev)
     G = torch.zeros(d, dtype=torch.float32, device=dev)
@@ -153,7 +161,9 @@ def main():
                    "code_pad_words": args.code_pad_words},
         "roofline": {"bound": "hbm", "kernel": f"step_kernel[{dominant}]",
                      "achieved": dk["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": dk["achieved_GBps"] / HBM_PEAK_GBPS, "traffic": None},
+                     "frac": dk["achieved_GBps"] / HBM_PEAK_GBPS,
+                     "algorithmic_bytes": dk["bytes_per_coord"] * d,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dominant))},
         "kernels": kernels,
         "quantize_pack": {"ms_per_worker": quant_ms, "worker_coords_per_s": d / (quant_ms * 1e-3),
                           "achieved_GBps": 4.25 * d / (quant_ms * 1e-3) / 1e9,

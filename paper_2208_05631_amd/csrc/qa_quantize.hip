@@ -208,7 +208,10 @@ __global__ __launch_bounds__(kThreads) void quantize_tile_kernel(QuantArgs a) {
   if (lo + kTile <= a.d) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const float4 q = *reinterpret_cast<const float4*>(g + lo + (j * kThreads + t) * 4);
+      // the gradient is read exactly once: nontemporal
+      typedef float floatx4 __attribute__((ext_vector_type(4)));
+      const floatx4 q = __builtin_nontemporal_load(
+          reinterpret_cast<const floatx4*>(g + lo + (j * kThreads + t) * 4));
       v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
     }
   } else {
