@@ -34,9 +34,11 @@ _lib = None
 
 
 def lib():
+    """The compiled oracle.  QA_ORACLE_LIB may name another build of the same source (the
+    mutation test points it at deliberately broken copies to show that the pins notice)."""
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(os.environ.get("QA_ORACLE_LIB") or build())
         _declare(_lib)
     return _lib
 

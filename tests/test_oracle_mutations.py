@@ -1,0 +1,62 @@
+"""The pins must notice plausible mistakes: each case plants ONE wrong token in a copy of the
+oracle source (on the CPU, never in the GPU code), rebuilds it, and expects the pin suite to
+fail against that copy."""
+import os
+import subprocess
+import sys
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "qa_oracle.cpp")
+
+MUTATIONS = [
+    ("threshold_divides_by_n_plus_1", "* S1) / (double)n);", "* S1) / (double)(n + 1));"),
+    ("scale_keeps_equal_magnitudes", "if (a > Delta) { S2 += (double)a; ++cnt; }",
+     "if (a >= Delta) { S2 += (double)a; ++cnt; }"),
+    ("negative_side_compares_wrong_sign", "if (v < -Delta) return -1;", "if (v < Delta) return -1;"),
+    ("minus_one_packed_as_10", "code[i] == 1 ? 1u : (code[i] == -1 ? 3u : 0u)",
+     "code[i] == 1 ? 1u : (code[i] == -1 ? 2u : 0u)"),
+    ("pack_shift_wraps_at_8", "words[i / 16] |= f << (2 * (i % 16));", "words[i / 16] |= f << (2 * (i % 8));"),
+    ("reserved_pattern_decodes_minus_one", "return f == 1u ? 1 : (f == 3u ? -1 : 0);",
+     "return f == 1u ? 1 : (f >= 2u ? -1 : 0);"),
+    ("average_forgets_division", "return (float)(acc / (double)M);", "return (float)(acc);"),
+    ("average_uses_wrong_bucket", "const int64_t k = i / bucket_b;", "const int64_t k = i / 16;"),
+    ("delta_inside_the_root", "return delta + std::sqrt(*G);", "return std::sqrt(delta + *G);"),
+    ("H_without_current_gradient", "  *G = *G + g2;\n  return delta + std::sqrt(*G);",
+     "  const float Gold = *G;\n  *G = *G + g2;\n  return delta + std::sqrt(Gold);"),
+    ("qcmd_tau_without_eta", "const float tau = (lambda * eta) / H;", "const float tau = lambda / H;"),
+    ("qcmd_ascends", "const float u = x - step;", "const float u = x + step;"),
+    ("qrda_wrong_sign", "return -std::copysign(mag, z);", "return std::copysign(mag, z);"),
+    ("qrda_threshold_without_t", "const float tl = (float)t * lambda;", "const float tl = lambda;"),
+    ("qrda_equality_kept", "if (!(r > 0.0f)) return 0.0f;", "if (!(r >= 0.0f)) return 0.0f;"),
+    ("qrda_z_subtracts", "    z[i] = z[i] + q[i];\n    x[i] = qrda_component",
+     "    z[i] = z[i] - q[i];\n    x[i] = qrda_component"),
+    ("logistic_gradient_sign", "*coef_out = (float)((-(double)y * sig) / (double)B);",
+     "*coef_out = (float)(((double)y * sig) / (double)B);"),
+    ("logistic_sigmoid_branches_swapped", "m >= 0 ? e / (1.0 + e) : 1.0 / (1.0 + e)",
+     "m >= 0 ? 1.0 / (1.0 + e) : e / (1.0 + e)"),
+    ("requantize_ignores_buckets", "requant == 1 ? bucket : 0, thr_coef, q.data());",
+     "0, thr_coef, q.data());"),
+    ("exact_threshold_objective", "double obj = run * run / (double)k;", "double obj = run / (double)k;"),
+    ("csr_gradient_uses_row_position", "acc[indices[k]] += (double)coef[b] * (double)vals[k];",
+     "acc[indices[k]] += (double)coef[b] * (double)vals[indptr[r]];"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_pins_catch_planted_mistake(name, old, new):
+    src = open(SRC).read()
+    assert src.count(old) == 1, f"mutation site for {name} not unique/found"
+    with tempfile.TemporaryDirectory() as tmp:
+        cpp = os.path.join(tmp, "mut.cpp")
+        so = os.path.join(tmp, "libmut.so")
+        open(cpp, "w").write(src.replace(old, new))
+        subprocess.run(["g++", "-std=c++17", "-O1", "-ffp-contract=off", "-fPIC", "-shared", cpp, "-o", so],
+                       check=True)
+        env = dict(os.environ, QA_ORACLE_LIB=so)
+        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                            os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                           env=env, cwd=ROOT, capture_output=True, text=True)
+        assert r.returncode != 0, f"pins did not notice: {name}"
