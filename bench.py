@@ -37,6 +37,10 @@ WORKLOADS = {
     "opt_qcmd": dict(d=10 ** 8, M=8, bucket=4096, gen="student", lam=1e-5, schedule="qcmd"),
     "opt_qrda": dict(d=250_000_000, M=32, bucket=4096, gen="gauss", lam=1e-5, schedule="qrda"),
     "mid": dict(d=1 << 26, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
+    # whole Algorithm-1 steps (local gradients -> quantize+pack -> fused QCMD step) on the
+    # synthetic stand-ins for the paper's linear-model experiments
+    "tiny_train": dict(train="dense", d=1000, n=4096, M=4, B=64, bucket=0, lam=1e-3),
+    "sparse_train": dict(train="csr", d=1 << 20, n=1 << 16, M=16, B=256, bucket=4096, lam=1e-4),
     "small": dict(d=1 << 22, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
 }
 
@@ -45,6 +49,55 @@ def algorithmic_bytes_per_coord(kind, M):
     """Bytes the method itself must move per coordinate and step: 2-bit codes of M workers
     plus the fp32 state each kernel reads and writes (scales add 4*M/4096, ignored)."""
     return {"qcmd": 16 + M / 4, "qcmd_z": 24 + M / 4, "qrda": 20 + M / 4}[kind]
+
+
+def train_bench(args, wl, qa, synth, torch, np, dev):
+    """K full steps of Algorithm 1 (minus indicator/selection): M local gradients, one batched
+    quantize+pack, one fused QCMD step.  Row ids of all steps are uploaded before timing."""
+    d, M, B, bucket, lam, n = wl["d"], wl["M"], wl["B"], wl["bucket"], wl["lam"], wl["n"]
+    eta, delta = 0.1, 1e-8
+    csr = wl["train"] == "csr"
+    prob = synth.csr_problem(n=n, d=d, M=M, seed=1) if csr else synth.dense_problem(n=n, d=d, M=M, seed=0)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    if csr:
+        A, indptr, indices = up(prob.vals), up(prob.indptr), up(prob.indices)
+    else:
+        A, indptr, indices = up(prob.A), None, None
+    y = up(prob.y)
+    L = qa.Layout.make(d, M, bucket)
+    gs = ((d + 3) // 4) * 4
+    x, G, z = (torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(3))
+    g = torch.zeros((M, gs), dtype=torch.float32, device=dev)
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    scales = torch.zeros((M, L.scale_stride), dtype=torch.float32, device=dev)
+    ws = lambda op: torch.empty(max(qa.qa_workspace_bytes(L, op), 256), dtype=torch.uint8, device=dev)
+    ws_g = ws(qa.QA_OP_GRAD_CSR if csr else qa.QA_OP_GRAD_DENSE)
+    ws_q, ws_s = ws(qa.QA_OP_QUANTIZE), ws(qa.QA_OP_STEP)
+    total = args.warmup + args.steps
+    rows = up(np.stack([synth.minibatch_rows(n, M, B, t, 1) for t in range(1, total + 1)]))
+    fmt = qa.QA_CSR if csr else qa.QA_DENSE
+
+    def step(t):
+        qa.qa_local_grad_batched(fmt, A, indptr, indices, n, d, y, rows[t], B, M, x, g, gs, None, ws_g)
+        qa.qa_quantize_pack(L, g, gs, codes, scales, None, 0, ws_q)
+        qa.qa_step_qcmd(L, codes, scales, x, G, None, eta, lam, delta, qa.QA_REQUANT_NONE, ws_s)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total):
+        step(t)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    out = {"metric": "full Algorithm-1 step (M local gradients + quantize+pack + fused QCMD): coordinates/s",
+           "value": d * args.steps / wall, "unit": "coordinates/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{args.workload}: d={d}, n={n}, M={M}, B={B}, bucket={bucket}, "
+                                  f"{wl['train']} rows", "launches_per_step": (4 if csr else 2) + 2},
+           "nnz_x_after": int((x != 0).sum().item())}
+    print(json.dumps(out))
 
 
 def main():
@@ -72,6 +125,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = WORKLOADS[args.workload]
+    if "train" in wl:
+        return train_bench(args, wl, qa, synth, torch, np, dev)
     d, M, bucket, lam = wl["d"], wl["M"], wl["bucket"], wl["lam"]
     eta, delta = 0.1, 1e-8
     W = (d + 15) // 16

@@ -92,8 +92,9 @@ int qa_version(void);
 const char* qa_strerror(int code);
 
 /* Bytes of device workspace that `op` needs for this layout (0 if none).  For
- * QA_OP_GRAD_CSR / QA_OP_GRAD_DENSE only layout->d is used.  Returns 0 for a NULL or invalid
- * layout. */
+ * QA_OP_GRAD_CSR / QA_OP_GRAD_DENSE only layout->d and layout->M are used (the size for
+ * qa_local_grad_batched over M workers; qa_local_grad needs 1/M of it).  Returns 0 for a NULL or
+ * invalid layout. */
 size_t qa_workspace_bytes(const qa_layout* layout, int op);
 
 /* Minibatch gradient of one worker for the logistic loss log(1 + exp(-y a.x)), y in {-1,+1}
@@ -114,6 +115,16 @@ int qa_local_grad(int format, const float* A_or_vals, const int64_t* indptr, con
                   int64_t n_rows, int64_t d, const float* y, const int32_t* batch_rows, int32_t B,
                   const float* x, float* g_out, float* loss_out, void* ws, size_t ws_bytes,
                   void* stream);
+
+/* The same for M workers in one call ("for M worker ... do in parallel", Algorithm 1): worker m
+ * uses batch_rows[m*B .. m*B+B), writes g_out[m*g_stride .. + d) and loss_out[m] (loss_out may
+ * be NULL).  g_stride >= d and a multiple of 4.  All workers read the same x.
+ * ws: qa_workspace_bytes(layout with d and M, QA_OP_GRAD_CSR or QA_OP_GRAD_DENSE). */
+int qa_local_grad_batched(int format, const float* A_or_vals, const int64_t* indptr,
+                          const int32_t* indices, int64_t n_rows, int64_t d, const float* y,
+                          const int32_t* batch_rows, int32_t B, int32_t M, const float* x,
+                          float* g_out, int64_t g_stride, float* loss_out, void* ws, size_t ws_bytes,
+                          void* stream);
 
 /* Threshold quantizer of Sections 3.4-3.5 and 2-bit encoding for M gradients
  * g[m*g_stride + i], m < M, i < d, bucket by bucket (bucket k = [k*b, min((k+1)*b, d)),

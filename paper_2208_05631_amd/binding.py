@@ -65,6 +65,8 @@ _lib.qa_workspace_bytes.restype = _sz
 _lib.qa_workspace_bytes.argtypes = [C.POINTER(Layout), C.c_int]
 _lib.qa_local_grad.argtypes = [C.c_int, _vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _vp, C.c_int32,
                                _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.qa_local_grad_batched.argtypes = [C.c_int, _vp, _vp, _vp, C.c_int64, C.c_int64, _vp, _vp, C.c_int32,
+                                       C.c_int32, _vp, _vp, C.c_int64, _vp, _vp, _sz, _vp]
 _lib.qa_quantize_pack.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp, C.c_uint32,
                                   _vp, _sz, _vp]
 _lib.qa_aggregate_unpack.argtypes = [C.POINTER(Layout), _vp, _vp, _vp, _vp]
@@ -112,6 +114,13 @@ def qa_local_grad(fmt, A_or_vals, indptr, indices, n_rows, d, y, batch_rows, B, 
     _check(_lib.qa_local_grad(fmt, _p(A_or_vals), _p(indptr), _p(indices), n_rows, d, _p(y),
                               _p(batch_rows), B, _p(x), _p(g_out), _p(loss_out), _p(ws), _nbytes(ws),
                               _stream(stream)), "qa_local_grad")
+
+
+def qa_local_grad_batched(fmt, A_or_vals, indptr, indices, n_rows, d, y, batch_rows, B, M, x, g_out,
+                          g_stride, loss_out, ws, stream=None):
+    _check(_lib.qa_local_grad_batched(fmt, _p(A_or_vals), _p(indptr), _p(indices), n_rows, d, _p(y),
+                                      _p(batch_rows), B, M, _p(x), _p(g_out), g_stride, _p(loss_out),
+                                      _p(ws), _nbytes(ws), _stream(stream)), "qa_local_grad_batched")
 
 
 def qa_quantize_pack(layout, g, g_stride, codes, scales, thresholds, flags, ws, stream=None):

@@ -25,8 +25,8 @@ extern "C" size_t qa_workspace_bytes(const qa_layout* layout, int op) {
   using namespace qa;
   if (!layout) return 0;
   if (op == QA_OP_GRAD_CSR || op == QA_OP_GRAD_DENSE) {
-    if (layout->d < 1) return 0;
-    return grad_workspace_bytes(layout->d, op == QA_OP_GRAD_CSR);
+    if (layout->d < 1 || layout->M < 1) return 0;
+    return (size_t)layout->M * grad_workspace_bytes(layout->d, op == QA_OP_GRAD_CSR);
   }
   if (check_layout(layout) != QA_OK) return 0;
   if (op == QA_OP_QUANTIZE) return quantize_workspace_bytes(layout);

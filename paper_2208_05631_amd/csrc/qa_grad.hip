@@ -29,7 +29,23 @@ struct GradArgs {
   float* coef;               // [B]   workspace
   double* loss_part;         // [B]   workspace
   double* acc;               // [d]   workspace (CSR)
+  // batched calls: worker m = blockIdx.y uses rows + m*B, g + m*g_stride, loss_out + m and the
+  // m-th slice of each workspace array
+  int64_t g_stride;
+  int64_t ws_stride_bytes;
 };
+
+// View of the arguments for the worker selected by blockIdx.y.
+__device__ __forceinline__ GradArgs for_worker(GradArgs a) {
+  const int64_t m = blockIdx.y;
+  a.rows += m * a.B;
+  a.g += m * a.g_stride;
+  if (a.loss_out) a.loss_out += m;
+  a.coef = reinterpret_cast<float*>(reinterpret_cast<char*>(a.coef) + m * a.ws_stride_bytes);
+  a.loss_part = reinterpret_cast<double*>(reinterpret_cast<char*>(a.loss_part) + m * a.ws_stride_bytes);
+  a.acc = reinterpret_cast<double*>(reinterpret_cast<char*>(a.acc) + m * a.ws_stride_bytes);
+  return a;
+}
 
 // coef and loss of one sample from its binary32 margin term p = a.x
 __device__ __forceinline__ void logistic_terms(float p, float y, int B, float* coef, double* loss) {
@@ -40,7 +56,8 @@ __device__ __forceinline__ void logistic_terms(float p, float y, int B, float* c
   *coef = (float)((-(double)y * sig) / (double)B);
 }
 
-__global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a) {
+__global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a_all) {
+  const GradArgs a = for_worker(a_all);
   __shared__ double lds_d[kWaves];
   const int b = blockIdx.x;
   const int64_t r = a.rows[b];
@@ -58,7 +75,8 @@ __global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a) {
   }
 }
 
-__global__ __launch_bounds__(kThreads) void dense_colsum_kernel(GradArgs a) {
+__global__ __launch_bounds__(kThreads) void dense_colsum_kernel(GradArgs a_all) {
+  const GradArgs a = for_worker(a_all);
   const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (j >= a.d) return;
   double acc = 0.0;
@@ -70,14 +88,17 @@ __global__ __launch_bounds__(kThreads) void dense_colsum_kernel(GradArgs a) {
   a.g[j] = (float)acc;
 }
 
-__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* p, int64_t n) {
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* p_all, int64_t n,
+                                                            int64_t stride) {
+  float* p = p_all + (int64_t)blockIdx.y * stride;
   const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
   if (i + 3 < n) *reinterpret_cast<float4*>(p + i) = make_float4(0.f, 0.f, 0.f, 0.f);
   else for (int e = 0; e < 4; ++e) if (i + e < n) p[i + e] = 0.0f;
 }
 
 // one wave per batch row: margin, coef, loss; also clears the accumulator at the row's columns
-__global__ __launch_bounds__(kThreads) void csr_margin_kernel(GradArgs a) {
+__global__ __launch_bounds__(kThreads) void csr_margin_kernel(GradArgs a_all) {
+  const GradArgs a = for_worker(a_all);
   const int b = blockIdx.x * kWaves + threadIdx.x / kWave;
   if (b >= a.B) return;
   const int lane = threadIdx.x % kWave;
@@ -103,7 +124,8 @@ __global__ __launch_bounds__(kThreads) void csr_margin_kernel(GradArgs a) {
 }
 
 template <bool FINALIZE>
-__global__ __launch_bounds__(kThreads) void csr_scatter_kernel(GradArgs a) {
+__global__ __launch_bounds__(kThreads) void csr_scatter_kernel(GradArgs a_all) {
+  const GradArgs a = for_worker(a_all);
   const int b = blockIdx.x * kWaves + threadIdx.x / kWave;
   if (b >= a.B) return;
   const int lane = threadIdx.x % kWave;
@@ -119,7 +141,8 @@ __global__ __launch_bounds__(kThreads) void csr_scatter_kernel(GradArgs a) {
   }
 }
 
-__global__ __launch_bounds__(kThreads) void loss_finalize_kernel(GradArgs a) {
+__global__ __launch_bounds__(kThreads) void loss_finalize_kernel(GradArgs a_all) {
+  const GradArgs a = for_worker(a_all);
   __shared__ double lds_d[kWaves];
   double s = 0.0;
   for (int b = threadIdx.x; b < a.B; b += kThreads) s += a.loss_part[b];
@@ -134,47 +157,67 @@ size_t grad_workspace_bytes(int64_t d, bool csr) {
          (csr ? align256((size_t)d * sizeof(double)) : 0);
 }
 
-}  // namespace qa
-
-extern "C" int qa_local_grad(int format, const float* A_or_vals, const int64_t* indptr,
-                             const int32_t* indices, int64_t n_rows, int64_t d, const float* y,
-                             const int32_t* batch_rows, int32_t B, const float* x, float* g_out,
-                             float* loss_out, void* ws, size_t ws_bytes, void* stream_) {
-  using namespace qa;
+static int grad_launch(int format, const float* A_or_vals, const int64_t* indptr,
+                       const int32_t* indices, int64_t n_rows, int64_t d, const float* y,
+                       const int32_t* batch_rows, int32_t B, int32_t M, const float* x, float* g_out,
+                       int64_t g_stride, float* loss_out, void* ws, size_t ws_bytes,
+                       hipStream_t stream) {
   if (format != QA_DENSE && format != QA_CSR) return QA_ERR_INVALID_ARG;
   if (!A_or_vals || !y || !batch_rows || !x || !g_out) return QA_ERR_INVALID_ARG;
   if (format == QA_CSR && (!indptr || !indices)) return QA_ERR_INVALID_ARG;
-  if (n_rows < 1 || d < 1 || d >= (int64_t(1) << 31) || B < 1 || B > kMaxBatch)
+  if (n_rows < 1 || d < 1 || d >= (int64_t(1) << 31) || B < 1 || B > kMaxBatch || M < 1 || M > 4096)
     return QA_ERR_INVALID_ARG;
+  if (M > 1 && (g_stride < d || (g_stride % 4) != 0)) return QA_ERR_INVALID_ARG;
   if (!aligned(g_out, 16) || !aligned(A_or_vals, 4) || !aligned(x, 4) || !aligned(indptr, 8) ||
       !aligned(indices, 4) || !aligned(batch_rows, 4) || !aligned(loss_out, 4))
     return QA_ERR_ALIGNMENT;
   const bool csr = format == QA_CSR;
-  if (!ws || ws_bytes < grad_workspace_bytes(d, csr)) return QA_ERR_WORKSPACE;
+  const size_t per_worker = grad_workspace_bytes(d, csr);
+  if (!ws || ws_bytes < per_worker * (size_t)M) return QA_ERR_WORKSPACE;
   if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
 
   GradArgs a{};
   a.A = A_or_vals; a.indptr = indptr; a.indices = indices; a.n_rows = n_rows; a.d = d;
   a.y = y; a.rows = batch_rows; a.B = B; a.x = x; a.g = g_out; a.loss_out = loss_out;
+  a.g_stride = g_stride; a.ws_stride_bytes = (int64_t)per_worker;
   char* p = static_cast<char*>(ws);
   a.coef = reinterpret_cast<float*>(p);        p += align256((size_t)kMaxBatch * sizeof(float));
   a.loss_part = reinterpret_cast<double*>(p);  p += align256((size_t)kMaxBatch * sizeof(double));
   a.acc = reinterpret_cast<double*>(p);
 
   const dim3 block(kThreads);
+  const unsigned Mu = (unsigned)M;
   if (!csr) {
-    hipLaunchKernelGGL(dense_margin_kernel, dim3(B), block, 0, stream, a);
-    hipLaunchKernelGGL(dense_colsum_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads)), block, 0,
-                       stream, a);
+    hipLaunchKernelGGL(dense_margin_kernel, dim3(B, Mu), block, 0, stream, a);
+    hipLaunchKernelGGL(dense_colsum_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), Mu), block,
+                       0, stream, a);
   } else {
-    const dim3 grid_rows((B + kWaves - 1) / kWaves);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((d + 4 * kThreads - 1) / (4 * kThreads))),
-                       block, 0, stream, g_out, d);
+    const dim3 grid_rows((B + kWaves - 1) / kWaves, Mu);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((d + 4 * kThreads - 1) / (4 * kThreads)), Mu),
+                       block, 0, stream, g_out, d, g_stride);
     hipLaunchKernelGGL(csr_margin_kernel, grid_rows, block, 0, stream, a);
     hipLaunchKernelGGL((csr_scatter_kernel<false>), grid_rows, block, 0, stream, a);
     hipLaunchKernelGGL((csr_scatter_kernel<true>), grid_rows, block, 0, stream, a);
   }
-  if (loss_out) hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), block, 0, stream, a);
+  if (loss_out) hipLaunchKernelGGL(loss_finalize_kernel, dim3(1, Mu), block, 0, stream, a);
   return launch_status();
+}
+
+}  // namespace qa
+
+extern "C" int qa_local_grad(int format, const float* A_or_vals, const int64_t* indptr,
+                             const int32_t* indices, int64_t n_rows, int64_t d, const float* y,
+                             const int32_t* batch_rows, int32_t B, const float* x, float* g_out,
+                             float* loss_out, void* ws, size_t ws_bytes, void* stream) {
+  return qa::grad_launch(format, A_or_vals, indptr, indices, n_rows, d, y, batch_rows, B, 1, x, g_out,
+                         0, loss_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int qa_local_grad_batched(int format, const float* A_or_vals, const int64_t* indptr,
+                                     const int32_t* indices, int64_t n_rows, int64_t d,
+                                     const float* y, const int32_t* batch_rows, int32_t B, int32_t M,
+                                     const float* x, float* g_out, int64_t g_stride, float* loss_out,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  return qa::grad_launch(format, A_or_vals, indptr, indices, n_rows, d, y, batch_rows, B, M, x, g_out,
+                         g_stride, loss_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }

@@ -15,7 +15,7 @@ def test_every_declared_symbol_is_exported():
     hdr = open(os.path.join(ROOT, "include", "qadagrad.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(qa_[a-z_]+)\s*\(", hdr))
-    assert {"qa_local_grad", "qa_quantize_pack", "qa_aggregate_unpack", "qa_step_qcmd",
+    assert {"qa_local_grad", "qa_local_grad_batched", "qa_quantize_pack", "qa_aggregate_unpack", "qa_step_qcmd",
             "qa_step_qrda", "qa_workspace_bytes", "qa_strerror", "qa_version"} <= names
     lib = C.CDLL(B.lib_path())
     for n in names:
@@ -42,7 +42,7 @@ def test_workspace_sizes():
     nt = (10**6 + 4095) // 4096
     assert qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE) >= 8 * nt * 12
     assert qa.qa_workspace_bytes(L, qa.QA_OP_STEP) >= 4 * 10**6       # averaged vector for GLOBAL
-    assert qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR) >= 8 * 10**6
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR) >= 8 * 8 * 10**6      # M = 8 accumulators
     assert 0 < qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_DENSE) < 8 * 10**6
     bad = qa.Layout.make(10**6, 8, 100)                               # not a power of two
     assert qa.qa_workspace_bytes(bad, qa.QA_OP_STEP) == 0

@@ -298,3 +298,35 @@ def test_local_grad_csr_matches_oracle():
     assert np.allclose(gg, og, rtol=1e-6, atol=1e-12)
     assert host(loss)[0] == pytest.approx(ol, rel=1e-6)
     assert (gg == og).mean() > 0.999
+
+
+@pytest.mark.parametrize("csr", [False, True])
+def test_local_grad_batched_equals_per_worker_calls_and_oracle(csr):
+    rng = np.random.default_rng(8)
+    n, d, k, B, M = 400, 3000, 30, 48, 5
+    y = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    x = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    rows = rng.integers(0, n, (M, B)).astype(np.int32)
+    if csr:
+        vals, indptr, idx = _random_csr(rng, n, d, k)
+        A_d, ip_d, ix_d = dev(vals), dev(indptr), dev(idx)
+        ref = [oracle.local_grad_csr(vals, indptr, idx, d, y, rows[m], x) for m in range(M)]
+        fmt, op = qa.QA_CSR, qa.QA_OP_GRAD_CSR
+    else:
+        A = rng.standard_normal((n, d)).astype(np.float32)
+        A_d, ip_d, ix_d = dev(A), None, None
+        ref = [oracle.local_grad_dense(A, y, rows[m], x) for m in range(M)]
+        fmt, op = qa.QA_DENSE, qa.QA_OP_GRAD_DENSE
+    gs = d + 8
+    ws = workspace(qa.qa_workspace_bytes(qa.Layout.make(d, M, 0), op))
+    g = torch.full((M, gs), 5.0, dtype=torch.float32, device=DEV)
+    loss = torch.zeros(M, dtype=torch.float32, device=DEV)
+    qa.qa_local_grad_batched(fmt, A_d, ip_d, ix_d, n, d, dev(y), dev(rows), B, M, dev(x), g, gs, loss, ws)
+    torch.cuda.synchronize()
+    gg, ll = host(g), host(loss)
+    assert np.all(gg[:, d:] == 5.0)                      # padding between workers untouched
+    for m in range(M):
+        assert np.array_equal(gg[m, :d] != 0, ref[m][0] != 0)
+        assert np.allclose(gg[m, :d], ref[m][0], rtol=1e-6, atol=1e-12)
+        assert ll[m] == pytest.approx(ref[m][1], rel=1e-6)
+    assert (gg[:, :d] == np.stack([r[0] for r in ref])).mean() > 0.999

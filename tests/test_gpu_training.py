@@ -60,9 +60,10 @@ class GpuTrainer:
                          self.x, out, loss, self.ws_g)
 
     def step(self, rows, method, t, eta, lam, delta, requant):
-        rd = dev(rows)
-        for m in range(self.M):
-            self.grad(rd[m], rows.shape[1], self.g[m], None)
+        fmt = qa.QA_CSR if self.csr else qa.QA_DENSE
+        qa.qa_local_grad_batched(fmt, self.A, self.indptr, self.indices, self.n, self.d, self.y,
+                                 dev(rows), rows.shape[1], self.M, self.x, self.g, self.gs, None,
+                                 self.ws_g)
         qa.qa_quantize_pack(self.L, self.g, self.gs, self.codes, self.scales, None, 0, self.ws_q)
         if method == "qcmd":
             qa.qa_step_qcmd(self.L, self.codes, self.scales, self.x, self.G, self.z, eta, lam, delta,
