@@ -72,6 +72,10 @@ def _declare(L):
                                 _vp, _f32, _f32, _f32, _i32]
     L.orc_step_qrda.argtypes = [_u32p, _i64, _f32p, _i64, _i64, _i32, _i64, _f32, _f32p, _f32p,
                                 _f32p, _i64, _f32, _f32, _f32, _i32]
+    L.orc_indicator.argtypes = [_i32, _f32p, _i64, _f32p, _f32p, _vp, _i64, _f32, _f32, _f32, _u32p]
+    L.orc_indicator_or.argtypes = [_u32p, _i64, _i32, _i64, _u32p]
+    L.orc_quantize_selected.argtypes = [_f32p, _u32p, _i64, _i64, _f32, _u32p, _u32p, _f32p, _f32p]
+    L.orc_decode_selected.argtypes = [_u32p, _u32p, _i64, _i64, _u32p]
     L.orc_local_grad_dense.argtypes = [_f32p, _i64, _i64, _f32p, _i32p, _i32, _f32p, _f32p,
                                        C.POINTER(_f32)]
     L.orc_local_grad_csr.argtypes = [_f32p, _i64p, _i32p, _i64, _i64, _f32p, _i32p, _i32, _f32p,
@@ -256,3 +260,53 @@ def local_grad_csr(vals, indptr, indices, d, y, batch_rows, x):
     lib().orc_local_grad_csr(vals, indptr, indices, indptr.size - 1, d, y, rows, rows.size, x, g,
                              C.byref(loss))
     return g, loss.value
+
+
+# ---- indicator / selection / sparse encoding ---------------------------------------------
+
+QCMD, QRDA = 0, 1
+
+
+def n_ind_words(d: int) -> int:
+    return (d + 31) // 32
+
+
+def indicator(method, g, x, G, z, t, eta, lam, delta):
+    """-> u32[ceil(d/32)]: bit i set iff x_i != 0 or the worker's own update of x_i is != 0."""
+    g = np.ascontiguousarray(g, np.float32)
+    _chk_state(x, G, z)
+    out = np.empty(n_ind_words(g.size), np.uint32)
+    lib().orc_indicator(method, g, g.size, x, G, _ptr(z), t, eta, lam, delta, out)
+    return out
+
+
+def indicator_or(ind, d):
+    ind = np.ascontiguousarray(ind, np.uint32)
+    out = np.empty(n_ind_words(d), np.uint32)
+    lib().orc_indicator_or(ind, ind.shape[1], ind.shape[0], d, out)
+    return out
+
+
+def quantize_selected(g, ind, bucket=0, thr_coef=0.75):
+    """-> (sel_codes u32[nb*area], counts u32[nb], scales f32[nb], thresholds f32[nb]);
+    area = ceil(bucket_len/16) words per bucket, only the first ceil(count/16) are written."""
+    g = np.ascontiguousarray(g, np.float32)
+    ind = np.ascontiguousarray(ind, np.uint32)
+    d = g.size
+    nb = n_buckets(d, bucket)
+    b = bucket if bucket > 0 else d
+    area = (b + 15) // 16
+    sel = np.zeros(nb * area, np.uint32)
+    cnt = np.zeros(nb, np.uint32)
+    sc = np.zeros(nb, np.float32)
+    th = np.zeros(nb, np.float32)
+    lib().orc_quantize_selected(g, ind, d, bucket, thr_coef, sel, cnt, sc, th)
+    return sel, cnt, sc, th
+
+
+def decode_selected(ind, sel_codes, d, bucket=0):
+    ind = np.ascontiguousarray(ind, np.uint32)
+    sel_codes = np.ascontiguousarray(sel_codes, np.uint32)
+    out = np.empty(n_words(d), np.uint32)
+    lib().orc_decode_selected(ind, sel_codes, d, bucket, out)
+    return out

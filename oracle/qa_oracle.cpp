@@ -315,6 +315,92 @@ void orc_step_qrda(const uint32_t* codes, int64_t code_stride, const float* scal
   orc_update_qrda(q.data(), d, x, G, z, t, eta, lambda, delta);
 }
 
+// ---- indicator, selection and sparse encoding (Section 3.2: equations "select" and "ind";
+//      Algorithm 1, worker block; "Encode" paragraph: (32 + d + 2k) bits) ----------------------
+//
+// Worker m forms the parameter it WOULD get from its own full-precision gradient g,
+//   H^ = delta + sqrt(G + g^2)   (c^ = ||[q_{1:t-1}, g]||_2, G being the sum of the q^2 so far),
+//   x^ = the QCMD or QRDA update with g in place of q_t,
+// and marks coordinate i iff x_i != 0 or x^_i != 0.  Only marked components are quantized
+// (the quantizer sees the k marked components as a vector of length k) and sent together with
+// the d-bit indicator.  method: 0 = QCMD, 1 = QRDA.  Indicator bit i = bit (i%32) of word i/32.
+void orc_indicator(int method, const float* g, int64_t d, const float* x, const float* G,
+                   const float* z, int64_t t, float eta, float lambda, float delta,
+                   uint32_t* ind_out) {
+  const int64_t nw = (d + 31) / 32;
+  for (int64_t w = 0; w < nw; ++w) ind_out[w] = 0u;
+  for (int64_t i = 0; i < d; ++i) {
+    float Gh = G[i];
+    const float Hh = accumulate_H(&Gh, g[i], delta);
+    float xh;
+    if (method == 0) {
+      xh = qcmd_component(x[i], g[i], Hh, eta, lambda);
+    } else {
+      const float zh = z[i] + g[i];
+      xh = qrda_component(zh, Hh, t, eta, lambda);
+    }
+    if (x[i] != 0.0f || xh != 0.0f) ind_out[i / 32] |= 1u << (i % 32);
+  }
+}
+
+// Synchronous indicator: bitwise OR of the M indicators (Algorithm 1, server).
+void orc_indicator_or(const uint32_t* ind, int64_t ind_stride, int M, int64_t d, uint32_t* out) {
+  const int64_t nw = (d + 31) / 32;
+  for (int64_t w = 0; w < nw; ++w) {
+    uint32_t v = 0u;
+    for (int m = 0; m < M; ++m) v |= ind[(int64_t)m * ind_stride + w];
+    out[w] = v;
+  }
+}
+
+// Q(S(g, I)) bucket by bucket: the marked components of bucket k, in index order, form a vector
+// of length count[k]; it is quantized by the threshold quantizer (threshold uses count[k] as
+// its length) and its codes are packed from bit 0 of word k*area_words of `sel_codes`
+// (area_words = ceil(bucket_len/16)).  count[k] == 0: scale 0, threshold 0, nothing written.
+void orc_quantize_selected(const float* g, const uint32_t* ind, int64_t d, int64_t bucket,
+                           float thr_coef, uint32_t* sel_codes, uint32_t* count, float* scale,
+                           float* thresh) {
+  const int64_t b = bucket_len(d, bucket), nb = n_buckets(d, bucket);
+  const int64_t area = (b + 15) / 16;
+  std::vector<float> sel;
+  std::vector<int8_t> code;
+  for (int64_t k = 0; k < nb; ++k) {
+    const int64_t lo = k * b, hi = std::min(lo + b, d);
+    sel.clear();
+    for (int64_t i = lo; i < hi; ++i)
+      if ((ind[i / 32] >> (i % 32)) & 1u) sel.push_back(g[i]);
+    count[k] = (uint32_t)sel.size();
+    scale[k] = 0.0f;
+    if (thresh) thresh[k] = 0.0f;
+    if (sel.empty()) continue;
+    code.resize(sel.size());
+    float s, D;
+    quantize_vector(sel.data(), (int64_t)sel.size(), 0, thr_coef, code.data(), &s, &D, nullptr);
+    scale[k] = s;
+    if (thresh) thresh[k] = D;
+    pack_codes(code.data(), (int64_t)sel.size(), sel_codes + k * area);
+  }
+}
+
+// S^{-1}: put the codes of the marked components back at their coordinates (unmarked -> 0) in
+// the dense 2-bit layout of one worker.
+void orc_decode_selected(const uint32_t* ind, const uint32_t* sel_codes, int64_t d, int64_t bucket,
+                         uint32_t* dense_words) {
+  const int64_t b = bucket_len(d, bucket), nb = n_buckets(d, bucket);
+  const int64_t area = (b + 15) / 16;
+  std::vector<int8_t> code(d, 0);
+  for (int64_t k = 0; k < nb; ++k) {
+    const int64_t lo = k * b, hi = std::min(lo + b, d);
+    int64_t j = 0;
+    for (int64_t i = lo; i < hi; ++i)
+      if ((ind[i / 32] >> (i % 32)) & 1u) {
+        code[i] = (int8_t)decode_field(sel_codes[k * area + j / 16], (int)(j % 16));
+        ++j;
+      }
+  }
+  pack_codes(code.data(), d, dense_words);
+}
+
 // ---- local gradient: L1-regularised logistic regression (Section 4.1) ----------------
 //
 // Loss of one sample (a, y), y in {-1,+1}:  log(1 + exp(-y * a.x)); the minibatch

@@ -42,6 +42,14 @@ MUTATIONS = [
     ("exact_threshold_objective", "double obj = run * run / (double)k;", "double obj = run / (double)k;"),
     ("csr_gradient_uses_row_position", "acc[indices[k]] += (double)coef[b] * (double)vals[k];",
      "acc[indices[k]] += (double)coef[b] * (double)vals[indptr[r]];"),
+    ("indicator_needs_both", "if (x[i] != 0.0f || xh != 0.0f) ind_out", "if (x[i] != 0.0f && xh != 0.0f) ind_out"),
+    # (dropping g^2 from H^ is not a detectable mistake: whether x^ is zero does not depend on H^
+    #  in exact arithmetic -- |x H - eta g| > lambda eta, resp. |z + g| > t lambda)
+    ("indicator_qrda_ignores_local_gradient", "const float zh = z[i] + g[i];", "const float zh = z[i];"),
+    ("selection_takes_unmarked", "if ((ind[i / 32] >> (i % 32)) & 1u) sel.push_back(g[i]);",
+     "if (!((ind[i / 32] >> (i % 32)) & 1u)) sel.push_back(g[i]);"),
+    ("decode_advances_on_every_coordinate", "        ++j;\n      }\n  }\n  pack_codes(code.data(), d, dense_words);",
+     "      }\n      ++j;\n  }\n  pack_codes(code.data(), d, dense_words);"),
 ]
 
 
@@ -57,6 +65,7 @@ def test_pins_catch_planted_mistake(name, old, new):
                        check=True)
         env = dict(os.environ, QA_ORACLE_LIB=so)
         r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                            os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                            os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                            os.path.join(ROOT, "tests", "test_oracle_selection_pins.py")],
                            env=env, cwd=ROOT, capture_output=True, text=True)
         assert r.returncode != 0, f"pins did not notice: {name}"

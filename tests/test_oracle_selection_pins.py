@@ -1,0 +1,100 @@
+"""Pins for the oracle's indicator / selection / sparse-encoding functions (Section 3.2 and the
+Encode paragraph): hand example, definition through the already pinned update and quantizer
+functions, round trips, special cases.  No GPU, no product code."""
+import numpy as np
+import pytest
+
+import oracle
+from conftest import golden
+
+
+def f32(xs):
+    return np.array([float(x) for x in xs], np.float32)
+
+
+def bits_of(ind, d):
+    return np.array([(int(ind[i // 32]) >> (i % 32)) & 1 for i in range(d)], bool)
+
+
+def test_hand_example_indicator_selection_and_message_size():
+    g = golden("indicator_hand_example.txt")
+    x, G, gr = f32(g["x"]), f32(g["G"]), f32(g["g"])
+    ind = oracle.indicator(oracle.QCMD, gr, x, G, None, 1, float(g["eta"][0]), float(g["lambda"][0]),
+                           float(g["delta"][0]))
+    assert bits_of(ind, 3).astype(int).tolist() == [int(b) for b in g["indicator_bits"]]
+    sel, cnt, sc, th = oracle.quantize_selected(gr, ind)
+    assert cnt[0] == int(g["selected_count"][0])
+    assert th[0] == pytest.approx(float(g["selected_Delta"][0]), rel=1e-6)
+    assert sc[0] == pytest.approx(float(g["selected_s"][0]), rel=1e-6)
+    assert oracle.unpack(sel, int(cnt[0])).tolist() == [int(c) for c in g["selected_codes"]]
+    dense = oracle.decode_selected(ind, sel, 3)
+    assert oracle.unpack(dense, 3).tolist() == [int(c) for c in g["decoded"]]
+    assert 32 + 3 + 2 * int(cnt[0]) == int(g["message_bits"][0])
+
+
+@pytest.mark.parametrize("method", [oracle.QCMD, oracle.QRDA])
+def test_indicator_follows_its_definition_through_the_pinned_updates(method):
+    rng = np.random.default_rng(method)
+    d, eta, lam, delta, t = 300, 0.1, 0.3, 1e-3, 7
+    x = (rng.standard_normal(d) * (rng.random(d) < 0.3)).astype(np.float32)
+    G = (rng.random(d) * 2).astype(np.float32)
+    z = (rng.standard_normal(d) * 2).astype(np.float32)
+    g = (rng.standard_normal(d) * rng.choice([0.01, 1.0], d)).astype(np.float32)
+    ind = oracle.indicator(method, g, x, G, z, t, eta, lam, delta)
+    xh, Gh, zh = x.copy(), G.copy(), z.copy()
+    if method == oracle.QCMD:
+        oracle.update_qcmd(g, xh, Gh, None, eta, lam, delta)      # the worker's own update, q := g
+    else:
+        oracle.update_qrda(g, xh, Gh, zh, t, eta, lam, delta)
+    expect = (x != 0) | (xh != 0)
+    assert np.array_equal(bits_of(ind, d), expect)
+    assert 0 < expect.sum() < d                                   # both outcomes occur
+    assert int(ind[-1]) >> (d % 32) == 0                          # unused bits stay zero
+
+
+@pytest.mark.parametrize("d,bucket", [(1000, 0), (1000, 256), (9000, 4096), (4096, 4096)])
+def test_quantize_selected_is_the_quantizer_on_the_compacted_vector(d, bucket):
+    rng = np.random.default_rng(d + bucket)
+    g = rng.standard_normal(d).astype(np.float32)
+    mask = rng.random(d) < 0.2
+    mask[:5] = False
+    if bucket:
+        mask[bucket:2 * bucket] = False                           # an empty bucket
+    ind = np.zeros(oracle.n_ind_words(d), np.uint32)
+    for i in np.nonzero(mask)[0]:
+        ind[i // 32] |= np.uint32(1 << (i % 32))
+    sel, cnt, sc, th = oracle.quantize_selected(g, ind, bucket=bucket)
+    b = bucket or d
+    area = (b + 15) // 16
+    dense = oracle.unpack(oracle.decode_selected(ind, sel, d, bucket=bucket), d)
+    for k in range(oracle.n_buckets(d, bucket)):
+        lo, hi = k * b, min((k + 1) * b, d)
+        v = g[lo:hi][mask[lo:hi]]
+        assert cnt[k] == v.size
+        if v.size == 0:
+            assert sc[k] == 0 and th[k] == 0
+            continue
+        c, s1, t1 = oracle.quantize(v)                            # pinned quantizer, length k
+        assert sc[k] == s1[0] and th[k] == t1[0]
+        assert np.array_equal(oracle.unpack(sel[k * area:], v.size), c)
+        assert np.array_equal(dense[lo:hi][mask[lo:hi]], c)
+    assert not dense[~mask].any()
+
+
+def test_all_ones_indicator_equals_dense_path():
+    rng = np.random.default_rng(5)
+    d, b = 5000, 1024
+    g = rng.standard_normal(d).astype(np.float32)
+    ind = np.full(oracle.n_ind_words(d), 0xFFFFFFFF, np.uint32)
+    ind[-1] = np.uint32((1 << (d % 32)) - 1)
+    sel, cnt, sc, th = oracle.quantize_selected(g, ind, bucket=b)
+    codes, scales, thr = oracle.quantize_pack(g[None, :], bucket=b)
+    assert np.array_equal(sc, scales[0]) and np.array_equal(th, thr[0])
+    assert np.array_equal(oracle.decode_selected(ind, sel, d, bucket=b), codes[0])
+    assert cnt.sum() == d
+
+
+def test_indicator_or():
+    rng = np.random.default_rng(6)
+    ind = rng.integers(0, 2 ** 32, (5, 10), dtype=np.uint64).astype(np.uint32)
+    assert np.array_equal(oracle.indicator_or(ind, 320), np.bitwise_or.reduce(ind, axis=0))
