@@ -171,6 +171,48 @@ int qa_step_qrda(const qa_layout* layout, const uint32_t* codes, const float* sc
                  float* G, float* z, int64_t t, float eta, float lambda, float delta, int requant,
                  void* ws, size_t ws_bytes, void* stream);
 
+/* ---- indicator, selection and sparse encoding (Section 3.2, equations "select" and "ind";
+ * Algorithm 1: worker block and the server's decode; Encode paragraph: 32 + d + 2k bits) ----
+ *
+ * A worker sends only the components of its gradient whose parameter is, or would become,
+ * non-zero, plus one bit per coordinate saying which ones.  The indicator of worker m is
+ * ind[m*ind_stride + i/32], bit i%32; unused bits of the last word are 0.
+ * These calls require bucket == 4096, or bucket == 0 with d <= 4096 (QA_ERR_UNSUPPORTED otherwise).
+ */
+#define QA_METHOD_QCMD 0
+#define QA_METHOD_QRDA 1
+
+/* Indicators of all M workers.  Worker m forms, from its own full-precision gradient
+ * g[m*g_stride + i], the parameter it would get:  H^ = delta + sqrt(G_i + g*g), then the QCMD
+ * (method 0) or QRDA (method 1, with z_i + g and step index t) closed form with g in place of
+ * q, evaluated exactly like qa_step_qcmd / qa_step_qrda; bit i = (x_i != 0 or x^_i != 0).
+ * x, G, z are only read.  z may be NULL for QCMD.  ind_stride >= ceil(d/32). */
+int qa_indicator(const qa_layout* layout, int method, const float* g, int64_t g_stride,
+                 const float* x, const float* G, const float* z, int64_t t, float eta, float lambda,
+                 float delta, uint32_t* ind_out, int64_t ind_stride, void* stream);
+
+/* Synchronous indicator: ind_syn_out[w] = OR over the M workers of ind[m*ind_stride + w]. */
+int qa_indicator_or(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                    uint32_t* ind_syn_out, void* stream);
+
+/* Q(S(g, I)) for M workers: in every bucket k the marked components, in index order, form a
+ * vector of length counts[m*scale_stride + k]; threshold (with that length as n), scale and
+ * ternary codes as in qa_quantize_pack; its codes are packed from bit 0 of word
+ * sel_codes[m*code_stride + k*256].  Only the first ceil(count/16) words of a bucket's 256-word
+ * area are written (unused bits of the last one are 0), the rest is left untouched: the message
+ * of a bucket is 32 + 4096 + 2*count bits.  count == 0 gives scale 0, threshold 0, no codes.
+ * thresholds may be NULL. */
+int qa_quantize_pack_selected(const qa_layout* layout, const float* g, int64_t g_stride,
+                              const uint32_t* ind, int64_t ind_stride, uint32_t* sel_codes,
+                              uint32_t* counts, float* scales, float* thresholds, void* stream);
+
+/* S^{-1} (Algorithm 1, server: "Decode ... to get Q(g^(m))"): writes the dense 2-bit codes of
+ * qa_layout for all M workers, codes_out[m*code_stride + w], w < ceil(d/16): the j-th marked
+ * component of a bucket gets the j-th code of its area, unmarked components get 0.  With the
+ * scales from qa_quantize_pack_selected the result feeds qa_aggregate_unpack / qa_step_*. */
+int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                       const uint32_t* sel_codes, uint32_t* codes_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,6 +17,7 @@ QA_REQUANT_NONE, QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL = 0, 1, 2
 QA_THRESH_GIVEN = 1
 QA_OP_QUANTIZE, QA_OP_STEP, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE = 1, 2, 3, 4
 QA_DENSE, QA_CSR = 0, 1
+QA_METHOD_QCMD, QA_METHOD_QRDA = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -74,6 +75,12 @@ _lib.qa_step_qcmd.argtypes = [C.POINTER(Layout), _vp, _vp, _vp, _vp, _vp, C.c_fl
                               C.c_float, C.c_int, _vp, _sz, _vp]
 _lib.qa_step_qrda.argtypes = [C.POINTER(Layout), _vp, _vp, _vp, _vp, _vp, C.c_int64, C.c_float,
                               C.c_float, C.c_float, C.c_int, _vp, _sz, _vp]
+_lib.qa_indicator.argtypes = [C.POINTER(Layout), C.c_int, _vp, C.c_int64, _vp, _vp, _vp, C.c_int64,
+                              C.c_float, C.c_float, C.c_float, _vp, C.c_int64, _vp]
+_lib.qa_indicator_or.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp]
+_lib.qa_quantize_pack_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, C.c_int64, _vp, _vp,
+                                           _vp, _vp, _vp]
+_lib.qa_decode_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp]
 
 
 def _p(t):
@@ -144,3 +151,26 @@ def qa_step_qrda(layout, codes, scales, x, G, z, t, eta, lam, delta, requant, ws
     _check(_lib.qa_step_qrda(C.byref(layout), _p(codes), _p(scales), _p(x), _p(G), _p(z), t, eta,
                              lam, delta, requant, _p(ws), _nbytes(ws), _stream(stream)),
            "qa_step_qrda")
+
+
+def qa_indicator(layout, method, g, g_stride, x, G, z, t, eta, lam, delta, ind_out, ind_stride,
+                 stream=None):
+    _check(_lib.qa_indicator(C.byref(layout), method, _p(g), g_stride, _p(x), _p(G), _p(z), t, eta, lam,
+                             delta, _p(ind_out), ind_stride, _stream(stream)), "qa_indicator")
+
+
+def qa_indicator_or(layout, ind, ind_stride, ind_syn_out, stream=None):
+    _check(_lib.qa_indicator_or(C.byref(layout), _p(ind), ind_stride, _p(ind_syn_out), _stream(stream)),
+           "qa_indicator_or")
+
+
+def qa_quantize_pack_selected(layout, g, g_stride, ind, ind_stride, sel_codes, counts, scales,
+                              thresholds, stream=None):
+    _check(_lib.qa_quantize_pack_selected(C.byref(layout), _p(g), g_stride, _p(ind), ind_stride,
+                                          _p(sel_codes), _p(counts), _p(scales), _p(thresholds),
+                                          _stream(stream)), "qa_quantize_pack_selected")
+
+
+def qa_decode_selected(layout, ind, ind_stride, sel_codes, codes_out, stream=None):
+    _check(_lib.qa_decode_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes), _p(codes_out),
+                                   _stream(stream)), "qa_decode_selected")

@@ -1,0 +1,297 @@
+// Indicator, selection and sparse encoding (Section 3.2, equations "select" and "ind";
+// Algorithm 1 worker block and server decode; Encode paragraph: 32 + d + 2k bits) for gfx950.
+//
+//   indicator_kernel          : I_i = (x_i != 0) or (x^_i != 0), x^ being the worker's own QCMD/QRDA
+//                               update from its full-precision gradient; one bit per coordinate,
+//                               formed with wave ballots (64 consecutive coordinates per ballot).
+//   quantize_selected_kernel  : per 4096-tile, threshold/scale over the marked components only and
+//                               their 2-bit codes compacted in index order (block prefix sum of
+//                               the per-thread popcounts, LDS bit stream).
+//   decode_selected_kernel    : S^{-1}: spreads the compact codes back to the dense 2-bit layout
+//                               that the fused steps read.
+#include "qa_common.h"
+
+namespace qa {
+
+struct SelArgs {
+  const float* g; int64_t g_stride;
+  const float* x; const float* G; const float* z;
+  uint32_t* ind; const uint32_t* ind_in; int64_t ind_stride;
+  uint32_t* sel_codes; const uint32_t* sel_in; uint32_t* dense; int64_t code_stride;
+  uint32_t* counts; float* scales; float* thresholds; int64_t scale_stride;
+  int64_t d, W, NW;            // coordinates, dense code words, indicator words
+  int M, method;
+  float eta, lam_eta, delta, t_lam, thr_coef;
+};
+
+// The worker's own would-be parameter from gradient component g (same operation order as the
+// update of the fused steps).
+__device__ __forceinline__ float local_update(const SelArgs& a, float g, float x, float G, float z) {
+  const float g2 = g * g;
+  const float Gh = G + g2;
+  const float H = a.delta + sqrtf(Gh);
+  if (a.method == 0) {
+    const float step = (a.eta * g) / H;
+    const float u = x - step;
+    const float tau = a.lam_eta / H;
+    const float r = fabsf(u) - tau;
+    return r > 0.0f ? copysignf(r, u) : 0.0f;
+  }
+  const float zh = z + g;
+  const float r = fabsf(zh) - a.t_lam;
+  const float mag = (a.eta * r) / H;
+  return r > 0.0f ? -copysignf(mag, zh) : 0.0f;
+}
+
+// wave w of the work-group owns coordinates [w*1024, (w+1)*1024) of the tile, lane l the
+// coordinates j*64 + l (j = 0..15): each ballot is 64 consecutive indicator bits.
+__global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t base = (int64_t)blockIdx.x * kTile + wave * 1024;
+  float x[16], G[16], z[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int64_t c = base + j * 64 + lane;
+    const bool in = c < a.d;
+    x[j] = in ? a.x[c] : 0.0f;
+    G[j] = in ? a.G[c] : 0.0f;
+    z[j] = (in && a.method == 1) ? a.z[c] : 0.0f;
+  }
+  for (int m = 0; m < a.M; ++m) {
+    const float* g = a.g + (int64_t)m * a.g_stride;
+    uint32_t* out = a.ind + (int64_t)m * a.ind_stride;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int64_t c = base + j * 64 + lane;
+      bool mark = false;
+      if (c < a.d) {
+        const float xh = local_update(a, g[c], x[j], G[j], z[j]);
+        mark = x[j] != 0.0f || xh != 0.0f;
+      }
+      const uint64_t bits = __ballot(mark);
+      const int64_t w0 = (base + j * 64) / 32;
+      if (lane < 2 && w0 + lane < a.NW) out[w0 + lane] = (uint32_t)(bits >> (32 * lane));
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void indicator_or_kernel(SelArgs a) {
+  const int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (w >= a.NW) return;
+  uint32_t v = 0u;
+  for (int m = 0; m < a.M; ++m) v |= a.ind_in[(int64_t)m * a.ind_stride + w];
+  a.ind[w] = v;
+}
+
+// Exclusive prefix sum of `v` over the 256 threads and the total; two barriers.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* lds_w, uint32_t* total) {
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  uint32_t incl = v;
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += o;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) lds_w[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t s = lds_w[w];
+    if (w < wave) before += s;
+    tot += s;
+  }
+  *total = tot;
+  return before + incl - v;
+}
+
+// the 16 indicator bits of coordinates [16t, 16t+16) of tile `tile`
+__device__ __forceinline__ uint32_t mask16_of(const uint32_t* ind, int64_t NW, int64_t tile, int t) {
+  const int64_t w = tile * (kTile / 32) + t / 2;
+  const uint32_t word = w < NW ? ind[w] : 0u;
+  return (word >> (16 * (t & 1))) & 0xFFFFu;
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_selected_kernel(SelArgs a) {
+  __shared__ uint32_t stream[kTileWords + 1];
+  __shared__ uint32_t lds_w[kWaves];
+  __shared__ double lds_s1[kWaves];
+  __shared__ double lds_s2[kWaves];
+  __shared__ uint32_t lds_c[kWaves];
+  const int t = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const float* g = a.g + (int64_t)m * a.g_stride;
+  const uint32_t mask = mask16_of(a.ind_in + (int64_t)m * a.ind_stride, a.NW, tile, t);
+  const int64_t i0 = tile * kTile + 16 * (int64_t)t;
+
+  float v[16];
+  if (i0 + 16 <= a.d) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 f = *reinterpret_cast<const float4*>(g + i0 + 4 * q);
+      v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = (i0 + j < a.d) ? g[i0 + j] : 0.0f;
+  }
+  stream[t] = 0u;
+  if (t == 0) stream[kTileWords] = 0u;
+
+  double s1 = 0.0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j)
+    if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
+  const uint32_t cnt = (uint32_t)__popc(mask);
+  uint32_t K;
+  const uint32_t before = block_exclusive_scan(cnt, lds_w, &K);
+  const double S1 = block_sum_f64(s1, lds_s1);
+  const float Delta = K ? threshold_from_sum(S1, a.thr_coef, (int64_t)K) : 0.0f;
+
+  double s2 = 0.0;
+  uint32_t c2 = 0, bits = 0, pos = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    if ((mask >> j) & 1u) {
+      const float av = fabsf(v[j]);
+      if (av > Delta) { s2 += (double)av; ++c2; }
+      bits |= ternary_field(v[j], Delta) << (2 * pos);
+      ++pos;
+    }
+  }
+  // append this thread's 2*cnt bits at bit 2*before of the tile's compact stream
+  if (cnt) {
+    const uint32_t word = before / 16, sh = 2 * (before % 16);
+    atomicOr(&stream[word], bits << sh);
+    if (sh && (2 * cnt + sh > 32)) atomicOr(&stream[word + 1], bits >> (32 - sh));
+  }
+  s2 = wave_sum_f64(s2);
+  c2 = wave_sum_u32(c2);
+  if ((t % kWave) == 0) { lds_s2[t / kWave] = s2; lds_c[t / kWave] = c2; }
+  __syncthreads();
+  const uint32_t nwords = (K + 15) / 16;
+  if ((uint32_t)t < nwords) (a.sel_codes + (int64_t)m * a.code_stride)[tile * kTileWords + t] = stream[t];
+  if (t == 0) {
+    const double S2 = (lds_s2[0] + lds_s2[1]) + (lds_s2[2] + lds_s2[3]);
+    const uint32_t C = lds_c[0] + lds_c[1] + lds_c[2] + lds_c[3];
+    a.counts[(int64_t)m * a.scale_stride + tile] = K;
+    a.scales[(int64_t)m * a.scale_stride + tile] = scale_from_sum(S2, C);
+    if (a.thresholds) a.thresholds[(int64_t)m * a.scale_stride + tile] = Delta;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void decode_selected_kernel(SelArgs a) {
+  __shared__ uint32_t stream[kTileWords + 1];
+  __shared__ uint32_t lds_w[kWaves];
+  const int t = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const uint32_t mask = mask16_of(a.ind_in + (int64_t)m * a.ind_stride, a.NW, tile, t);
+  const uint32_t cnt = (uint32_t)__popc(mask);
+  uint32_t K;
+  const uint32_t before = block_exclusive_scan(cnt, lds_w, &K);
+  const uint32_t nwords = (K + 15) / 16;
+  stream[t] = (uint32_t)t < nwords ? (a.sel_in + (int64_t)m * a.code_stride)[tile * kTileWords + t] : 0u;
+  if (t == 0) stream[kTileWords] = 0u;
+  __syncthreads();
+  const uint32_t word = before / 16, sh = 2 * (before % 16);
+  uint32_t win = stream[word] >> sh;
+  if (sh) win |= stream[word + 1] << (32 - sh);
+  uint32_t out = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    if ((mask >> j) & 1u) { out |= (win & 3u) << (2 * j); win >>= 2; }
+  }
+  const int64_t w = tile * kTileWords + t;
+  if (w < a.W) (a.dense + (int64_t)m * a.code_stride)[w] = out;
+}
+
+static int check_select_layout(const qa_layout* L) {
+  int rc = check_layout(L);
+  if (rc != QA_OK) return rc;
+  // thresholds/scales per 4096-tile, or one per vector when the vector is a single tile
+  if (L->bucket == kTile || (L->bucket == 0 && L->d <= kTile)) return QA_OK;
+  return QA_ERR_UNSUPPORTED;
+}
+
+static SelArgs base_args(const qa_layout* L) {
+  SelArgs a{};
+  a.d = L->d; a.W = words_of(L->d); a.NW = (L->d + 31) / 32; a.M = L->M;
+  a.code_stride = L->code_stride; a.scale_stride = L->scale_stride; a.thr_coef = L->thr_coef;
+  return a;
+}
+
+}  // namespace qa
+
+extern "C" int qa_indicator(const qa_layout* layout, int method, const float* g, int64_t g_stride,
+                            const float* x, const float* G, const float* z, int64_t t, float eta,
+                            float lambda, float delta, uint32_t* ind_out, int64_t ind_stride,
+                            void* stream) {
+  using namespace qa;
+  int rc = check_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (method != 0 && method != 1) return QA_ERR_INVALID_ARG;
+  if (!g || !x || !G || !ind_out || (method == 1 && !z)) return QA_ERR_INVALID_ARG;
+  if (g_stride < layout->d || ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
+  if (!(eta > 0.0f) || !(lambda >= 0.0f) || !(delta > 0.0f) || (method == 1 && t < 1))
+    return QA_ERR_INVALID_ARG;
+  if (!aligned(g, 4) || !aligned(x, 4) || !aligned(G, 4) || !aligned(z, 4) || !aligned(ind_out, 4))
+    return QA_ERR_ALIGNMENT;
+  SelArgs a = base_args(layout);
+  a.method = method; a.g = g; a.g_stride = g_stride; a.x = x; a.G = G; a.z = z;
+  a.ind = ind_out; a.ind_stride = ind_stride;
+  a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta; a.t_lam = (float)t * lambda;
+  hipLaunchKernelGGL(indicator_kernel, dim3((unsigned)tiles_of(layout->d)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), a);
+  return launch_status();
+}
+
+extern "C" int qa_indicator_or(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                               uint32_t* ind_syn_out, void* stream) {
+  using namespace qa;
+  int rc = check_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!ind || !ind_syn_out || ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
+  if (!aligned(ind, 4) || !aligned(ind_syn_out, 4)) return QA_ERR_ALIGNMENT;
+  SelArgs a = base_args(layout);
+  a.ind_in = ind; a.ind_stride = ind_stride; a.ind = ind_syn_out;
+  hipLaunchKernelGGL(indicator_or_kernel, dim3((unsigned)((a.NW + kThreads - 1) / kThreads)),
+                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  return launch_status();
+}
+
+extern "C" int qa_quantize_pack_selected(const qa_layout* layout, const float* g, int64_t g_stride,
+                                         const uint32_t* ind, int64_t ind_stride, uint32_t* sel_codes,
+                                         uint32_t* counts, float* scales, float* thresholds,
+                                         void* stream) {
+  using namespace qa;
+  int rc = check_select_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!g || !ind || !sel_codes || !counts || !scales) return QA_ERR_INVALID_ARG;
+  if (g_stride < layout->d || (g_stride % 4) != 0 || ind_stride < (layout->d + 31) / 32)
+    return QA_ERR_INVALID_ARG;
+  if (!aligned(g, 16) || !aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(counts, 4) ||
+      !aligned(scales, 4) || !aligned(thresholds, 4))
+    return QA_ERR_ALIGNMENT;
+  SelArgs a = base_args(layout);
+  a.g = g; a.g_stride = g_stride; a.ind_in = ind; a.ind_stride = ind_stride;
+  a.sel_codes = sel_codes; a.counts = counts; a.scales = scales; a.thresholds = thresholds;
+  hipLaunchKernelGGL(quantize_selected_kernel, dim3((unsigned)tiles_of(layout->d), (unsigned)layout->M),
+                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  return launch_status();
+}
+
+extern "C" int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                                  const uint32_t* sel_codes, uint32_t* codes_out, void* stream) {
+  using namespace qa;
+  int rc = check_select_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!ind || !sel_codes || !codes_out || ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
+  if (!aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(codes_out, 4)) return QA_ERR_ALIGNMENT;
+  SelArgs a = base_args(layout);
+  a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = sel_codes; a.dense = codes_out;
+  hipLaunchKernelGGL(decode_selected_kernel, dim3((unsigned)tiles_of(layout->d), (unsigned)layout->M),
+                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  return launch_status();
+}

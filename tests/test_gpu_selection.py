@@ -1,0 +1,161 @@
+"""Parity of the indicator / selection / sparse-encoding kernels with the oracle (bit-exact:
+indicator bits, counts, compact codes, decoded dense codes; scales and thresholds equal), and
+an end-to-end run of Algorithm 1 WITH selection on the sparse synthetic problem, where the
+message size 32*nb + d + 2k bits is accounted."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2208_05631_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2208_05631_amd as qa
+    from gpu_util import DEV, dev, host, workspace
+
+
+def rand_state(rng, d, nz=0.3):
+    x = (rng.standard_normal(d) * 0.1 * (rng.random(d) < nz)).astype(np.float32)
+    G = (rng.random(d) * 1e-3).astype(np.float32)
+    z = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    return x, G, z
+
+
+@pytest.mark.parametrize("method", [0, 1])
+@pytest.mark.parametrize("d,M", [(1, 1), (33, 2), (1000, 3), (4096, 2), (70001, 4)])
+def test_indicator_matches_oracle(method, d, M):
+    rng = np.random.default_rng(d + M + method)
+    x, G, z = rand_state(rng, d)
+    g = (rng.standard_normal((M, d)) * rng.choice([1e-3, 0.05], (M, d))).astype(np.float32)
+    eta, lam, delta, t = 0.1, 0.01, 1e-8, 5
+    NW = (d + 31) // 32
+    ind = torch.full((M, NW + 3), -1, dtype=torch.int32, device=DEV)
+    L = qa.Layout.make(d, M, 0 if d <= 4096 else 4096)
+    qa.qa_indicator(L, method, dev(g), d, dev(x), dev(G), dev(z), t, eta, lam, delta, ind, NW + 3)
+    syn = torch.zeros(NW, dtype=torch.int32, device=DEV)
+    qa.qa_indicator_or(L, ind, NW + 3, syn)
+    torch.cuda.synchronize()
+    got = host(ind).view(np.uint32)
+    ref = np.stack([oracle.indicator(method, g[m], x, G, z, t, eta, lam, delta) for m in range(M)])
+    assert np.array_equal(got[:, :NW], ref)
+    assert np.all(got[:, NW:] == 0xFFFFFFFF)                         # padding untouched
+    assert np.array_equal(host(syn).view(np.uint32), oracle.indicator_or(ref, d))
+    frac = np.unpackbits(ref.view(np.uint8)).mean()
+    assert d < 100 or 0.02 < frac < 0.98
+
+
+def random_indicator(rng, M, d, p):
+    bits = rng.random((M, d)) < p
+    NW = (d + 31) // 32
+    ind = np.zeros((M, NW), np.uint32)
+    for m in range(M):
+        idx = np.nonzero(bits[m])[0]
+        np.bitwise_or.at(ind[m], idx // 32, (np.uint32(1) << (idx % 32).astype(np.uint32)))
+    return ind
+
+
+@pytest.mark.parametrize("d,M,bucket,p", [(1, 1, 0, 1.0), (1000, 2, 0, 0.3), (4096, 2, 4096, 0.5),
+                                          (4097, 2, 4096, 0.01), (70001, 3, 4096, 0.2),
+                                          (70001, 2, 4096, 1.0), (20000, 2, 4096, 0.0)])
+def test_quantize_selected_and_decode_match_oracle(d, M, bucket, p):
+    rng = np.random.default_rng(d + M)
+    g = (rng.standard_normal((M, d)) * 1e-2).astype(np.float32)
+    ind = random_indicator(rng, M, d, p)
+    if d > 8192:
+        ind[0, 128:256] = 0                                          # an empty bucket
+    L = qa.Layout.make(d, M, bucket)
+    nb, W, NW = L.n_buckets, L.words, (d + 31) // 32
+    gs = ((d + 3) // 4) * 4
+    gp = np.zeros((M, gs), np.float32); gp[:, :d] = g
+    sel = torch.full((M, L.code_stride), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((M, nb), dtype=torch.int32, device=DEV)
+    sc = torch.full((M, nb), -1.0, dtype=torch.float32, device=DEV)
+    th = torch.full((M, nb), -1.0, dtype=torch.float32, device=DEV)
+    dense = torch.full((M, L.code_stride), -1, dtype=torch.int32, device=DEV)
+    ind_d = dev(ind.view(np.int32))
+    qa.qa_quantize_pack_selected(L, dev(gp), gs, ind_d, NW, sel, cnt, sc, th)
+    qa.qa_decode_selected(L, ind_d, NW, sel, dense)
+    torch.cuda.synchronize()
+    sel_h, cnt_h = host(sel).view(np.uint32), host(cnt).view(np.uint32)
+    area = 256 if bucket else (d + 15) // 16
+    for m in range(M):
+        o_sel, o_cnt, o_sc, o_th = oracle.quantize_selected(g[m], ind[m], bucket=bucket)
+        assert np.array_equal(cnt_h[m], o_cnt)
+        assert np.array_equal(host(sc)[m], o_sc) and np.array_equal(host(th)[m], o_th)
+        for k in range(nb):
+            nwk = (int(o_cnt[k]) + 15) // 16
+            lo = k * area
+            assert np.array_equal(sel_h[m, k * 256: k * 256 + nwk], o_sel[lo: lo + nwk]), (m, k)
+            untouched = sel_h[m, k * 256 + nwk: min((k + 1) * 256, L.code_stride)]
+            assert np.all(untouched == 0x5A5A5A5A)                   # only ceil(count/16) words written
+        assert np.array_equal(host(dense).view(np.uint32)[m, :W], oracle.decode_selected(ind[m], o_sel, d, bucket=bucket))
+
+
+def test_unsupported_bucket_sizes_are_refused():
+    L = qa.Layout.make(100000, 2, 1024)
+    t = torch.zeros(8, dtype=torch.int32, device=DEV)
+    with pytest.raises(qa.QaError) as e:
+        qa.qa_decode_selected(L, t, 100000, t, t)
+    assert e.value.code == -5
+
+
+@pytest.mark.parametrize("method", ["qcmd", "qrda"])
+def test_training_with_selection_matches_oracle(method):
+    """Algorithm 1 with the indicator: local gradients -> indicator -> Q(S(g, I)) -> decode ->
+    fused step, on the CSR stand-in (d = 2^18 here), T = 25.  Both sides run the whole loop."""
+    d, M, B, b, T = 1 << 18, 8, 128, 4096, 25
+    eta, lam, delta = 0.1, 1e-4, 1e-8
+    p = synth.csr_problem(n=1 << 13, d=d, nnz_per_row=50, M=M, seed=3)
+    L = qa.Layout.make(d, M, b)
+    nb, NW, gs = L.n_buckets, (d + 31) // 32, d
+    A, ip, ix, y = dev(p.vals), dev(p.indptr), dev(p.indices), dev(p.y)
+    x, G, z = (torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(3))
+    g = torch.zeros((M, gs), dtype=torch.float32, device=DEV)
+    ind = torch.zeros((M, NW), dtype=torch.int32, device=DEV)
+    sel = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    dense = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((M, nb), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((M, nb), dtype=torch.float32, device=DEV)
+    ws_g = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR))
+    ox, oG, oz = (np.zeros(d, np.float32) for _ in range(3))
+    mth = qa.QA_METHOD_QCMD if method == "qcmd" else qa.QA_METHOD_QRDA
+    bits_sparse = bits_dense = 0
+    for t in range(1, T + 1):
+        rows = synth.minibatch_rows(p.n, M, B, t, 3)
+        qa.qa_local_grad_batched(qa.QA_CSR, A, ip, ix, p.n, d, y, dev(rows), B, M, x, g, gs, None, ws_g)
+        qa.qa_indicator(L, mth, g, gs, x, G, z, t, eta, lam, delta, ind, NW)
+        qa.qa_quantize_pack_selected(L, g, gs, ind, NW, sel, cnt, sc, None)
+        qa.qa_decode_selected(L, ind, NW, sel, dense)
+        if method == "qcmd":
+            qa.qa_step_qcmd(L, dense, sc, x, G, z, eta, lam, delta, 0, None)
+        else:
+            qa.qa_step_qrda(L, dense, sc, x, G, z, t, eta, lam, delta, 0, None)
+        # oracle side
+        og = np.stack([oracle.local_grad_csr(p.vals, p.indptr, p.indices, d, p.y, rows[m], ox)[0] for m in range(M)])
+        oind = np.stack([oracle.indicator(mth, og[m], ox, oG, oz, t, eta, lam, delta) for m in range(M)])
+        ocodes = np.zeros((M, L.words), np.uint32)
+        oscales = np.zeros((M, nb), np.float32)
+        k_total = 0
+        for m in range(M):
+            s_, c_, sc_, _ = oracle.quantize_selected(og[m], oind[m], bucket=b)
+            ocodes[m] = oracle.decode_selected(oind[m], s_, d, bucket=b)
+            oscales[m] = sc_
+            k_total += int(c_.sum())
+        if method == "qcmd":
+            oracle.step_qcmd(ocodes, oscales, d, b, ox, oG, oz, eta, lam, delta)
+        else:
+            oracle.step_qrda(ocodes, oscales, d, b, ox, oG, oz, t, eta, lam, delta)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(ind).view(np.uint32), oind), f"indicator, step {t}"
+        assert int(host(cnt).view(np.uint32).sum()) == k_total
+        assert np.array_equal(host(dense).view(np.uint32)[:, :L.words], ocodes), f"codes, step {t}"
+        assert np.array_equal(host(x) == 0, ox == 0), f"zero set, step {t}"
+        for nm, a_, o_ in (("x", x, ox), ("G", G, oG), ("z", z, oz)):
+            assert np.allclose(host(a_), o_, rtol=1e-5, atol=0), f"{nm}, step {t}"
+        bits_sparse += M * (32 * nb + d) + 2 * k_total
+        bits_dense += M * (32 * nb + 2 * d)
+    print(f"{method}: message bits with selection / dense = {bits_sparse / bits_dense:.3f}; "
+          f"nnz(x) = {(ox != 0).sum()}")
+    assert bits_sparse < 0.6 * bits_dense
