@@ -41,6 +41,8 @@ WORKLOADS = {
     # synthetic stand-ins for the paper's linear-model experiments
     "tiny_train": dict(train="dense", d=1000, n=4096, M=4, B=64, bucket=0, lam=1e-3),
     "sparse_train": dict(train="csr", d=1 << 20, n=1 << 16, M=16, B=256, bucket=4096, lam=1e-4),
+    # worker/server side of the sparse encoding: indicator -> Q(S(g, I)) -> decode
+    "select": dict(select=True, d=1 << 28, M=8, bucket=4096),
     "small": dict(d=1 << 22, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
 }
 
@@ -100,6 +102,56 @@ def train_bench(args, wl, qa, synth, torch, np, dev):
     print(json.dumps(out))
 
 
+def select_bench(args, wl, qa, synth, torch, np, dev):
+    """Indicator, selected quantize+pack and decode for M workers; each kernel timed alone."""
+    d, M, bucket = wl["d"], wl["M"], wl["bucket"]
+    eta, lam, delta = 0.1, 1e-4, 1e-8
+    L = qa.Layout.make(d, M, bucket)
+    nb, NW = L.n_buckets, (d + 31) // 32
+    g = torch.empty((M, d), dtype=torch.float32, device=dev)
+    for m in range(M):
+        synth.grad_laplace_sparse(d, m, 1, device=dev, out=g[m])
+    gen = torch.Generator(device=dev); gen.manual_seed(5)
+    x = torch.randn(d, generator=gen, device=dev) * (torch.rand(d, generator=gen, device=dev) < 0.02)
+    G = torch.rand(d, generator=gen, device=dev) * 1e-6
+    z = torch.zeros(d, dtype=torch.float32, device=dev)
+    ind = torch.zeros((M, NW), dtype=torch.int32, device=dev)
+    sel = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    dense = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    cnt = torch.zeros((M, nb), dtype=torch.int32, device=dev)
+    sc = torch.zeros((M, nb), dtype=torch.float32, device=dev)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    t_ind = timed(lambda: qa.qa_indicator(L, qa.QA_METHOD_QCMD, g, d, x, G, z, 1, eta, lam, delta, ind, NW))
+    t_q = timed(lambda: qa.qa_quantize_pack_selected(L, g, d, ind, NW, sel, cnt, sc, None))
+    t_dec = timed(lambda: qa.qa_decode_selected(L, ind, NW, sel, dense))
+    k = int(cnt.sum().item())
+    frac = k / (M * d)
+    by = {"indicator": (4 * M + 8 + M / 8) * d, "quantize_selected": M * d * (4 + 1 / 8) + k / 4,
+          "decode": M * d * (1 / 8 + 1 / 4) + k / 4}
+    ms = {"indicator": t_ind, "quantize_selected": t_q, "decode": t_dec}
+    out = {"metric": "sparse encoding kernels: worker-coordinates/s (indicator + Q(S(g,I)) + decode)",
+           "value": M * d / ((t_ind + t_q + t_dec) * 1e-3), "unit": "worker-coordinates/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_ind + t_q + t_dec,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": f"select: d={d}, M={M}, bucket={bucket}, selected fraction {frac:.4f}"},
+           "kernels": {n: {"ms": ms[n], "algorithmic_GBps": by[n] / (ms[n] * 1e-3) / 1e9,
+                           "frac_of_peak": by[n] / (ms[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS} for n in ms},
+           "message_bits_vs_dense": (M * (32 * nb + d) + 2 * k) / (M * (32 * nb + 2 * d))}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,6 +179,8 @@ def main():
     wl = WORKLOADS[args.workload]
     if "train" in wl:
         return train_bench(args, wl, qa, synth, torch, np, dev)
+    if "select" in wl:
+        return select_bench(args, wl, qa, synth, torch, np, dev)
     d, M, bucket, lam = wl["d"], wl["M"], wl["bucket"], wl["lam"]
     eta, delta = 0.1, 1e-8
     W = (d + 15) // 16
