@@ -76,6 +76,11 @@ def _declare(L):
     L.orc_indicator_or.argtypes = [_u32p, _i64, _i32, _i64, _u32p]
     L.orc_quantize_selected.argtypes = [_f32p, _u32p, _i64, _i64, _f32, _u32p, _u32p, _f32p, _f32p]
     L.orc_decode_selected.argtypes = [_u32p, _u32p, _i64, _i64, _u32p]
+    L.orc_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+    L.orc_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, _i64]
+    L.orc_uniform.restype = _f32
+    L.orc_quantize_stochastic.argtypes = [_f32p, _i64, _i64, C.c_uint64, C.c_uint32, C.c_uint32, _i8p,
+                                          _f32p]
     L.orc_local_grad_dense.argtypes = [_f32p, _i64, _i64, _f32p, _i32p, _i32, _f32p, _f32p,
                                        C.POINTER(_f32)]
     L.orc_local_grad_csr.argtypes = [_f32p, _i64p, _i32p, _i64, _i64, _f32p, _i32p, _i32, _f32p,
@@ -310,3 +315,36 @@ def decode_selected(ind, sel_codes, d, bucket=0):
     out = np.empty(n_words(d), np.uint32)
     lib().orc_decode_selected(ind, sel_codes, d, bucket, out)
     return out
+
+
+# ---- stochastic ternary quantizer ---------------------------------------------------------
+
+def philox4x32_10(ctr, key):
+    out = np.empty(4, np.uint32)
+    lib().orc_philox4x32_10(np.asarray(ctr, np.uint32), np.asarray(key, np.uint32), out)
+    return out
+
+
+def uniform(seed, step, m, i):
+    return float(lib().orc_uniform(seed, step, m, i))
+
+
+def quantize_stochastic(v, bucket=0, seed=0, step=0, m=0):
+    """-> (codes int8[d], scales f32[nb]) of the max-norm stochastic ternary quantizer."""
+    v = np.ascontiguousarray(v, np.float32)
+    code = np.empty(v.size, np.int8)
+    sc = np.empty(n_buckets(v.size, bucket), np.float32)
+    lib().orc_quantize_stochastic(v, v.size, bucket, seed, step, m, code, sc)
+    return code, sc
+
+
+def quantize_pack_stochastic(g, bucket=0, seed=0, step=0):
+    g = np.ascontiguousarray(g, np.float32)
+    M, d = g.shape
+    codes = np.zeros((M, n_words(d)), np.uint32)
+    scales = np.zeros((M, n_buckets(d, bucket)), np.float32)
+    for m in range(M):
+        c, s = quantize_stochastic(g[m], bucket, seed, step, m)
+        codes[m] = pack(c)
+        scales[m] = s
+    return codes, scales

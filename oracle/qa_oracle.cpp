@@ -401,6 +401,59 @@ void orc_decode_selected(const uint32_t* ind, const uint32_t* sel_codes, int64_t
   pack_codes(code.data(), d, dense_words);
 }
 
+// ---- stochastic ternary quantizer (the "ternary" baseline of Section 4.1: TernGrad, Wen et
+//      al. 2017, which the paper cites and does not restate) with a counter-based generator ----
+//
+// Per bucket: s = max_i |v_i|;  component i is kept with probability |v_i| / s and then coded
+// as sign(v_i), so that E[s * code_i] = v_i.  The uniform numbers come from Philox4x32-10
+// (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11), keyed by
+// the 64-bit seed, counter = (i/4 low, i/4 high, worker, step); component i takes output word
+// i%4.  u = (r >> 8) * 2^-24 in [0,1); keep iff u < |v_i|/s with the division in binary32.
+void orc_philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t out[4]) {
+  uint32_t c[4] = {ctr_in[0], ctr_in[1], ctr_in[2], ctr_in[3]};
+  uint32_t k0 = key_in[0], k1 = key_in[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c[0];
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c[2];
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0;
+    const uint32_t n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+    const uint32_t n3 = (uint32_t)p0;
+    c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+  }
+  for (int j = 0; j < 4; ++j) out[j] = c[j];
+}
+
+// The uniform number of component i of worker m at step `step`.
+float orc_uniform(uint64_t seed, uint32_t step, uint32_t m, int64_t i) {
+  const uint64_t j = (uint64_t)i / 4;
+  const uint32_t ctr[4] = {(uint32_t)j, (uint32_t)(j >> 32), m, step};
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t r[4];
+  orc_philox4x32_10(ctr, key, r);
+  return (float)(r[i % 4] >> 8) * 0x1p-24f;
+}
+
+void orc_quantize_stochastic(const float* v, int64_t d, int64_t bucket, uint64_t seed, uint32_t step,
+                             uint32_t m, int8_t* code_out, float* scale_out) {
+  const int64_t b = bucket_len(d, bucket), nb = n_buckets(d, bucket);
+  for (int64_t k = 0; k < nb; ++k) {
+    const int64_t lo = k * b, hi = std::min(lo + b, d);
+    float s = 0.0f;
+    for (int64_t i = lo; i < hi; ++i) {
+      const float a = std::fabs(v[i]);
+      if (a > s) s = a;                        // NaN never wins
+    }
+    scale_out[k] = s;
+    for (int64_t i = lo; i < hi; ++i) {
+      const float p = std::fabs(v[i]) / s;     // 0/0 = NaN when the bucket is all zero: never kept
+      const bool keep = orc_uniform(seed, step, m, i) < p;
+      code_out[i] = keep ? (v[i] < 0.0f ? -1 : 1) : 0;
+    }
+  }
+}
+
 // ---- local gradient: L1-regularised logistic regression (Section 4.1) ----------------
 //
 // Loss of one sample (a, y), y in {-1,+1}:  log(1 + exp(-y * a.x)); the minibatch

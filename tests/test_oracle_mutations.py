@@ -48,6 +48,15 @@ MUTATIONS = [
     ("indicator_qrda_ignores_local_gradient", "const float zh = z[i] + g[i];", "const float zh = z[i];"),
     ("selection_takes_unmarked", "if ((ind[i / 32] >> (i % 32)) & 1u) sel.push_back(g[i]);",
      "if (!((ind[i / 32] >> (i % 32)) & 1u)) sel.push_back(g[i]);"),
+    ("philox_key_not_bumped", "if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }",
+     "if (round > 1) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }"),
+    ("philox_nine_rounds", "for (int round = 0; round < 10; ++round) {", "for (int round = 0; round < 9; ++round) {"),
+    ("stochastic_keep_probability_inverted", "const bool keep = orc_uniform(seed, step, m, i) < p;",
+     "const bool keep = orc_uniform(seed, step, m, i) >= p;"),
+    ("stochastic_scale_is_mean_not_max", "      if (a > s) s = a;                        // NaN never wins",
+     "      s += a / (float)(hi - lo);"),
+    ("stochastic_same_draw_for_all_workers", "const uint32_t ctr[4] = {(uint32_t)j, (uint32_t)(j >> 32), m, step};",
+     "const uint32_t ctr[4] = {(uint32_t)j, (uint32_t)(j >> 32), 0, step};"),
     ("decode_advances_on_every_coordinate", "        ++j;\n      }\n  }\n  pack_codes(code.data(), d, dense_words);",
      "      }\n      ++j;\n  }\n  pack_codes(code.data(), d, dense_words);"),
 ]
@@ -66,6 +75,7 @@ def test_pins_catch_planted_mistake(name, old, new):
         env = dict(os.environ, QA_ORACLE_LIB=so)
         r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                             os.path.join(ROOT, "tests", "test_oracle_pins.py"),
-                            os.path.join(ROOT, "tests", "test_oracle_selection_pins.py")],
+                            os.path.join(ROOT, "tests", "test_oracle_selection_pins.py"),
+                            os.path.join(ROOT, "tests", "test_oracle_stochastic_pins.py")],
                            env=env, cwd=ROOT, capture_output=True, text=True)
         assert r.returncode != 0, f"pins did not notice: {name}"
