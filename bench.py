@@ -43,6 +43,8 @@ WORKLOADS = {
     "sparse_train": dict(train="csr", d=1 << 20, n=1 << 16, M=16, B=256, bucket=4096, lam=1e-4),
     # worker/server side of the sparse encoding: indicator -> Q(S(g, I)) -> decode
     "select": dict(select=True, d=1 << 28, M=8, bucket=4096),
+    # stochastic (TernGrad/Philox) quantizer against the threshold quantizer on the same input
+    "stochastic": dict(stoch=True, d=1 << 28, M=4, bucket=4096),
     "small": dict(d=1 << 22, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
 }
 
@@ -152,6 +154,41 @@ def select_bench(args, wl, qa, synth, torch, np, dev):
     print(json.dumps(out))
 
 
+def stochastic_bench(args, wl, qa, synth, torch, np, dev):
+    d, M, bucket = wl["d"], wl["M"], wl["bucket"]
+    L = qa.Layout.make(d, M, bucket)
+    g = torch.empty((M, d), dtype=torch.float32, device=dev)
+    for m in range(M):
+        synth.grad_gaussian_biased(d, m, 1, device=dev, out=g[m])
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    scales = torch.zeros((M, L.scale_stride), dtype=torch.float32, device=dev)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    t_s = timed(lambda: qa.qa_quantize_pack_stochastic(L, g, d, codes, scales, 7, 1))
+    t_t = timed(lambda: qa.qa_quantize_pack(L, g, d, codes, scales, None, 0, None))
+    gb = 4.25 * M * d / 1e9
+    out = {"metric": "stochastic ternary quantize+pack: worker-coordinates/s",
+           "value": M * d / (t_s * 1e-3), "unit": "worker-coordinates/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_s, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"stochastic: d={d}, M={M}, bucket={bucket}, dense Gaussian gradients"},
+           "kernels": {"stochastic": {"ms": t_s, "algorithmic_GBps": gb / (t_s * 1e-3),
+                                      "frac_of_peak": gb / (t_s * 1e-3) / HBM_PEAK_GBPS},
+                       "threshold": {"ms": t_t, "algorithmic_GBps": gb / (t_t * 1e-3),
+                                     "frac_of_peak": gb / (t_t * 1e-3) / HBM_PEAK_GBPS}}}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +218,8 @@ def main():
         return train_bench(args, wl, qa, synth, torch, np, dev)
     if "select" in wl:
         return select_bench(args, wl, qa, synth, torch, np, dev)
+    if "stoch" in wl:
+        return stochastic_bench(args, wl, qa, synth, torch, np, dev)
     d, M, bucket, lam = wl["d"], wl["M"], wl["bucket"], wl["lam"]
     eta, delta = 0.1, 1e-8
     W = (d + 15) // 16

@@ -140,6 +140,18 @@ int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, 
                      float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
                      void* stream);
 
+/* Stochastic ternary quantizer, the "ternary" comparison of Section 4.1 (TernGrad, cited in
+ * Section 2; the paper does not restate it): per bucket s = max|v_i|, component i is kept with
+ * probability |v_i|/s and coded as its sign, so that E[s*code_i] = v_i.  Same outputs and
+ * encoding as qa_quantize_pack (codes, scales; no thresholds).  The uniform numbers are
+ * Philox4x32-10 (Salmon et al., SC'11) with key = seed, counter = (i/4 low, i/4 high, worker
+ * m, step), component i taking output word i%4, u = (r >> 8) * 2^-24, kept iff u < |v_i|/s in
+ * binary32: the result is a pure function of (g, seed, step).  bucket must be 0 or >= 4096
+ * (QA_ERR_UNSUPPORTED otherwise); no workspace. */
+int qa_quantize_pack_stochastic(const qa_layout* layout, const float* g, int64_t g_stride,
+                                uint32_t* codes, float* scales, uint64_t seed, uint32_t step,
+                                void* stream);
+
 /* Server average (equation SynQ_t of Section 3.1; "Average the quantized gradients" in
  * Algorithm 1), materialised:  gbar_out[i] = (1/M) sum_m scales[m][i/bucket] * code[m][i],
  * sum and division in binary64, rounded once. */

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL, QA_REQUANT_NONE, QA_THRESH_GIVEN, Layout, QaError,
     lib_path, qa_aggregate_unpack, qa_local_grad, qa_local_grad_batched, qa_quantize_pack, qa_step_qcmd, qa_step_qrda,
     qa_strerror, qa_version, qa_workspace_bytes, qa_indicator, qa_indicator_or,
-    qa_quantize_pack_selected, qa_decode_selected,
+    qa_quantize_pack_selected, qa_decode_selected, qa_quantize_pack_stochastic,
 )

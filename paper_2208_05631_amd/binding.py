@@ -81,6 +81,8 @@ _lib.qa_indicator_or.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp]
 _lib.qa_quantize_pack_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, C.c_int64, _vp, _vp,
                                            _vp, _vp, _vp]
 _lib.qa_decode_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp]
+_lib.qa_quantize_pack_stochastic.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, C.c_uint64,
+                                             C.c_uint32, _vp]
 
 
 def _p(t):
@@ -174,3 +176,8 @@ def qa_quantize_pack_selected(layout, g, g_stride, ind, ind_stride, sel_codes, c
 def qa_decode_selected(layout, ind, ind_stride, sel_codes, codes_out, stream=None):
     _check(_lib.qa_decode_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes), _p(codes_out),
                                    _stream(stream)), "qa_decode_selected")
+
+
+def qa_quantize_pack_stochastic(layout, g, g_stride, codes, scales, seed, step, stream=None):
+    _check(_lib.qa_quantize_pack_stochastic(C.byref(layout), _p(g), g_stride, _p(codes), _p(scales),
+                                            seed, step, _stream(stream)), "qa_quantize_pack_stochastic")

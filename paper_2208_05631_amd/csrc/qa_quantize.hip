@@ -347,6 +347,122 @@ __global__ __launch_bounds__(kThreads) void quantize_scale_finalize_kernel(Quant
     a.scales[(int64_t)m * a.scale_stride + k] = scale_from_sum(s, (uint64_t)c);
 }
 
+// ---- stochastic ternary quantizer (TernGrad: max-norm scale, keep probability |v|/s) ----------
+//
+// Uniform numbers: Philox4x32-10 keyed by the 64-bit seed, counter (j low, j high, worker, step)
+// with j the index of the float4 group, so one generator call serves the four components of a
+// group (component i takes output word i % 4).  u = (r >> 8) * 2^-24; keep iff u < |v| / s with
+// the division in binary32.  The max is exact, so its reduction order is free.
+
+struct StochArgs {
+  QuantArgs q;
+  uint32_t seed_lo, seed_hi, step;
+  int pass;                 // two-pass path: 0 = bucket max, 1 = codes
+};
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ float tile_abs_max(const float v[4][4]) {
+  float s = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { const float a = fabsf(v[j][e]); s = a > s ? a : s; }   // NaN never wins
+  return s;
+}
+
+__device__ __forceinline__ float wave_max_f32(float s) {
+  float o;
+  o = __int_as_float(dpp_i32<kDppQuadXor1>(__float_as_int(s))); s = o > s ? o : s;
+  o = __int_as_float(dpp_i32<kDppQuadXor2>(__float_as_int(s))); s = o > s ? o : s;
+  o = __int_as_float(dpp_i32<kDppRowHalfMirror>(__float_as_int(s))); s = o > s ? o : s;
+  o = __int_as_float(dpp_i32<kDppRowMirror>(__float_as_int(s))); s = o > s ? o : s;
+  float r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), 0));
+#pragma unroll
+  for (int l = 16; l < 64; l += 16) {
+    o = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), l));
+    r = o > r ? o : r;
+  }
+  return r;
+}
+
+// codes of the tile for scale s; element (j, e) of thread t is vector index base + 4*(j*256+t)+e
+__device__ __forceinline__ void stochastic_codes(const StochArgs& a, const float v[4][4], float s,
+                                                 int64_t tile, int m) {
+  const int t = threadIdx.x;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint64_t grp = (uint64_t)tile * (kTile / 4) + (uint64_t)(j * kThreads + t);
+    uint32_t r[4];
+    philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), (uint32_t)m, a.step, a.seed_lo, a.seed_hi, r);
+    uint32_t b = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float u = (float)(r[e] >> 8) * 0x1p-24f;
+      const float p = fabsf(v[j][e]) / s;
+      const uint32_t f = u < p ? (v[j][e] < 0.0f ? 3u : 1u) : 0u;
+      b |= f << (2 * e);
+    }
+    uint32_t w = b << (8 * (t & 3));
+    w |= (uint32_t)dpp_i32<kDppQuadXor1>((int)w);
+    w |= (uint32_t)dpp_i32<kDppQuadXor2>((int)w);
+    if ((t & 3) == j) mine = w;
+  }
+  const int64_t widx = tile * kTileWords + (t & 3) * 64 + (t >> 2);
+  if (widx < a.q.W) (a.q.codes + (int64_t)m * a.q.code_stride)[widx] = mine;
+}
+
+// bucket == tile (4096, or one scale per vector with d <= 4096): one pass
+__global__ __launch_bounds__(kThreads) void quantize_stochastic_tile_kernel(StochArgs a) {
+  __shared__ float lds_m[kWaves];
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  float v[4][4];
+  load_tile(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
+  float s = wave_max_f32(tile_abs_max(v));
+  if ((threadIdx.x % kWave) == 0) lds_m[threadIdx.x / kWave] = s;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) s = lds_m[w] > s ? lds_m[w] : s;
+  if (threadIdx.x == 0) a.q.scales[(int64_t)m * a.q.scale_stride + tile] = s;
+  stochastic_codes(a, v, s, tile, m);
+}
+
+// bucket > 4096 or one scale per large vector: pass 0 folds tile maxima into scales[] (which
+// the host zeroed) with integer atomic max on the bit pattern of the non-negative float;
+// pass 1 reads the finished scale and writes the codes.
+__global__ __launch_bounds__(kThreads) void quantize_stochastic_twopass_kernel(StochArgs a) {
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t k = tile / a.q.tiles_per_bucket;
+  float v[4][4];
+  load_tile(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
+  float* sc = a.q.scales + (int64_t)m * a.q.scale_stride + k;
+  if (a.pass == 0) {
+    const float s = wave_max_f32(tile_abs_max(v));
+    if ((threadIdx.x % kWave) == 0) atomicMax(reinterpret_cast<unsigned int*>(sc), __float_as_uint(s));
+  } else {
+    stochastic_codes(a, v, *sc, tile, m);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void zero_scales_kernel(float* scales, int64_t stride, int64_t nb) {
+  const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (k < nb) scales[(int64_t)blockIdx.y * stride + k] = 0.0f;
+}
+
 // ---- host side -------------------------------------------------------------------------------
 
 static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -420,4 +536,39 @@ extern "C" int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t
     return QA_ERR_ALIGNMENT;
   return quantize_launch(layout, g, g_stride, codes, scales, thresholds, flags, ws, ws_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+extern "C" int qa_quantize_pack_stochastic(const qa_layout* layout, const float* g, int64_t g_stride,
+                                           uint32_t* codes, float* scales, uint64_t seed,
+                                           uint32_t step, void* stream_) {
+  using namespace qa;
+  int rc = check_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!g || !codes || !scales) return QA_ERR_INVALID_ARG;
+  if (g_stride < layout->d || (g_stride % 4) != 0) return QA_ERR_INVALID_ARG;
+  if (layout->bucket != 0 && layout->bucket < kTile) return QA_ERR_UNSUPPORTED;
+  if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(scales, 4)) return QA_ERR_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  StochArgs a{};
+  a.q.g = g; a.q.g_stride = g_stride; a.q.d = layout->d; a.q.W = words_of(layout->d);
+  a.q.codes = codes; a.q.code_stride = layout->code_stride;
+  a.q.scales = scales; a.q.scale_stride = layout->scale_stride;
+  a.q.ntiles = tiles_of(layout->d);
+  a.q.nb = buckets_of(layout->d, layout->bucket);
+  a.seed_lo = (uint32_t)seed; a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
+  if (a.q.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+  const dim3 block(kThreads), grid((unsigned)a.q.ntiles, (unsigned)layout->M);
+  if (layout->bucket == kTile || a.q.ntiles == 1) {
+    hipLaunchKernelGGL(quantize_stochastic_tile_kernel, grid, block, 0, stream, a);
+    return launch_status();
+  }
+  a.q.tiles_per_bucket = layout->bucket ? layout->bucket / kTile : a.q.ntiles;
+  hipLaunchKernelGGL(zero_scales_kernel, dim3((unsigned)((a.q.nb + kThreads - 1) / kThreads),
+                                              (unsigned)layout->M), block, 0, stream, scales,
+                     layout->scale_stride, a.q.nb);
+  a.pass = 0;
+  hipLaunchKernelGGL(quantize_stochastic_twopass_kernel, grid, block, 0, stream, a);
+  a.pass = 1;
+  hipLaunchKernelGGL(quantize_stochastic_twopass_kernel, grid, block, 0, stream, a);
+  return launch_status();
 }

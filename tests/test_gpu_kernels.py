@@ -330,3 +330,36 @@ def test_local_grad_batched_equals_per_worker_calls_and_oracle(csr):
         assert np.allclose(gg[m, :d], ref[m][0], rtol=1e-6, atol=1e-12)
         assert ll[m] == pytest.approx(ref[m][1], rel=1e-6)
     assert (gg[:, :d] == np.stack([r[0] for r in ref])).mean() > 0.999
+
+
+# ------------------------------------------------------------------ stochastic ternary quantizer
+
+@pytest.mark.parametrize("d,M,bucket", [(1, 1, 0), (1000, 3, 0), (4096, 2, 4096), (70001, 3, 4096),
+                                        (70001, 2, 16384), (70001, 2, 0), (300001, 2, 4096)])
+def test_stochastic_quantizer_matches_oracle(d, M, bucket):
+    g = make_grad("gauss" if d % 2 else "laplace_sparse", M, d, seed=d + 3)
+    if d > 9000:
+        g[0, 4096:8192] = 0.0                       # an all-zero tile: scale 0, nothing kept
+    seed, step = 0x1234567811223344, 17
+    oc, osc = oracle.quantize_pack_stochastic(g, bucket=bucket, seed=seed, step=step)
+    L = qa.Layout.make(d, M, bucket)
+    gs = ((d + 3) // 4) * 4
+    gp = np.zeros((M, gs), np.float32); gp[:, :d] = g
+    codes = torch.full((M, L.code_stride), -1, dtype=torch.int32, device=DEV)
+    scales = torch.full((M, L.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+    qa.qa_quantize_pack_stochastic(L, dev(gp), gs, codes, scales, seed, step)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(scales)[:, :L.n_buckets], osc)
+    assert np.array_equal(host(codes).view(np.uint32)[:, :L.words], oc)
+    c2 = torch.zeros_like(codes)
+    qa.qa_quantize_pack_stochastic(L, dev(gp), gs, c2, scales, seed, step + 1)
+    torch.cuda.synchronize()
+    assert d < 100 or not torch.equal(c2, codes)    # another step, other draws
+
+
+def test_stochastic_quantizer_refuses_small_buckets():
+    L = qa.Layout.make(10000, 1, 256)
+    t = torch.zeros(16, dtype=torch.float32, device=DEV)
+    with pytest.raises(qa.QaError) as e:
+        qa.qa_quantize_pack_stochastic(L, t, 10000, t, t, 1, 1)
+    assert e.value.code == -5
