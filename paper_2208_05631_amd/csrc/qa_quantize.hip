@@ -365,10 +365,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 #pragma unroll
   for (int round = 0; round < 10; ++round) {
     if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
-    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;      // one 32x32->64 multiply each
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c0 = n0; c1 = (uint32_t)p1; c2 = n2; c3 = (uint32_t)p0;
   }
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
@@ -401,20 +401,33 @@ __device__ __forceinline__ float wave_max_f32(float s) {
 __device__ __forceinline__ void stochastic_codes(const StochArgs& a, const float v[4][4], float s,
                                                  int64_t tile, int m) {
   const int t = threadIdx.x;
+  const float rs = __builtin_amdgcn_rcpf(s);
   uint32_t mine = 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint64_t grp = (uint64_t)tile * (kTile / 4) + (uint64_t)(j * kThreads + t);
     uint32_t r[4];
     philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), (uint32_t)m, a.step, a.seed_lo, a.seed_hi, r);
-    uint32_t b = 0;
+    // keep iff u < fl(|v| / s).  The hardware reciprocal gives |v|/s to a few ulp; only when u
+    // lies within that margin of it (probability ~1e-6) is the correctly rounded quotient needed.
+    float u[4], av[4];
+    bool keep[4], unsure = false;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float u = (float)(r[e] >> 8) * 0x1p-24f;
-      const float p = fabsf(v[j][e]) / s;
-      const uint32_t f = u < p ? (v[j][e] < 0.0f ? 3u : 1u) : 0u;
-      b |= f << (2 * e);
+      u[e] = (float)(r[e] >> 8) * 0x1p-24f;
+      av[e] = fabsf(v[j][e]);
+      const float pa = av[e] * rs;
+      const float lo = pa * 0.999999f, hi = pa * 1.000001f;
+      keep[e] = u[e] < lo;
+      unsure |= !(u[e] < lo) && !(u[e] > hi);            // also NaN/Inf products
     }
+    if (__any(unsure)) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) keep[e] = u[e] < av[e] / s;
+    }
+    uint32_t b = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) b |= (keep[e] ? (v[j][e] < 0.0f ? 3u : 1u) : 0u) << (2 * e);
     uint32_t w = b << (8 * (t & 3));
     w |= (uint32_t)dpp_i32<kDppQuadXor1>((int)w);
     w |= (uint32_t)dpp_i32<kDppQuadXor2>((int)w);
