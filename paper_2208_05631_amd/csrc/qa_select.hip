@@ -43,6 +43,54 @@ __device__ __forceinline__ float local_update(const SelArgs& a, float g, float x
   return r > 0.0f ? -copysignf(mag, zh) : 0.0f;
 }
 
+// Whether the worker's own update is non-zero, decided without square root or division whenever
+// that is provably the same as evaluating local_update():
+//   QCMD with x == 0:  x^ != 0  <=>  fl(a/H) > fl(b/H),  a = |fl(eta*g)|, b = fl(lambda*eta).
+//     Correctly rounded division by the same H > 0 is monotone, so a <= b gives "zero"; and if
+//     a > b*(1+2^-21) while b/H is a normal number, the two quotients differ by more than their
+//     rounding errors (2^-24 relative each), which gives "non-zero".
+//   QRDA:  r = fl(|fl(z+g)| - t*lambda) is formed exactly as in the update; r <= 0 gives "zero",
+//     and r > 0 gives "non-zero" unless (eta*r)/H underflows to 0.
+//   H <= delta + max(1, G + g*g) bounds the quotients away from the subnormal range.
+// Everything else (ties within the margin, possible underflow, NaN/Inf) is left undecided and
+// the caller evaluates the closed form itself.
+__device__ __forceinline__ bool quick_indicator(const SelArgs& a, float g, float x, float G, float z,
+                                                bool* mark) {
+  *mark = true;
+  if (x != 0.0f) return true;
+  const float s2 = G + g * g;
+  if (!(s2 >= 0.0f)) return false;                       // NaN or invalid accumulator
+  const float h_ub = a.delta + (s2 > 1.0f ? s2 : 1.0f);
+  if (a.method == 0) {
+    const float av = fabsf(a.eta * g), b = a.lam_eta;
+    *mark = av > b;
+    return av <= b || (av > b * 1.0000005f && b >= h_ub * 0x1p-100f);
+  }
+  const float zh = z + g;
+  const float r = fabsf(zh) - a.t_lam;
+  *mark = r > 0.0f;
+  return !(r > 0.0f) || a.eta * r >= h_ub * 0x1p-100f;
+}
+
+// Rare path: the 1024 coordinates of one wave for worker m, all through the closed form.
+__device__ __forceinline__ void indicator_slab_exact(const SelArgs& a, int m, int64_t base, int lane) {
+  const float* g = a.g + (int64_t)m * a.g_stride;
+  uint32_t* out = a.ind + (int64_t)m * a.ind_stride;
+#pragma unroll 1
+  for (int j = 0; j < 16; ++j) {
+    const int64_t c = base + j * 64 + lane;
+    bool mark = false;
+    if (c < a.d) {
+      const float x = a.x[c];
+      const float xh = local_update(a, g[c], x, a.G[c], a.method == 1 ? a.z[c] : 0.0f);
+      mark = x != 0.0f || xh != 0.0f;
+    }
+    const uint64_t bits = __ballot(mark);
+    const int64_t w0 = (base + j * 64) / 32;
+    if (lane < 2 && w0 + lane < a.NW) out[w0 + lane] = (uint32_t)(bits >> (32 * lane));
+  }
+}
+
 // wave w of the work-group owns coordinates [w*1024, (w+1)*1024) of the tile, lane l the
 // coordinates j*64 + l (j = 0..15): each ballot is 64 consecutive indicator bits.
 __global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
@@ -52,26 +100,33 @@ __global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
     const int64_t c = base + j * 64 + lane;
-    const bool in = c < a.d;
-    x[j] = in ? a.x[c] : 0.0f;
-    G[j] = in ? a.G[c] : 0.0f;
-    z[j] = (in && a.method == 1) ? a.z[c] : 0.0f;
+    const int64_t cc = c < a.d ? c : a.d - 1;    // clamped: loads stay unconditional
+    x[j] = a.x[cc];
+    G[j] = a.G[cc];
+    z[j] = a.method == 1 ? a.z[cc] : 0.0f;
   }
   for (int m = 0; m < a.M; ++m) {
     const float* g = a.g + (int64_t)m * a.g_stride;
     uint32_t* out = a.ind + (int64_t)m * a.ind_stride;
+    bool undecided = false;
+    float gv[16];                                // all 16 loads in flight before any use
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int64_t c = base + j * 64 + lane;
+      gv[j] = g[c < a.d ? c : a.d - 1];
+    }
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const int64_t c = base + j * 64 + lane;
       bool mark = false;
-      if (c < a.d) {
-        const float xh = local_update(a, g[c], x[j], G[j], z[j]);
-        mark = x[j] != 0.0f || xh != 0.0f;
-      }
+      const bool ok = quick_indicator(a, gv[j], x[j], G[j], z[j], &mark);
+      undecided |= (c < a.d) && !ok;
+      mark = mark && (c < a.d);
       const uint64_t bits = __ballot(mark);
       const int64_t w0 = (base + j * 64) / 32;
       if (lane < 2 && w0 + lane < a.NW) out[w0 + lane] = (uint32_t)(bits >> (32 * lane));
     }
+    if (__any(undecided)) indicator_slab_exact(a, m, base, lane);   // overwrites the slab's words
   }
 }
 

@@ -46,6 +46,46 @@ def test_indicator_matches_oracle(method, d, M):
     assert d < 100 or 0.02 < frac < 0.98
 
 
+@pytest.mark.parametrize("method", [0, 1])
+@pytest.mark.parametrize("lam", [0.0, 0.01])
+def test_indicator_at_decision_boundaries_matches_oracle(method, lam):
+    """Gradients within a few ulps of the zero/non-zero boundary of the worker's own update,
+    huge accumulators (quotients underflow), non-finite values: the division-free decision
+    must hand these to the closed form."""
+    rng = np.random.default_rng(3 + method)
+    d, M, eta, delta, t = 8192, 2, 0.1, 1e-8, 7
+    x = np.zeros(d, np.float32)
+    x[::97] = 0.5
+    G = (rng.random(d) * 1e-3).astype(np.float32)
+    G[1::5] = np.float32(1e30)
+    G[2::11] = np.float32(3e38)
+    z = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    g = np.empty((M, d), np.float32)
+    for m in range(M):
+        if method == 0:
+            base = np.full(d, lam, np.float32)                       # |eta*g| ~ lambda*eta
+        else:
+            base = (np.sign(rng.standard_normal(d)) * (t * lam) - z).astype(np.float32)   # |z+g| ~ t*lambda
+        ulps = rng.integers(-3, 4, d)
+        v = base.copy()
+        for k in range(1, 4):
+            v = np.where(ulps >= k, np.nextafter(v, np.float32(np.inf)), v)
+            v = np.where(ulps <= -k, np.nextafter(v, np.float32(-np.inf)), v)
+        v[3::13] *= rng.choice([-1.0, 1.0], v[3::13].size).astype(np.float32)
+        v[5::101] = np.float32(1e-38)
+        v[7::211] = np.nan
+        v[9::223] = np.inf
+        v[11::227] = np.float32(1e20)
+        g[m] = v
+    NW = d // 32
+    L = qa.Layout.make(d, M, 4096)
+    ind = torch.zeros((M, NW), dtype=torch.int32, device=DEV)
+    qa.qa_indicator(L, method, dev(g), d, dev(x), dev(G), dev(z), t, eta, lam, delta, ind, NW)
+    torch.cuda.synchronize()
+    ref = np.stack([oracle.indicator(method, g[m], x, G, z, t, eta, lam, delta) for m in range(M)])
+    assert np.array_equal(host(ind).view(np.uint32), ref)
+
+
 def random_indicator(rng, M, d, p):
     bits = rng.random((M, d)) < p
     NW = (d + 31) // 32
