@@ -58,6 +58,10 @@ extern "C" {
 
 /* flags of qa_quantize_pack */
 #define QA_THRESH_GIVEN 1u /* thresholds[] is an INPUT; only scales and codes are computed   */
+#define QA_THRESH_EXACT 2u /* thresholds[] is an OUTPUT holding the exact least-squares optimum
+                              found by ranking (Section 3.4) instead of the 0.75*mean|v| rule;
+                              needs bucket == 4096 or (bucket == 0 and d <= 4096), and a
+                              non-NULL thresholds array                                      */
 
 /* operations for qa_workspace_bytes */
 #define QA_OP_QUANTIZE 1
@@ -135,6 +139,9 @@ int qa_local_grad_batched(int format, const float* A_or_vals, const int64_t* ind
  * Writes codes[m*code_stride + w] for every w < ceil(d/16), scales[m*scale_stride + k] and,
  * if thresholds != NULL and QA_THRESH_GIVEN is not set, thresholds[m*scale_stride + k].
  * With QA_THRESH_GIVEN thresholds must be non-NULL and is read instead of computed.
+ * With QA_THRESH_EXACT each bucket's threshold is the largest magnitude NOT kept by the k that
+ * maximises (sum of the k largest |v|)^2 / k (equal magnitudes are never split), so that the
+ * strict comparisons keep exactly the optimal set; scale and codes follow as usual.
  * g_stride >= d and a multiple of 4.  ws: qa_workspace_bytes(layout, QA_OP_QUANTIZE). */
 int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, uint32_t* codes,
                      float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,

@@ -59,6 +59,7 @@ def _declare(L):
     L.orc_quantize.argtypes = [_f32p, _i64, _i64, _f32, _i8p, _f32p, _vp, _vp]
     L.orc_exact_threshold.argtypes = [_f32p, _i64, C.POINTER(_f64), C.POINTER(_f64),
                                       C.POINTER(_f64), C.POINTER(_i64)]
+    L.orc_exact_thresholds.argtypes = [_f32p, _i64, _i64, _f32p]
     L.orc_pack.argtypes = [_i8p, _i64, _u32p]
     L.orc_unpack.argtypes = [_u32p, _i64, _i8p]
     L.orc_quantize_pack.argtypes = [_f32p, _i64, _i64, _i32, _i64, _f32, _u32p, _i64, _f32p,
@@ -138,6 +139,14 @@ def exact_threshold(v):
     a, s, o, k = _f64(), _f64(), _f64(), _i64()
     lib().orc_exact_threshold(v, v.size, C.byref(a), C.byref(s), C.byref(o), C.byref(k))
     return a.value, s.value, o.value, k.value
+
+
+def exact_thresholds(v, bucket=0):
+    """Per bucket, the strict threshold whose kept set {|v| > Delta} is the least-squares optimum."""
+    v = np.ascontiguousarray(v, np.float32)
+    th = np.empty(n_buckets(v.size, bucket), np.float32)
+    lib().orc_exact_thresholds(v, v.size, bucket, th)
+    return th
 
 
 def pack(code):

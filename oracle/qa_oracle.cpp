@@ -204,6 +204,25 @@ void orc_exact_threshold(const float* v, int64_t n, double* kept_min_out, double
   *kept_out = best_k;
 }
 
+// The optimal threshold as a number to compare with strictly: per bucket, the largest magnitude
+// that is NOT kept by the optimum above (the (k*+1)-th largest; 0 if everything non-zero is
+// kept or the bucket is all zero), so that {|v_i| > Delta} is exactly the optimal kept set.
+void orc_exact_thresholds(const float* v, int64_t d, int64_t bucket, float* thresh_out) {
+  const int64_t b = bucket_len(d, bucket), nb = n_buckets(d, bucket);
+  for (int64_t k = 0; k < nb; ++k) {
+    const int64_t lo = k * b, n = std::min(b, d - lo);
+    double kept_min, s, obj;
+    int64_t kept;
+    orc_exact_threshold(v + lo, n, &kept_min, &s, &obj, &kept);
+    float Delta = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {           // largest magnitude below the kept ones
+      const float a = std::fabs(v[lo + i]);
+      if ((double)a < kept_min && a > Delta) Delta = a;
+    }
+    thresh_out[k] = Delta;
+  }
+}
+
 // ---- encoding -------------------------------------------------------------------
 
 void orc_pack(const int8_t* code, int64_t d, uint32_t* words) { pack_codes(code, d, words); }

@@ -260,6 +260,168 @@ __global__ __launch_bounds__(kThreads) void quantize_tile_kernel(QuantArgs a) {
   }
 }
 
+// ---- exact optimal threshold by ranking (Section 3.4: "rank the components of the gradient
+//      and treat them as potential thresholds") for one 4096-tile ---------------------------------
+//
+// |v| of the tile is sorted in descending order (bitonic network on the bit patterns, which
+// order like the non-negative floats), prefix sums are formed in binary64, and the k that
+// maximises (sum of the k largest)^2 / k is taken among the k that do not split equal
+// magnitudes.  The threshold written is the largest magnitude NOT kept (0 if none), to be
+// compared with strictly like the approximate one.
+//
+// The network runs on 16 keys per thread held in registers.  Position i of the 4096 has 12 bits;
+// a thread owns the 16 positions that differ in four of them ("free" bits) and the other eight
+// come from its thread index.  Three ownerships cover every stage: free bits 0-3, 4-7 or 8-11.
+// A stage that exchanges across bit b is done by the ownership whose free bits hold b, as a
+// register min/max; keys move between ownerships through LDS (two buffers, used alternately, so
+// one barrier per move is enough: a buffer is rewritten only after the barrier that follows
+// every thread's last read of it).  Rows of 16 are padded to 17 words against bank conflicts.
+constexpr int kSortPitch = kTile + kTile / 16;
+
+template <int OWN> __device__ __forceinline__ int sort_position(int t, int r) {
+  if (OWN == 0) return t * 16 + r;
+  if (OWN == 1) return (t & 15) | (r << 4) | ((t >> 4) << 8);
+  return t | (r << 8);
+}
+
+// The stages of phase P (blocks of 2^P positions, alternately descending and ascending) that
+// exchange across the lowest NST free bits of ownership OWN, highest first.  A block that must
+// come out ascending is sorted descending on complemented keys.
+template <int OWN, int P, int NST>
+__device__ __forceinline__ void sort_stages(uint32_t (&e)[16], int t) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    e[r] ^= (uint32_t)(-((sort_position<OWN>(t, r) >> P) & 1));
+#pragma unroll
+  for (int lb = NST - 1; lb >= 0; --lb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (!(r & (1 << lb))) {
+        const uint32_t x = e[r], y = e[r | (1 << lb)];
+        e[r] = x > y ? x : y;
+        e[r | (1 << lb)] = x > y ? y : x;
+      }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    e[r] ^= (uint32_t)(-((sort_position<OWN>(t, r) >> P) & 1));
+}
+
+template <int FROM, int TO>
+__device__ __forceinline__ void sort_move(uint32_t (&e)[16], int t, uint32_t* buf) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = sort_position<FROM>(t, r);
+    buf[i + (i >> 4)] = e[r];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = sort_position<TO>(t, r);
+    e[r] = buf[i + (i >> 4)];
+  }
+}
+
+// Phase P of the network for P >= 5, entered and left in ownership 0.  n counts the moves made
+// so far and picks the buffer.
+template <int P>
+__device__ __forceinline__ void sort_phase(uint32_t (&e)[16], int t, uint32_t (*buf)[kSortPitch],
+                                           int& n) {
+  if constexpr (P > 8) {
+    sort_move<0, 2>(e, t, buf[n++ & 1]);
+    sort_stages<2, P, P - 8>(e, t);
+    sort_move<2, 1>(e, t, buf[n++ & 1]);
+    sort_stages<1, P, 4>(e, t);
+  } else {
+    sort_move<0, 1>(e, t, buf[n++ & 1]);
+    sort_stages<1, P, P - 4>(e, t);
+  }
+  sort_move<1, 0>(e, t, buf[n++ & 1]);
+  sort_stages<0, P, 4>(e, t);
+}
+
+__global__ __launch_bounds__(kThreads) void exact_threshold_kernel(QuantArgs a) {
+  __shared__ uint32_t buf[2][kSortPitch];
+  __shared__ uint32_t lds_first[kThreads];
+  __shared__ double lds_tot[kWaves];
+  __shared__ double lds_obj[kWaves];
+  __shared__ int lds_k[kWaves];
+  __shared__ float lds_next[kWaves];
+  const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  uint32_t e[16];                 // which 16 of the tile a thread starts with does not matter
+  {
+    float v[4][4];
+    load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) e[j * 4 + c] = __float_as_uint(fabsf(v[j][c]));
+  }
+  sort_stages<0, 1, 1>(e, t);
+  sort_stages<0, 2, 2>(e, t);
+  sort_stages<0, 3, 3>(e, t);
+  sort_stages<0, 4, 4>(e, t);
+  int n = 0;
+  sort_phase<5>(e, t, buf, n);
+  sort_phase<6>(e, t, buf, n);
+  sort_phase<7>(e, t, buf, n);
+  sort_phase<8>(e, t, buf, n);
+  sort_phase<9>(e, t, buf, n);
+  sort_phase<10>(e, t, buf, n);
+  sort_phase<11>(e, t, buf, n);
+  sort_phase<12>(e, t, buf, n);
+  // the thread now holds positions 16t .. 16t+15 of the descending order
+  lds_first[t] = e[0];
+  __syncthreads();
+  float av[17];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) av[j] = __uint_as_float(e[j]);
+  av[16] = t < kThreads - 1 ? __uint_as_float(lds_first[t + 1]) : 0.0f;
+  double run[16];
+  run[0] = (double)av[0];
+#pragma unroll
+  for (int j = 1; j < 16; ++j) run[j] = run[j - 1] + (double)av[j];
+  double incl = run[15];
+  for (int off = 1; off < kWave; off <<= 1) {
+    const double o = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += o;
+  }
+  if (lane == kWave - 1) lds_tot[wave] = incl;
+  __syncthreads();
+  double before = incl - run[15];
+  for (int w = 0; w < wave; ++w) before += lds_tot[w];
+  // best candidate of this thread (smallest k among equal objectives); k = 0: none
+  double best = -1.0;
+  int best_k = 0;
+  float best_next = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int k = 16 * t + j + 1;
+    if (av[j] > 0.0f && av[j] > av[j + 1]) {
+      const double r = before + run[j];
+      const double obj = r * r / (double)k;
+      if (obj > best) { best = obj; best_k = k; best_next = av[j + 1]; }
+    }
+  }
+  for (int off = 1; off < kWave; off <<= 1) {
+    const double o = __shfl_xor(best, off, kWave);
+    const int ok = __shfl_xor(best_k, off, kWave);
+    const float on = __shfl_xor(best_next, off, kWave);
+    if (o > best || (o == best && ok < best_k)) { best = o; best_k = ok; best_next = on; }
+  }
+  if (lane == 0) { lds_obj[wave] = best; lds_k[wave] = best_k; lds_next[wave] = best_next; }
+  __syncthreads();
+  if (t == 0) {
+    for (int w = 1; w < kWaves; ++w) {
+      const double o = lds_obj[w];
+      const int ok = lds_k[w];
+      if (o > best || (o == best && ok < best_k)) { best = o; best_k = ok; best_next = lds_next[w]; }
+    }
+    a.thresholds[(int64_t)m * a.scale_stride + tile] = best_k > 0 ? best_next : 0.0f;
+  }
+}
+
 // ---- bucket > 4096 or whole vector : two passes -----------------------------------------------
 
 // pass 1: part_sum[m][tile] = sum |v| over the tile
@@ -501,6 +663,12 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   const dim3 block(kThreads);
   if (a.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
   const dim3 grid_tiles((unsigned)a.ntiles, (unsigned)L->M);
+  if (flags & QA_THRESH_EXACT) {
+    // one ranking per tile: the tile must be the bucket
+    if (!(L->bucket == kTile || (L->bucket == 0 && a.ntiles == 1))) return QA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(exact_threshold_kernel, grid_tiles, block, 0, stream, a);
+    a.thresh_given = 1;                                  // the passes below read what it wrote
+  }
 
   if (L->bucket != 0 && L->bucket <= kTile) {
     a.log2b = ilog2(L->bucket);
@@ -542,8 +710,9 @@ extern "C" int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t
   int rc = check_layout(layout);
   if (rc != QA_OK) return rc;
   if (!g || !codes || !scales) return QA_ERR_INVALID_ARG;
-  if (flags & ~QA_THRESH_GIVEN) return QA_ERR_INVALID_ARG;
-  if ((flags & QA_THRESH_GIVEN) && !thresholds) return QA_ERR_INVALID_ARG;
+  if (flags & ~(QA_THRESH_GIVEN | QA_THRESH_EXACT)) return QA_ERR_INVALID_ARG;
+  if ((flags & QA_THRESH_GIVEN) && (flags & QA_THRESH_EXACT)) return QA_ERR_INVALID_ARG;
+  if ((flags & (QA_THRESH_GIVEN | QA_THRESH_EXACT)) && !thresholds) return QA_ERR_INVALID_ARG;
   if (g_stride < layout->d || (g_stride % 4) != 0) return QA_ERR_INVALID_ARG;
   if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(thresholds, 4))
     return QA_ERR_ALIGNMENT;

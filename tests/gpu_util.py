@@ -24,7 +24,7 @@ def workspace(nbytes):
 
 
 def gpu_quantize_pack(g, bucket, thr_coef=0.75, thresholds=None, code_stride=None,
-                      scale_stride=None, g_stride=None):
+                      scale_stride=None, g_stride=None, exact=False):
     """g: numpy f32 [M, d] -> (codes u32 [M, cs], scales [M, ss], thresholds [M, ss]) as numpy."""
     M, d = g.shape
     L = qa.Layout.make(d, M, bucket, thr_coef, code_stride, scale_stride)
@@ -39,6 +39,8 @@ def gpu_quantize_pack(g, bucket, thr_coef=0.75, thresholds=None, code_stride=Non
     if thresholds is not None:
         th[:, :L.n_buckets] = dev(np.asarray(thresholds, np.float32).reshape(M, -1))
         flags = qa.QA_THRESH_GIVEN
+    if exact:
+        flags = qa.QA_THRESH_EXACT
     ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE))
     qa.qa_quantize_pack(L, gd, gs, codes, scales, th, flags, ws)
     torch.cuda.synchronize()

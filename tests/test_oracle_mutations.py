@@ -40,6 +40,10 @@ MUTATIONS = [
     ("requantize_ignores_buckets", "requant == 1 ? bucket : 0, thr_coef, q.data());",
      "0, thr_coef, q.data());"),
     ("exact_threshold_objective", "double obj = run * run / (double)k;", "double obj = run / (double)k;"),
+    ("exact_thresholds_drop_the_smallest_kept", "if ((double)a < kept_min && a > Delta) Delta = a;",
+     "if ((double)a <= kept_min && a > Delta) Delta = a;"),
+    ("exact_thresholds_take_any_smaller_magnitude", "if ((double)a < kept_min && a > Delta) Delta = a;",
+     "if ((double)a < kept_min && Delta == 0.0f) Delta = a;"),
     ("csr_gradient_uses_row_position", "acc[indices[k]] += (double)coef[b] * (double)vals[k];",
      "acc[indices[k]] += (double)coef[b] * (double)vals[indptr[r]];"),
     ("indicator_needs_both", "if (x[i] != 0.0f || xh != 0.0f) ind_out", "if (x[i] != 0.0f && xh != 0.0f) ind_out"),

@@ -72,6 +72,28 @@ def test_exact_threshold_is_brute_force_optimum(seed):
 
 
 @pytest.mark.parametrize("seed", range(4))
+def test_exact_thresholds_realise_the_optimum_through_the_strict_quantizer(seed):
+    rng = np.random.default_rng(200 + seed)
+    d, b = 1300, 512
+    v = rng.standard_normal(d).astype(np.float32)
+    v[rng.random(d) < 0.3] = 0.0
+    v[10] = v[11] = v[12]                                    # equal magnitudes cannot be split
+    v[600:700] = 0.0
+    th = oracle.exact_thresholds(v, bucket=b)
+    code, sc, _ = oracle.quantize(v, bucket=b, thresholds=th)
+    for k in range(3):
+        piece = v[k * b:(k + 1) * b]
+        kept_min, s, obj, kk = oracle.exact_threshold(piece)
+        c = code[k * b:(k + 1) * b]
+        assert (c != 0).sum() == kk and np.array_equal(c != 0, np.abs(piece) >= kept_min)
+        assert sc[k] == pytest.approx(s, rel=1e-6)
+        _, s_a, cnt_a = oracle.threshold_scale(piece)        # never worse than the approximation
+        assert kk * float(sc[k]) ** 2 >= cnt_a * float(s_a) ** 2 * (1 - 1e-6)
+    assert oracle.exact_thresholds(np.zeros(5, np.float32))[0] == 0.0
+    assert oracle.exact_thresholds(np.array([2.0, -2.0, 2.0], np.float32))[0] == 0.0
+
+
+@pytest.mark.parametrize("seed", range(4))
 def test_approx_threshold_never_beats_exact(seed):
     rng = np.random.default_rng(100 + seed)
     v = (rng.standard_normal(5000) * rng.choice([0.1, 1.0, 5.0], 5000)).astype(np.float32)
