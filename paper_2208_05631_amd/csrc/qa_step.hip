@@ -8,10 +8,6 @@
 // gbar = (float)(acc / M), optionally re-quantizes gbar per bucket inside the tile, and applies
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
 #include <stdlib.h>
-#ifndef QA_EXP
-#define QA_EXP 0
-#endif
-
 #include "qa_common.h"
 
 namespace qa {
@@ -242,10 +238,6 @@ __device__ __forceinline__ void store_state(float* __restrict__ p, int64_t tile_
 // sums up, add.  Coordinate 4r+c of the thread's 16 sits in byte r of zq[c].
 __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t wc, uint32_t wd,
                                              const double* __restrict__ T, double acc[16]) {
-#if QA_EXP == 1
-  acc[0] += T[(wa ^ wb ^ wc ^ wd) & 0xFFu];
-  return;
-#endif
   const uint32_t xe = (wa & 0x33333333u) | ((wb & 0x33333333u) << 2);
   const uint32_t xo = ((wa >> 2) & 0x33333333u) | (wb & 0xCCCCCCCCu);
   const uint32_t ye = (wc & 0x33333333u) | ((wd & 0x33333333u) << 2);
@@ -293,11 +285,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     const int left = a.M;
 #pragma unroll
     for (int i = 0; i < kChunk; ++i)
-#if QA_EXP == 2
-      w[i] = (uint32_t)(tile * 977 + i * 31 + t) & 0x11111111u;
-#else
       w[i] = (FULL || i < left) ? stream_load(ctile + (int64_t)i * a.code_stride + tw) : 0u;
-#endif
   }
   State4 sG, sx, sz;
   if (MODE != kAggregate) {
