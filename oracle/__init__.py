@@ -73,6 +73,10 @@ def _declare(L):
                                 _vp, _f32, _f32, _f32, _i32]
     L.orc_step_qrda.argtypes = [_u32p, _i64, _f32p, _i64, _i64, _i32, _i64, _f32, _f32p, _f32p,
                                 _f32p, _i64, _f32, _f32, _f32, _i32]
+    L.orc_quantize_pack_segments.argtypes = [_f32p, _i64, _i64, _i32, _i64, _i64p, _i64p, _f32,
+                                             _u32p, _i64, _f32p, _vp, _i64]
+    L.orc_step_segments.argtypes = [_i32, _u32p, _i64, _f32p, _i64, _i64, _i32, _i64, _i64p, _i64p,
+                                    _f32, _f32p, _f32p, _vp, _i64, _f32, _f32, _f32, _i32]
     L.orc_indicator.argtypes = [_i32, _f32p, _i64, _f32p, _f32p, _vp, _i64, _f32, _f32, _f32, _u32p]
     L.orc_indicator_or.argtypes = [_u32p, _i64, _i32, _i64, _u32p]
     L.orc_quantize_selected.argtypes = [_f32p, _u32p, _i64, _i64, _f32, _u32p, _u32p, _f32p, _f32p]
@@ -246,6 +250,35 @@ def step_qrda(codes, scales, d, bucket, x, G, z, t, eta, lam, delta, requant=REQ
     _chk_state(x, G, z)
     lib().orc_step_qrda(codes, codes.shape[1], scales, scales.shape[1], d, codes.shape[0],
                         bucket, thr_coef, x, G, z, t, eta, lam, delta, requant)
+
+
+# ---- a list of tensors in one flat vector -------------------------------------------------
+
+def quantize_pack_segments(g, begin, length, thr_coef=0.75):
+    """g: f32[M, d]; tensor s = coordinates [begin[s], begin[s]+length[s]) ->
+    (codes u32[M, ceil(d/16)] with untouched words 0, scales f32[M, n_seg], thresholds)"""
+    g = np.ascontiguousarray(g, np.float32)
+    begin = np.ascontiguousarray(begin, np.int64)
+    length = np.ascontiguousarray(length, np.int64)
+    M, d = g.shape
+    codes = np.zeros((M, n_words(d)), np.uint32)
+    scales = np.zeros((M, max(begin.size, 1)), np.float32)
+    th = np.zeros_like(scales)
+    lib().orc_quantize_pack_segments(g, d, d, M, begin.size, begin, length, thr_coef, codes,
+                                     codes.shape[1], scales, _ptr(th), scales.shape[1])
+    return codes, scales, th
+
+
+def step_segments(method, codes, scales, d, begin, length, x, G, z, t, eta, lam, delta,
+                  requant=False, thr_coef=0.75):
+    codes = np.ascontiguousarray(codes, np.uint32)
+    scales = np.ascontiguousarray(scales, np.float32)
+    begin = np.ascontiguousarray(begin, np.int64)
+    length = np.ascontiguousarray(length, np.int64)
+    _chk_state(x, G, z)
+    lib().orc_step_segments(method, codes, codes.shape[1], scales, scales.shape[1], d,
+                            codes.shape[0], begin.size, begin, length, thr_coef, x, G, _ptr(z),
+                            t, eta, lam, delta, 1 if requant else 0)
 
 
 # ---- local gradient --------------------------------------------------------------------

@@ -334,6 +334,50 @@ void orc_step_qrda(const uint32_t* codes, int64_t code_stride, const float* scal
   orc_update_qrda(q.data(), d, x, G, z, t, eta, lambda, delta);
 }
 
+// ---- a list of parameter tensors in one flat vector (models such as the CNNs of Section 5.2,
+//      whose parameters are many tensors of very different sizes) --------------------------------
+//
+// Reading: the quantizer is applied to each tensor's gradient on its own (own threshold, own
+// scale), exactly as to a vector of that length.  Tensor s occupies coordinates
+// [begin[s], begin[s] + length[s]) of the flat vector; begin[s] is a multiple of 16 so that no
+// code word is shared; coordinates between tensors belong to no tensor: their code fields are 0
+// and the step leaves their state alone.  scales[m*scale_stride + s] is worker m's scale of
+// tensor s.  Every function below is the single-vector function applied slice by slice.
+void orc_quantize_pack_segments(const float* g, int64_t g_stride, int64_t d, int M, int64_t n_seg,
+                                const int64_t* begin, const int64_t* length, float thr_coef,
+                                uint32_t* codes, int64_t code_stride, float* scales,
+                                float* thresholds, int64_t scale_stride) {
+  (void)d;
+  for (int m = 0; m < M; ++m)
+    for (int64_t s = 0; s < n_seg; ++s) {
+      float* sc = scales + (int64_t)m * scale_stride + s;
+      float* th = thresholds ? thresholds + (int64_t)m * scale_stride + s : nullptr;
+      if (length[s] == 0) { *sc = 0.0f; if (th) *th = 0.0f; continue; }
+      orc_quantize_pack(g + (int64_t)m * g_stride + begin[s], 0, length[s], 1, 0, thr_coef,
+                        codes + (int64_t)m * code_stride + begin[s] / 16, 0, sc, th, 0, 0);
+    }
+}
+
+// requant: 0 = none, otherwise the averaged gradient of each tensor is quantized again as a
+// vector of that tensor's length.
+void orc_step_segments(int method, const uint32_t* codes, int64_t code_stride, const float* scales,
+                       int64_t scale_stride, int64_t d, int M, int64_t n_seg, const int64_t* begin,
+                       const int64_t* length, float thr_coef, float* x, float* G, float* z_or_null,
+                       int64_t t, float eta, float lambda, float delta, int requant) {
+  (void)d;
+  for (int64_t s = 0; s < n_seg; ++s) {
+    if (length[s] == 0) continue;
+    const int64_t b = begin[s];
+    float* zs = z_or_null ? z_or_null + b : nullptr;
+    if (method == 0)
+      orc_step_qcmd(codes + b / 16, code_stride, scales + s, scale_stride, length[s], M, 0,
+                    thr_coef, x + b, G + b, zs, eta, lambda, delta, requant ? 2 : 0);
+    else
+      orc_step_qrda(codes + b / 16, code_stride, scales + s, scale_stride, length[s], M, 0,
+                    thr_coef, x + b, G + b, zs, t, eta, lambda, delta, requant ? 2 : 0);
+  }
+}
+
 // ---- indicator, selection and sparse encoding (Section 3.2: equations "select" and "ind";
 //      Algorithm 1, worker block; "Encode" paragraph: (32 + d + 2k) bits) ----------------------
 //

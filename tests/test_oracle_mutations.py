@@ -44,6 +44,12 @@ MUTATIONS = [
      "if ((double)a <= kept_min && a > Delta) Delta = a;"),
     ("exact_thresholds_take_any_smaller_magnitude", "if ((double)a < kept_min && a > Delta) Delta = a;",
      "if ((double)a < kept_min && Delta == 0.0f) Delta = a;"),
+    ("tensor_codes_start_at_the_wrong_word", "codes + (int64_t)m * code_stride + begin[s] / 16, 0, sc, th, 0, 0);",
+     "codes + (int64_t)m * code_stride + begin[s] / 32, 0, sc, th, 0, 0);"),
+    ("tensor_step_uses_first_tensors_scale", "orc_step_qcmd(codes + b / 16, code_stride, scales + s,",
+     "orc_step_qcmd(codes + b / 16, code_stride, scales,"),
+    ("tensor_step_skips_second_quantization", "x + b, G + b, zs, t, eta, lambda, delta, requant ? 2 : 0);",
+     "x + b, G + b, zs, t, eta, lambda, delta, 0);"),
     ("csr_gradient_uses_row_position", "acc[indices[k]] += (double)coef[b] * (double)vals[k];",
      "acc[indices[k]] += (double)coef[b] * (double)vals[indptr[r]];"),
     ("indicator_needs_both", "if (x[i] != 0.0f || xh != 0.0f) ind_out", "if (x[i] != 0.0f && xh != 0.0f) ind_out"),
@@ -80,6 +86,7 @@ def test_pins_catch_planted_mistake(name, old, new):
         r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                             os.path.join(ROOT, "tests", "test_oracle_pins.py"),
                             os.path.join(ROOT, "tests", "test_oracle_selection_pins.py"),
-                            os.path.join(ROOT, "tests", "test_oracle_stochastic_pins.py")],
+                            os.path.join(ROOT, "tests", "test_oracle_stochastic_pins.py"),
+                            os.path.join(ROOT, "tests", "test_oracle_segments_pins.py")],
                            env=env, cwd=ROOT, capture_output=True, text=True)
         assert r.returncode != 0, f"pins did not notice: {name}"
