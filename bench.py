@@ -45,6 +45,8 @@ WORKLOADS = {
     "select": dict(select=True, d=1 << 28, M=8, bucket=4096),
     # stochastic (TernGrad/Philox) quantizer against the threshold quantizer on the same input
     "stochastic": dict(stoch=True, d=1 << 28, M=4, bucket=4096),
+    # a convolutional net's parameter list in one flat vector, each tensor quantized on its own
+    "multi_tensor": dict(segments=True, M=8),
     "small": dict(d=1 << 22, M=64, bucket=4096, gen="laplace", lam=1e-6, schedule="alternate"),
 }
 
@@ -193,6 +195,76 @@ def stochastic_bench(args, wl, qa, synth, torch, np, dev):
     print(json.dumps(out))
 
 
+def conv_net_tensor_list():
+    """Synthetic parameter list with the length mix of an AlexNet-style CIFAR classifier with
+    batch normalisation before every layer (5 conv + 3 fully connected layers: a few tensors of
+    10^5..10^7.6 weights, many of 10^1..10^3.6 biases and normalisation parameters)."""
+    lengths = []
+    cin = 3
+    for k, cout in ((11, 96), (5, 256), (3, 384), (3, 384), (3, 256)):
+        lengths += [cin, cin, k * k * cin * cout, cout]          # bn scale, bn shift, kernel, bias
+        cin = cout
+    fin = 256 * 6 * 6
+    for fout in (4096, 4096, 10):
+        lengths += [fin, fin, fin * fout, fout]
+        fin = fout
+    begin, pos = [], 0
+    for n in lengths:
+        begin.append(pos)
+        pos = (pos + n + 15) // 16 * 16
+    return begin, lengths, pos
+
+
+def segments_bench(args, wl, qa, synth, torch, np, dev):
+    M = wl["M"]
+    begin, length, d = conv_net_tensor_list()
+    nseg = len(begin)
+    L = qa.Layout.make(d, M, 0, 0.75, None, nseg)
+    table = torch.zeros(qa.qa_segment_plan_bytes(d, nseg), dtype=torch.uint8, device=dev)
+    plan = qa.qa_segment_plan_init(d, begin, length, table)
+    g = torch.empty((M, d), dtype=torch.float32, device=dev)
+    for m in range(M):
+        synth.grad_gaussian_biased(d, m, 1, device=dev, out=g[m])
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    scales = torch.zeros((M, nseg), dtype=torch.float32, device=dev)
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    G = torch.zeros(d, dtype=torch.float32, device=dev)
+    z = torch.zeros(d, dtype=torch.float32, device=dev)
+    wq = torch.empty(qa.qa_segment_workspace_bytes(plan, M, qa.QA_OP_QUANTIZE), dtype=torch.uint8, device=dev)
+    wst = torch.empty(qa.qa_segment_workspace_bytes(plan, M, qa.QA_OP_STEP), dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    covered = float(sum(length))
+    t_q = timed(lambda: qa.qa_quantize_pack_segments(L, plan, g, d, codes, scales, None, wq))
+    t_s = timed(lambda: qa.qa_step_qcmd_segments(L, plan, codes, scales, x, G, z, 0.1, 1e-5, 1e-8, 0, None))
+    t_r = timed(lambda: qa.qa_step_qrda_segments(L, plan, codes, scales, x, G, z, 3, 0.1, 1e-5, 1e-8,
+                                                 qa.QA_REQUANT_BUCKET, wst))
+    by_q = 8.25 * M * covered            # gradient read twice (two passes), codes written once
+    by_s = (24 + M / 4) * covered
+    by_r = (4 + M / 4 + 8.25 + 20 + 0.25) * covered   # average out, quantize it, update from it
+    total = t_q + t_s
+    out = {"metric": "tensor-list step (quantize+pack of M gradients + fused QCMD step): coordinates/s",
+           "value": covered / (total * 1e-3), "unit": "coordinates/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": total, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"multi_tensor: {nseg} tensors, {int(covered)} parameters "
+                                  f"(lengths {min(length)}..{max(length)}), M={M}, {plan.n_pieces} pieces"},
+           "kernels": {"quantize_pack_segments": {"ms": t_q, "algorithmic_GBps": by_q / (t_q * 1e-3) / 1e9},
+                       "step_qcmd_segments": {"ms": t_s, "algorithmic_GBps": by_s / (t_s * 1e-3) / 1e9},
+                       "step_qrda_segments_requant": {"ms": t_r, "algorithmic_GBps": by_r / (t_r * 1e-3) / 1e9}}}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +296,8 @@ def main():
         return select_bench(args, wl, qa, synth, torch, np, dev)
     if "stoch" in wl:
         return stochastic_bench(args, wl, qa, synth, torch, np, dev)
+    if "segments" in wl:
+        return segments_bench(args, wl, qa, synth, torch, np, dev)
     d, M, bucket, lam = wl["d"], wl["M"], wl["bucket"], wl["lam"]
     eta, delta = 0.1, 1e-8
     W = (d + 15) // 16

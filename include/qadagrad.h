@@ -51,7 +51,7 @@ extern "C" {
 #define QA_ERR_UNSUPPORTED (-5) /* valid request this build does not implement               */
 
 /* second-quantization mode of the fused steps ("q_t = Q(SynQ_t)", Section 3.2, equation Qt;
- * the methods marked with a dagger in Section 4.1 skip it) */
+ * the methods marked with a dagger in Section 5.1 skip it) */
 #define QA_REQUANT_NONE 0   /* q = SynQ                                                      */
 #define QA_REQUANT_BUCKET 1 /* q = Q(SynQ) with one threshold/scale per bucket of the layout */
 #define QA_REQUANT_GLOBAL 2 /* q = Q(SynQ) with one threshold/scale for the whole vector     */
@@ -103,7 +103,7 @@ size_t qa_workspace_bytes(const qa_layout* layout, int op);
 
 /* Minibatch gradient of one worker for the logistic loss log(1 + exp(-y a.x)), y in {-1,+1}
  * (stochastic gradient of Section 3.1 for the L1-regularised logistic regression of
- * Section 4.1; the regulariser is handled by the update, not here):
+ * Section 5.1; the regulariser is handled by the update, not here):
  *     p_b    = a_{r_b} . x                        (sum in binary64, rounded to binary32)
  *     coef_b = -y_{r_b} / (1 + exp(y_{r_b} p_b)) / B     (binary64, rounded to binary32)
  *     g_j    = sum_b coef_b * a_{r_b, j}          (sum in binary64, rounded to binary32)
@@ -147,7 +147,7 @@ int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, 
                      float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
                      void* stream);
 
-/* Stochastic ternary quantizer, the "ternary" comparison of Section 4.1 (TernGrad, cited in
+/* Stochastic ternary quantizer, the "ternary" comparison of Section 5.1 (TernGrad, cited in
  * Section 2; the paper does not restate it): per bucket s = max|v_i|, component i is kept with
  * probability |v_i|/s and coded as its sign, so that E[s*code_i] = v_i.  Same outputs and
  * encoding as qa_quantize_pack (codes, scales; no thresholds).  The uniform numbers are
@@ -231,6 +231,64 @@ int qa_quantize_pack_selected(const qa_layout* layout, const float* g, int64_t g
  * scales from qa_quantize_pack_selected the result feeds qa_aggregate_unpack / qa_step_*. */
 int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
                        const uint32_t* sel_codes, uint32_t* codes_out, void* stream);
+
+/* ---- a list of parameter tensors in one flat vector --------------------------------------------
+ *
+ * For models whose parameters are many tensors of very different sizes (the convolutional
+ * networks of Section 5).  The paper does not say at which granularity their gradients are
+ * quantized; this library's reading is: the quantizer of Sections 3.4-3.5 is applied to each
+ * tensor's gradient on its own (own threshold, own scale), exactly as to a vector of that
+ * length, and the update is the same per coordinate.  One launch covers the whole list.
+ *
+ * The tensors live in one flat vector of length d (x, G, z, the gradients and the 2-bit codes
+ * all use the flat index): tensor s occupies [begin[s], begin[s] + length[s]); begin[s] is a
+ * multiple of 16 (no code word is shared), the tensors are in ascending order and do not
+ * overlap; length[s] may be 0.  Coordinates between tensors belong to no tensor: their gradient
+ * is not read, their code fields inside a tensor's last word are written as 0, code words that
+ * no tensor touches are neither written nor read, and the steps leave their x, G, z alone.
+ * scales[m*scale_stride + s] / thresholds[...] belong to worker m's tensor s
+ * (layout->bucket must be 0 and layout->scale_stride >= n_seg).
+ *
+ * A plan is the device-resident description of the list, built once and reused.  The caller owns
+ * the table memory and keeps it unchanged while the plan is in use. */
+typedef struct qa_segment_plan {
+  int64_t d;         /* length of the flat vector                                            */
+  int64_t n_seg;     /* number of tensors                                                    */
+  int64_t n_pieces;  /* (4096-tile x tensor) intersections = work-groups per launch          */
+  const void* table; /* device memory written by qa_segment_plan_init                        */
+} qa_segment_plan;
+
+/* Bytes of device memory a plan's table may need (an upper bound; 0 for invalid arguments). */
+size_t qa_segment_plan_bytes(int64_t d, int64_t n_seg);
+
+/* Validates begin/length (HOST arrays of n_seg entries) against the rules above, writes the
+ * table (device, 8-byte aligned, at least qa_segment_plan_bytes) and fills *plan_out.  The copy
+ * is enqueued on `stream` and waited for: this call synchronises that stream.  1 <= n_seg,
+ * 1 <= d < 2^40. */
+int qa_segment_plan_init(int64_t d, int64_t n_seg, const int64_t* begin, const int64_t* length,
+                         void* table, size_t table_bytes, qa_segment_plan* plan_out, void* stream);
+
+/* Workspace of the tensor-list calls below: op = QA_OP_QUANTIZE or QA_OP_STEP (the latter only
+ * needed with requant != QA_REQUANT_NONE). */
+size_t qa_segment_workspace_bytes(const qa_segment_plan* plan, int32_t M, int op);
+
+/* qa_quantize_pack per tensor: thresholds (optional output) and scales per (worker, tensor),
+ * codes at the flat index.  A tensor of length 0 gets threshold 0 and scale 0. */
+int qa_quantize_pack_segments(const qa_layout* layout, const qa_segment_plan* plan, const float* g,
+                              int64_t g_stride, uint32_t* codes, float* scales, float* thresholds,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* qa_step_qcmd / qa_step_qrda per tensor.  requant: QA_REQUANT_NONE, or QA_REQUANT_BUCKET = the
+ * averaged gradient of each tensor is quantized again as a vector of that tensor's length
+ * (QA_REQUANT_GLOBAL is refused: there is no whole-vector scale here). */
+int qa_step_qcmd_segments(const qa_layout* layout, const qa_segment_plan* plan,
+                          const uint32_t* codes, const float* scales, float* x, float* G,
+                          float* z_or_null, float eta, float lambda, float delta, int requant,
+                          void* ws, size_t ws_bytes, void* stream);
+int qa_step_qrda_segments(const qa_layout* layout, const qa_segment_plan* plan,
+                          const uint32_t* codes, const float* scales, float* x, float* G, float* z,
+                          int64_t t, float eta, float lambda, float delta, int requant, void* ws,
+                          size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

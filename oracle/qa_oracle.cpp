@@ -334,7 +334,7 @@ void orc_step_qrda(const uint32_t* codes, int64_t code_stride, const float* scal
   orc_update_qrda(q.data(), d, x, G, z, t, eta, lambda, delta);
 }
 
-// ---- a list of parameter tensors in one flat vector (models such as the CNNs of Section 5.2,
+// ---- a list of parameter tensors in one flat vector (models such as the CNNs of Section 5,
 //      whose parameters are many tensors of very different sizes) --------------------------------
 //
 // Reading: the quantizer is applied to each tensor's gradient on its own (own threshold, own
@@ -464,7 +464,7 @@ void orc_decode_selected(const uint32_t* ind, const uint32_t* sel_codes, int64_t
   pack_codes(code.data(), d, dense_words);
 }
 
-// ---- stochastic ternary quantizer (the "ternary" baseline of Section 4.1: TernGrad, Wen et
+// ---- stochastic ternary quantizer (the "ternary" baseline of Section 5.1: TernGrad, Wen et
 //      al. 2017, which the paper cites and does not restate) with a counter-based generator ----
 //
 // Per bucket: s = max_i |v_i|;  component i is kept with probability |v_i| / s and then coded
@@ -517,7 +517,7 @@ void orc_quantize_stochastic(const float* v, int64_t d, int64_t bucket, uint64_t
   }
 }
 
-// ---- local gradient: L1-regularised logistic regression (Section 4.1) ----------------
+// ---- local gradient: L1-regularised logistic regression (Section 5.1) ----------------
 //
 // Loss of one sample (a, y), y in {-1,+1}:  log(1 + exp(-y * a.x)); the minibatch
 // gradient is the mean over the batch (the stochastic-gradient equation of Section 3.1).

@@ -54,6 +54,12 @@ class Layout(C.Structure):
         return (self.d + self.bucket - 1) // self.bucket if self.bucket else 1
 
 
+class SegmentPlan(C.Structure):
+    """Mirror of qa_segment_plan; `keep` holds the tensor that owns the device table."""
+    _fields_ = [("d", C.c_int64), ("n_seg", C.c_int64), ("n_pieces", C.c_int64), ("table", C.c_void_p)]
+    keep = None
+
+
 if not os.path.exists(lib_path()):
     raise ImportError(
         f"{lib_path()} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
@@ -84,6 +90,9 @@ _lib.qa_quantize_pack_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _v
 _lib.qa_decode_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp]
 _lib.qa_quantize_pack_stochastic.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, C.c_uint64,
                                              C.c_uint32, _vp]
+_lib.qa_segment_plan_bytes.restype = _sz
+_lib.qa_segment_plan_bytes.argtypes = [C.c_int64, C.c_int64]
+_lib.qa_segment_workspace_bytes.restype = _sz
 
 
 def _p(t):
@@ -182,3 +191,55 @@ def qa_decode_selected(layout, ind, ind_stride, sel_codes, codes_out, stream=Non
 def qa_quantize_pack_stochastic(layout, g, g_stride, codes, scales, seed, step, stream=None):
     _check(_lib.qa_quantize_pack_stochastic(C.byref(layout), _p(g), g_stride, _p(codes), _p(scales),
                                             seed, step, _stream(stream)), "qa_quantize_pack_stochastic")
+
+
+def qa_segment_plan_bytes(d: int, n_seg: int) -> int:
+    return int(_lib.qa_segment_plan_bytes(d, n_seg))
+
+
+def qa_segment_plan_init(d, begin, length, table, stream=None) -> SegmentPlan:
+    """begin, length: host sequences of ints; table: device tensor of at least
+    qa_segment_plan_bytes(d, len(begin)) bytes, kept alive by the returned plan."""
+    n = len(begin)
+    assert len(length) == n
+    b = (C.c_int64 * max(n, 1))(*[int(v) for v in begin])
+    l = (C.c_int64 * max(n, 1))(*[int(v) for v in length])
+    plan = SegmentPlan()
+    _lib.qa_segment_plan_init.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_int64),
+                                          C.POINTER(C.c_int64), _vp, _sz, C.POINTER(SegmentPlan), _vp]
+    _check(_lib.qa_segment_plan_init(d, n, b, l, _p(table), _nbytes(table), C.byref(plan),
+                                     _stream(stream)), "qa_segment_plan_init")
+    plan.keep = table
+    return plan
+
+
+def qa_segment_workspace_bytes(plan: SegmentPlan, M: int, op: int) -> int:
+    _lib.qa_segment_workspace_bytes.argtypes = [C.POINTER(SegmentPlan), C.c_int32, C.c_int]
+    return int(_lib.qa_segment_workspace_bytes(C.byref(plan), M, op))
+
+
+def qa_quantize_pack_segments(layout, plan, g, g_stride, codes, scales, thresholds, ws, stream=None):
+    _lib.qa_quantize_pack_segments.argtypes = [C.POINTER(Layout), C.POINTER(SegmentPlan), _vp, C.c_int64,
+                                               _vp, _vp, _vp, _vp, _sz, _vp]
+    _check(_lib.qa_quantize_pack_segments(C.byref(layout), C.byref(plan), _p(g), g_stride, _p(codes),
+                                          _p(scales), _p(thresholds), _p(ws), _nbytes(ws),
+                                          _stream(stream)), "qa_quantize_pack_segments")
+
+
+def qa_step_qcmd_segments(layout, plan, codes, scales, x, G, z_or_null, eta, lam, delta, requant, ws,
+                          stream=None):
+    _lib.qa_step_qcmd_segments.argtypes = [C.POINTER(Layout), C.POINTER(SegmentPlan), _vp, _vp, _vp, _vp,
+                                           _vp, C.c_float, C.c_float, C.c_float, C.c_int, _vp, _sz, _vp]
+    _check(_lib.qa_step_qcmd_segments(C.byref(layout), C.byref(plan), _p(codes), _p(scales), _p(x),
+                                      _p(G), _p(z_or_null), eta, lam, delta, requant, _p(ws),
+                                      _nbytes(ws), _stream(stream)), "qa_step_qcmd_segments")
+
+
+def qa_step_qrda_segments(layout, plan, codes, scales, x, G, z, t, eta, lam, delta, requant, ws,
+                          stream=None):
+    _lib.qa_step_qrda_segments.argtypes = [C.POINTER(Layout), C.POINTER(SegmentPlan), _vp, _vp, _vp, _vp,
+                                           _vp, C.c_int64, C.c_float, C.c_float, C.c_float, C.c_int,
+                                           _vp, _sz, _vp]
+    _check(_lib.qa_step_qrda_segments(C.byref(layout), C.byref(plan), _p(codes), _p(scales), _p(x),
+                                      _p(G), _p(z), t, eta, lam, delta, requant, _p(ws), _nbytes(ws),
+                                      _stream(stream)), "qa_step_qrda_segments")

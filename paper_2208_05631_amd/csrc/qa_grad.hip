@@ -1,5 +1,5 @@
 // Minibatch gradient of the logistic loss for one worker (stochastic gradient of Section 3.1
-// for the L1-regularised logistic regression of Section 4.1, arXiv 2208.05631), dense rows or
+// for the L1-regularised logistic regression of Section 5.1, arXiv 2208.05631), dense rows or
 // CSR rows, for gfx950.
 //
 //   margins  : p_b = a_{r_b}.x in binary64 (work-group per row for dense, wave per row for CSR),

@@ -8,7 +8,7 @@
 // gbar = (float)(acc / M), optionally re-quantizes gbar per bucket inside the tile, and applies
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
 #include <stdlib.h>
-#include "qa_common.h"
+#include "qa_segments.h"
 
 namespace qa {
 
@@ -27,6 +27,7 @@ struct StepArgs {
   int span_limit;     // max exponent span of a tile's scales for which any order is exact
   float* x; float* G; float* z; float* gbar;
   float eta, lam_eta, delta, t_lam, thr_coef;
+  SegTable seg;       // tensor-list launches: work-group = piece, one scale column per tensor
 };
 
 // 10 -> 00 so that the reserved pattern reads as zero; 01 and 11 are unchanged.
@@ -201,35 +202,36 @@ __device__ __forceinline__ void stream_store4(float* p, const float4& v) {
   __builtin_nontemporal_store(t, reinterpret_cast<floatx4*>(p));
 }
 
-// float4 groups j*256+t of the tile; out-of-range elements read as 0 (tail tile only)
+// float4 groups j*256+t of the tile; only coordinates in [lo, hi) are touched (lo is a multiple
+// of 16), the others read as 0.  full_tile: [lo, hi) is the whole tile.
 __device__ __forceinline__ void load_state(const float* __restrict__ p, int64_t tile_base,
-                                           int64_t d, bool full_tile, State4& s) {
+                                           int64_t lo, int64_t hi, bool full_tile, State4& s) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int64_t i = tile_base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
-    if (full_tile || i + 3 < d) {
+    if (full_tile || (i >= lo && i + 3 < hi)) {
       s.v[j] = *reinterpret_cast<const float4*>(p + i);
     } else {
       float e[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) e[c] = (i + c < d) ? p[i + c] : 0.0f;
+      for (int c = 0; c < 4; ++c) e[c] = (i + c >= lo && i + c < hi) ? p[i + c] : 0.0f;
       s.v[j] = make_float4(e[0], e[1], e[2], e[3]);
     }
   }
 }
 
-__device__ __forceinline__ void store_state(float* __restrict__ p, int64_t tile_base, int64_t d,
-                                            bool full_tile, const State4& s) {
+__device__ __forceinline__ void store_state(float* __restrict__ p, int64_t tile_base, int64_t lo,
+                                            int64_t hi, bool full_tile, const State4& s) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int64_t i = tile_base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
-    if (full_tile || i + 3 < d) {
+    if (full_tile || (i >= lo && i + 3 < hi)) {
       stream_store4(p + i, s.v[j]);
     } else {
       const float e[4] = {s.v[j].x, s.v[j].y, s.v[j].z, s.v[j].w};
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        if (i + c < d) p[i + c] = e[c];
+        if (i + c >= lo && i + c < hi) p[i + c] = e[c];
     }
   }
 }
@@ -268,10 +270,19 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   __shared__ uint32_t lds_u[kWaves];
   __shared__ int lds_e[3 * kWaves];
   const int t = threadIdx.x;
-  const int64_t tile = blockIdx.x;
+  // the work-group's tile, its live coordinates [lo, hi) and its column of scales
+  int64_t tile, lo, hi, k;
+  if (a.seg.piece_tile) {
+    const Piece pc = load_piece(a.seg, blockIdx.x, a.d);
+    tile = pc.tile; lo = pc.lo; hi = pc.hi; k = pc.seg;
+  } else {
+    tile = blockIdx.x;
+    lo = tile * kTile;
+    hi = lo + kTile < a.d ? lo + kTile : a.d;
+    k = a.log2b >= 0 ? (lo >> a.log2b) : 0;                            // same for the whole tile
+  }
   const int64_t tile_base = tile * kTile;
-  const bool full_tile = tile_base + kTile <= a.d;
-  const int64_t k = a.log2b >= 0 ? (tile_base >> a.log2b) : 0;         // same for the whole tile
+  const bool full_tile = hi - lo == kTile;
   const float* sc = a.scales + k;
   // words of this tile that exist; lanes beyond read the last one (in bounds) and are masked
   const int64_t words_here = a.W - tile * kTileWords;
@@ -289,9 +300,9 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   }
   State4 sG, sx, sz;
   if (MODE != kAggregate) {
-    load_state(a.G, tile_base, a.d, full_tile, sG);
-    if (MODE == kQcmd) load_state(a.x, tile_base, a.d, full_tile, sx);
-    if (MODE == kQrda || TRACK_Z) load_state(a.z, tile_base, a.d, full_tile, sz);
+    load_state(a.G, tile_base, lo, hi, full_tile, sG);
+    if (MODE == kQcmd) load_state(a.x, tile_base, lo, hi, full_tile, sx);
+    if (MODE == kQrda || TRACK_Z) load_state(a.z, tile_base, lo, hi, full_tile, sz);
   }
 
   // ---- can the sum over workers be reordered? (exponent span of the tile's scales) ----
@@ -381,13 +392,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] / Md);
   }
-  {
-    const int64_t i0 = tile_base + 16 * (int64_t)t;                    // masks dead lanes too
-    if (i0 + 16 > a.d) {
+  if (!full_tile) {                                       // dead lanes lie at or beyond hi
+    const int64_t i0 = tile_base + 16 * (int64_t)t;
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (i0 + j >= a.d || !live) q[j] = 0.0f;
-    }
+    for (int j = 0; j < 16; ++j)
+      if (i0 + j < lo || i0 + j >= hi) q[j] = 0.0f;
   }
 
   if (REQUANT) {                                          // bucket == 4096 == the tile
@@ -395,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);
     s1 = segment_sum(s1, kThreads, lds_d);
-    const int64_t n = (a.d - tile_base) < (int64_t)kTile ? (a.d - tile_base) : (int64_t)kTile;
+    const int64_t n = hi - lo;
     const float Delta = threshold_from_sum(s1, a.thr_coef, n);
     double s2 = 0.0;
     uint32_t cnt = 0;
@@ -424,7 +433,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   for (int j = 0; j < 4; ++j) sq.v[j] = *reinterpret_cast<const float4*>(qt + 4 * (j * kThreads + t));
 
   if (MODE == kAggregate) {
-    store_state(a.gbar, tile_base, a.d, full_tile, sq);
+    store_state(a.gbar, tile_base, lo, hi, full_tile, sq);
     return;
   }
 #pragma unroll
@@ -440,9 +449,9 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     sx.v[j] = make_float4(x[0], x[1], x[2], x[3]);
     sz.v[j] = make_float4(z[0], z[1], z[2], z[3]);
   }
-  store_state(a.G, tile_base, a.d, full_tile, sG);
-  store_state(a.x, tile_base, a.d, full_tile, sx);
-  if (MODE == kQrda || TRACK_Z) store_state(a.z, tile_base, a.d, full_tile, sz);
+  store_state(a.G, tile_base, lo, hi, full_tile, sG);
+  store_state(a.x, tile_base, lo, hi, full_tile, sx);
+  if (MODE == kQrda || TRACK_Z) store_state(a.z, tile_base, lo, hi, full_tile, sz);
 }
 
 // ---- host side -------------------------------------------------------------------------------
@@ -504,6 +513,7 @@ static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float
 // QA_STEP_KERNEL=ordered forces the worker-ordered kernel (diagnostics); default: table-driven
 // kernel whenever a tile's coordinates share their scales.
 static bool use_lut(const StepArgs& a) {
+  if (a.seg.piece_tile) return true;                     // pieces exist only in that kernel
   if (!a.tile_uniform) return false;
   const char* e = getenv("QA_STEP_KERNEL");
   return !(e && e[0] == 'o');
@@ -512,7 +522,7 @@ static bool use_lut(const StepArgs& a) {
 // which: -1 = worker-ordered kernel, otherwise the NGT of the table-driven kernel
 template <int MODE, bool TRACK_Z, bool REQUANT>
 static void launch_one(const StepArgs& a, int which, hipStream_t stream) {
-  const dim3 grid((unsigned)tiles_of(a.d)), block(kThreads);
+  const dim3 grid((unsigned)(a.seg.piece_tile ? a.seg.n_pieces : tiles_of(a.d))), block(kThreads);
   switch (which) {
     case 16: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 16>), grid, block, 0, stream, a); break;
     case 8: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 8>), grid, block, 0, stream, a); break;
@@ -594,7 +604,93 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
   return launch_status();
 }
 
+// Tensor-list steps: the table-driven kernel with one work-group per piece.  The second
+// quantization runs as separate passes: average -> workspace, quantize it per tensor as a
+// one-worker message, update from that message.
+size_t step_segments_workspace_bytes(const qa_segment_plan* P) {
+  return align256((size_t)P->d * sizeof(float)) + align256((size_t)words_of(P->d) * 4) +
+         2 * align256((size_t)P->n_seg * 4) + quantize_segments_workspace_bytes(P, 1);
+}
+
+static int step_segments_common(int mode, const qa_layout* L, const qa_segment_plan* P,
+                                const uint32_t* codes, const float* scales, float* x, float* G,
+                                float* z, bool track_z, int64_t t, float eta, float lambda,
+                                float delta, int requant, void* ws, size_t ws_bytes,
+                                hipStream_t stream) {
+  int rc = check_layout(L);
+  if (rc != QA_OK) return rc;
+  rc = check_plan(P, L);
+  if (rc != QA_OK) return rc;
+  if (!codes || !scales || !x || !G) return QA_ERR_INVALID_ARG;
+  if (mode == kQrda && !z) return QA_ERR_INVALID_ARG;
+  if (!(eta > 0.0f) || !(lambda >= 0.0f) || !(delta > 0.0f)) return QA_ERR_INVALID_ARG;
+  if (mode == kQrda && t < 1) return QA_ERR_INVALID_ARG;
+  if (requant == QA_REQUANT_GLOBAL) return QA_ERR_UNSUPPORTED;
+  if (requant != QA_REQUANT_NONE && requant != QA_REQUANT_BUCKET) return QA_ERR_INVALID_ARG;
+  if (!aligned(x, 16) || !aligned(G, 16) || !aligned(z, 16) || !aligned(codes, 4) ||
+      !aligned(scales, 4))
+    return QA_ERR_ALIGNMENT;
+  if (P->n_pieces == 0) return QA_OK;                    // every tensor is empty
+
+  qa_layout R = *L;
+  const uint32_t* use_codes = codes;
+  const float* use_scales = scales;
+  if (requant != QA_REQUANT_NONE) {
+    if (!ws || ws_bytes < step_segments_workspace_bytes(P)) return QA_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+    R.M = 1; R.code_stride = words_of(L->d); R.scale_stride = P->n_seg;
+    char* p = static_cast<char*>(ws);
+    float* gbar = reinterpret_cast<float*>(p);        p += align256((size_t)L->d * sizeof(float));
+    uint32_t* c1 = reinterpret_cast<uint32_t*>(p);    p += align256((size_t)R.code_stride * 4);
+    float* s1 = reinterpret_cast<float*>(p);          p += align256((size_t)P->n_seg * 4);
+    float* th1 = reinterpret_cast<float*>(p);         p += align256((size_t)P->n_seg * 4);
+    StepArgs ag = make_args(L, codes, scales);
+    ag.seg = seg_table_of(P);
+    ag.gbar = gbar;
+    launch_mode<kAggregate>(ag, false, false, stream);
+    const int64_t gs = (L->d + 3) & ~int64_t(3);
+    rc = quantize_segments_launch(&R, P, gbar, gs, c1, s1, th1, p,
+                                  quantize_segments_workspace_bytes(P, 1), stream);
+    if (rc != QA_OK) return rc;
+    use_codes = c1; use_scales = s1;
+  }
+  StepArgs a = make_args(&R, use_codes, use_scales);
+  a.seg = seg_table_of(P);
+  a.x = x; a.G = G; a.z = z;
+  a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta;
+  a.t_lam = (float)t * lambda;
+  if (mode == kQcmd) launch_mode<kQcmd>(a, track_z, false, stream);
+  else launch_mode<kQrda>(a, false, false, stream);
+  return launch_status();
+}
+
 }  // namespace qa
+
+extern "C" size_t qa_segment_workspace_bytes(const qa_segment_plan* plan, int32_t M, int op) {
+  using namespace qa;
+  if (!plan || plan->d < 1 || plan->n_seg < 1 || plan->n_pieces < 0 || M < 1 || M > 4096) return 0;
+  if (op == QA_OP_QUANTIZE) return quantize_segments_workspace_bytes(plan, M);
+  if (op == QA_OP_STEP) return step_segments_workspace_bytes(plan);
+  return 0;
+}
+
+extern "C" int qa_step_qcmd_segments(const qa_layout* layout, const qa_segment_plan* plan,
+                                     const uint32_t* codes, const float* scales, float* x, float* G,
+                                     float* z_or_null, float eta, float lambda, float delta,
+                                     int requant, void* ws, size_t ws_bytes, void* stream) {
+  return qa::step_segments_common(qa::kQcmd, layout, plan, codes, scales, x, G, z_or_null,
+                                  z_or_null != nullptr, 1, eta, lambda, delta, requant, ws,
+                                  ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int qa_step_qrda_segments(const qa_layout* layout, const qa_segment_plan* plan,
+                                     const uint32_t* codes, const float* scales, float* x, float* G,
+                                     float* z, int64_t t, float eta, float lambda, float delta,
+                                     int requant, void* ws, size_t ws_bytes, void* stream) {
+  return qa::step_segments_common(qa::kQrda, layout, plan, codes, scales, x, G, z, false, t, eta,
+                                  lambda, delta, requant, ws, ws_bytes,
+                                  static_cast<hipStream_t>(stream));
+}
 
 extern "C" int qa_aggregate_unpack(const qa_layout* layout, const uint32_t* codes,
                                    const float* scales, float* gbar_out, void* stream) {

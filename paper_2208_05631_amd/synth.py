@@ -4,7 +4,7 @@ This module only makes DATA (design matrices, labels, minibatch row ids, worker 
 It contains none of the method's arithmetic and is used by the tests, the smoke check and the
 benchmark to feed the same bits to the GPU library and to the CPU checker.
 
-The paper's linear-model experiments use LIBSVM news20 / rcv1 (Section 4.1, Table 1): very
+The paper's linear-model experiments use LIBSVM news20 / rcv1 (Section 5.1, Table 1): very
 high-dimensional, very sparse rows, +-1 labels, small minibatches per worker.  Those datasets
 are not available here; the generators below are stand-ins of the same kind of shape and do
 not reproduce any of their records.

@@ -86,7 +86,9 @@ def test_quantize_and_aggregate_argument_checks():
     assert q(C.byref(ok), FAKE, 999, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -1    # stride < d
     assert q(C.byref(ok), FAKE, 1002, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -1   # not % 4
     assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 1, FAKE, 1 << 20, None) == -1   # given, null
-    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 2, FAKE, 1 << 20, None) == -1   # unknown flag
+    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 4, FAKE, 1 << 20, None) == -1   # unknown flag
+    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 2, FAKE, 1 << 20, None) == -1   # exact, null
+    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, FAKE, 3, FAKE, 1 << 20, None) == -1   # given and exact
     assert q(C.byref(ok), FAKE + 4, 1000, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -2
     assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 0, None, 0, None) == -3
     assert B._lib.qa_aggregate_unpack(C.byref(ok), FAKE, FAKE, None, None) == -1
@@ -100,3 +102,37 @@ def test_local_grad_argument_checks():
     assert f(0, FAKE, None, None, 10, 10, FAKE, FAKE, 0, FAKE, FAKE, None, FAKE, 1 << 30, None) == -1
     assert f(0, FAKE, None, None, 10, 10, FAKE, FAKE, 4, FAKE, FAKE, None, None, 0, None) == -3
     assert f(0, FAKE, None, None, 10, 10, FAKE, FAKE, 4, FAKE, FAKE + 4, None, FAKE, 1 << 30, None) == -2
+
+
+def test_segment_plan_argument_checks():
+    """The tensor table is validated on the host before anything is copied to the device."""
+    init = B._lib.qa_segment_plan_init
+    init.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_void_p,
+                     C.c_size_t, C.POINTER(B.SegmentPlan), C.c_void_p]
+    plan = B.SegmentPlan()
+
+    def run(d, begin, length, table=FAKE, nbytes=1 << 20):
+        n = len(begin)
+        return init(d, n, (C.c_int64 * max(n, 1))(*begin), (C.c_int64 * max(n, 1))(*length), table,
+                    nbytes, C.byref(plan), None)
+
+    assert run(1000, [0, 8], [4, 4]) == -1              # begin not a multiple of 16
+    assert run(1000, [0, 16], [20, 4]) == -1            # overlap
+    assert run(1000, [32, 0], [4, 4]) == -1             # not ascending
+    assert run(1000, [0, 992], [4, 9]) == -1            # runs past d
+    assert run(1000, [0], [-1]) == -1
+    assert run(0, [0], [0]) == -1
+    assert run(1000, [], []) == -1                      # at least one tensor
+    assert run(1000, [0], [4], table=None) == -1
+    assert run(1000, [0], [4], table=FAKE + 4) == -2
+    assert run(1 << 20, [0], [1 << 20], nbytes=64) == -3
+    assert qa.qa_segment_plan_bytes(1 << 20, 10) == 8 * (4 + 20 + 11 + 2 * (256 + 10))
+    assert qa.qa_segment_plan_bytes(0, 10) == 0 and qa.qa_segment_plan_bytes(100, 0) == 0
+    bad = B.SegmentPlan(1000, 1, 1, None)
+    assert qa.qa_segment_workspace_bytes(B.SegmentPlan(1000, 3, 3, FAKE), 4, qa.QA_OP_QUANTIZE) > 0
+    ok = qa.Layout.make(1000, 4, 0)
+    B._lib.qa_quantize_pack_segments.argtypes = [C.POINTER(qa.Layout), C.POINTER(B.SegmentPlan), C.c_void_p,
+                                                 C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.c_size_t, C.c_void_p]
+    assert B._lib.qa_quantize_pack_segments(C.byref(ok), C.byref(bad), FAKE, 1000, FAKE, FAKE, None, FAKE,
+                                            1 << 20, None) == -1            # plan without table
