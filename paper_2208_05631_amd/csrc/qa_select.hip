@@ -54,22 +54,27 @@ __device__ __forceinline__ float local_update(const SelArgs& a, float g, float x
 //   H <= delta + max(1, G + g*g) bounds the quotients away from the subnormal range.
 // Everything else (ties within the margin, possible underflow, NaN/Inf) is left undecided and
 // the caller evaluates the closed form itself.
+// Written without branches: every lane runs the same straight-line code.
+template <int METHOD>
 __device__ __forceinline__ bool quick_indicator(const SelArgs& a, float g, float x, float G, float z,
                                                 bool* mark) {
-  *mark = true;
-  if (x != 0.0f) return true;
+  const bool xnz = x != 0.0f;
   const float s2 = G + g * g;
-  if (!(s2 >= 0.0f)) return false;                       // NaN or invalid accumulator
-  const float h_ub = a.delta + (s2 > 1.0f ? s2 : 1.0f);
-  if (a.method == 0) {
+  const bool valid = s2 >= 0.0f;                         // false for NaN or an invalid accumulator
+  const float tiny = (a.delta + (s2 > 1.0f ? s2 : 1.0f)) * 0x1p-100f;
+  bool m, decided;
+  if (METHOD == 0) {
     const float av = fabsf(a.eta * g), b = a.lam_eta;
-    *mark = av > b;
-    return av <= b || (av > b * 1.0000005f && b >= h_ub * 0x1p-100f);
+    m = av > b;
+    decided = (av <= b) | ((av > b * 1.0000005f) & (b >= tiny));
+  } else {
+    const float zh = z + g;
+    const float r = fabsf(zh) - a.t_lam;
+    m = r > 0.0f;
+    decided = !m | (a.eta * r >= tiny);
   }
-  const float zh = z + g;
-  const float r = fabsf(zh) - a.t_lam;
-  *mark = r > 0.0f;
-  return !(r > 0.0f) || a.eta * r >= h_ub * 0x1p-100f;
+  *mark = xnz | m;
+  return xnz | (valid & decided);
 }
 
 // Rare path: the 1024 coordinates of one wave for worker m, all through the closed form.
@@ -93,9 +98,9 @@ __device__ __forceinline__ void indicator_slab_exact(const SelArgs& a, int m, in
 
 // wave w of the work-group owns coordinates [w*1024, (w+1)*1024) of the tile, lane l the
 // coordinates j*64 + l (j = 0..15): each ballot is 64 consecutive indicator bits.
-__global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int64_t base = (int64_t)blockIdx.x * kTile + wave * 1024;
+//
+// Slab that ends at or beyond d (last tile only): every access clamped or masked.
+__device__ __forceinline__ void indicator_wave_tail(const SelArgs& a, int64_t base, int lane) {
   float x[16], G[16], z[16];
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
@@ -119,7 +124,8 @@ __global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
     for (int j = 0; j < 16; ++j) {
       const int64_t c = base + j * 64 + lane;
       bool mark = false;
-      const bool ok = quick_indicator(a, gv[j], x[j], G[j], z[j], &mark);
+      const bool ok = a.method == 0 ? quick_indicator<0>(a, gv[j], x[j], G[j], z[j], &mark)
+                                    : quick_indicator<1>(a, gv[j], x[j], G[j], z[j], &mark);
       undecided |= (c < a.d) && !ok;
       mark = mark && (c < a.d);
       const uint64_t bits = __ballot(mark);
@@ -127,6 +133,65 @@ __global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
       if (lane < 2 && w0 + lane < a.NW) out[w0 + lane] = (uint32_t)(bits >> (32 * lane));
     }
     if (__any(undecided)) indicator_slab_exact(a, m, base, lane);   // overwrites the slab's words
+  }
+}
+
+// Slab that lies wholly below d: no clamps or masks; the next worker's gradient is requested
+// before the current one is examined; ballot j (64 indicator bits) is kept by lane j, and lanes
+// 0..15 store the slab's 128 bytes.
+template <int METHOD>
+__device__ __forceinline__ void indicator_wave_full(const SelArgs& a, int64_t base, int lane) {
+  const float* px = a.x + base + lane;
+  const float* pG = a.G + base + lane;
+  const float* pz = METHOD == 1 ? a.z + base + lane : px;  // z may be null for QCMD
+  float x[16], G[16], z[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    x[j] = px[j * 64];
+    G[j] = pG[j * 64];
+    z[j] = METHOD == 1 ? pz[j * 64] : 0.0f;
+  }
+  const float* pg = a.g + base + lane;
+  uint32_t* out = a.ind + base / 32 + 2 * lane;
+  float gn[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) gn[j] = pg[j * 64];
+  for (int m = 0; m < a.M; ++m) {
+    float gv[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) gv[j] = gn[j];
+    if (m + 1 < a.M) {
+      const float* pn = pg + (int64_t)(m + 1) * a.g_stride;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) gn[j] = pn[j * 64];
+    }
+    bool undecided = false;
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      bool mark = false;
+      undecided |= !quick_indicator<METHOD>(a, gv[j], x[j], G[j], z[j], &mark);
+      const uint64_t bits = __ballot(mark);
+      lo = lane == j ? (uint32_t)bits : lo;
+      hi = lane == j ? (uint32_t)(bits >> 32) : hi;
+    }
+    if (__any(undecided)) {
+      indicator_slab_exact(a, m, base, lane);
+    } else if (lane < 16) {
+      out[(int64_t)m * a.ind_stride] = lo;
+      out[(int64_t)m * a.ind_stride + 1] = hi;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int64_t base = (int64_t)blockIdx.x * kTile + wave * 1024;
+  if (base + 1024 <= a.d) {
+    if (a.method == 0) indicator_wave_full<0>(a, base, lane);
+    else indicator_wave_full<1>(a, base, lane);
+  } else if (base < a.d) {
+    indicator_wave_tail(a, base, lane);
   }
 }
 
