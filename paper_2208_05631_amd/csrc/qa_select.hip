@@ -301,30 +301,111 @@ __global__ __launch_bounds__(kThreads) void quantize_selected_kernel(SelArgs a) 
   }
 }
 
+// Inclusive prefix sum over the 64 lanes with DPP: shifts within each row of 16 lanes, then the
+// last lane of a row is broadcast into the following rows.  A lane without a source adds 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
+  v += dpp_or_zero<0x111, 0xF>(v);      // row_shr:1
+  v += dpp_or_zero<0x112, 0xF>(v);      // row_shr:2
+  v += dpp_or_zero<0x114, 0xF>(v);      // row_shr:4
+  v += dpp_or_zero<0x118, 0xF>(v);      // row_shr:8
+  v += dpp_or_zero<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
+  v += dpp_or_zero<0x143, 0xC>(v);      // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// Deposit table: entry [nib][s] spreads the low 2-bit codes of s to the 2-bit fields of a byte
+// whose positions are the set bits of the 4-bit mask nib (first code to the lowest set bit).
+struct DepositLut { uint8_t v[16 * 256]; };
+constexpr DepositLut make_deposit_lut() {
+  DepositLut t{};
+  for (int nib = 0; nib < 16; ++nib)
+    for (int s = 0; s < 256; ++s) {
+      uint32_t w = (uint32_t)s, out = 0;
+      for (int b = 0; b < 4; ++b)
+        if ((nib >> b) & 1) { out |= (w & 3u) << (2 * b); w >>= 2; }
+      t.v[nib * 256 + s] = (uint8_t)out;
+    }
+  return t;
+}
+__device__ const DepositLut kDepositLut = make_deposit_lut();
+
+// A wave decodes kDecodeTiles consecutive 4096-tiles, phase by phase for all of them (their loads
+// are independent and overlap).  Within a tile lane l holds code words j*64 + l (j = 0..3), so
+// that each store instruction of the wave writes 256 consecutive bytes.  The position of a
+// word's first marked component in the tile's compact stream is the number of marked components
+// before it: a wave scan per j plus the totals of the earlier j.  The codes are spread to their
+// fields four components at a time through the deposit table (copied to LDS once per block).
+constexpr int kDecodeTiles = 2;
+
 __global__ __launch_bounds__(kThreads) void decode_selected_kernel(SelArgs a) {
-  __shared__ uint32_t stream[kTileWords + 1];
-  __shared__ uint32_t lds_w[kWaves];
-  const int t = threadIdx.x;
-  const int64_t tile = blockIdx.x;
+  __shared__ uint8_t lut[16 * 256];
+  reinterpret_cast<uint4*>(lut)[threadIdx.x] = reinterpret_cast<const uint4*>(kDepositLut.v)[threadIdx.x];
+  const int lane = threadIdx.x % kWave;
+  const int64_t tile0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kDecodeTiles;
   const int m = blockIdx.y;
-  const uint32_t mask = mask16_of(a.ind_in + (int64_t)m * a.ind_stride, a.NW, tile, t);
-  const uint32_t cnt = (uint32_t)__popc(mask);
-  uint32_t K;
-  const uint32_t before = block_exclusive_scan(cnt, lds_w, &K);
-  const uint32_t nwords = (K + 15) / 16;
-  stream[t] = (uint32_t)t < nwords ? (a.sel_in + (int64_t)m * a.code_stride)[tile * kTileWords + t] : 0u;
-  if (t == 0) stream[kTileWords] = 0u;
-  __syncthreads();
-  const uint32_t word = before / 16, sh = 2 * (before % 16);
-  uint32_t win = stream[word] >> sh;
-  if (sh) win |= stream[word + 1] << (32 - sh);
-  uint32_t out = 0;
+  const uint32_t* ind = a.ind_in + (int64_t)m * a.ind_stride;
+  uint32_t mask[kDecodeTiles][4], incl[kDecodeTiles][4];
 #pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    if ((mask >> j) & 1u) { out |= (win & 3u) << (2 * j); win >>= 2; }
+  for (int u = 0; u < kDecodeTiles; ++u)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int wl = j * 64 + lane;                        // code word within the tile
+      const int64_t iw = (tile0 + u) * (kTile / 32) + wl / 2;
+      const uint32_t word = iw < a.NW ? ind[iw] : 0u;
+      mask[u][j] = (word >> (16 * (wl & 1))) & 0xFFFFu;
+    }
+#pragma unroll
+  for (int u = 0; u < kDecodeTiles; ++u)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // bits at or beyond d are not components: ignoring them keeps every read of the compact
+      // stream inside the words that exist for this tile
+      const int64_t left = a.d - ((tile0 + u) * kTile + (int64_t)(j * 64 + lane) * 16);
+      if (left < 16) mask[u][j] = left > 0 ? (mask[u][j] & ((1u << left) - 1u)) : 0u;
+      incl[u][j] = wave_inclusive_scan_u32((uint32_t)__popc(mask[u][j]));
+    }
+  uint32_t win_lo[kDecodeTiles][4], win_hi[kDecodeTiles][4], sh[kDecodeTiles][4];
+#pragma unroll
+  for (int u = 0; u < kDecodeTiles; ++u) {
+    // clamped for tiles beyond the vector: their masks are 0, so nothing is read through it
+    const int64_t tile = (tile0 + u) * kTile < a.d ? tile0 + u : 0;
+    const uint32_t* sel = a.sel_in + (int64_t)m * a.code_stride + tile * kTileWords;
+    uint32_t start = 0;                                  // marked components in earlier j
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // the word's n <= 16 codes are codes before .. before+n-1 of the tile's compact stream:
+      // word before/16 and, only if they cross a word boundary, the next one; both lie below
+      // ceil(K/16) <= the words that exist for this tile (K = marked components of the tile)
+      const uint32_t n = (uint32_t)__popc(mask[u][j]);
+      const uint32_t before = start + incl[u][j] - n;
+      start += (uint32_t)__builtin_amdgcn_readlane((int)incl[u][j], kWave - 1);
+      const uint32_t w0 = before / 16;
+      sh[u][j] = 2 * (before % 16);
+      win_lo[u][j] = n != 0u ? sel[w0] : 0u;
+      win_hi[u][j] = (before % 16) + n > 16u ? sel[w0 + 1] : 0u;
+    }
   }
-  const int64_t w = tile * kTileWords + t;
-  if (w < a.W) (a.dense + (int64_t)m * a.code_stride)[w] = out;
+  __syncthreads();                                       // the table is in LDS
+#pragma unroll
+  for (int u = 0; u < kDecodeTiles; ++u)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t win = win_lo[u][j] >> sh[u][j];
+      if (sh[u][j]) win |= win_hi[u][j] << (32 - sh[u][j]);
+      uint32_t out = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t nib = (mask[u][j] >> (4 * q)) & 15u;
+        out |= (uint32_t)lut[nib * 256 + (win & 0xFFu)] << (8 * q);
+        win >>= 2 * __popc(nib);
+      }
+      const int64_t w = (tile0 + u) * kTileWords + j * 64 + lane;
+      if (w < a.W) (a.dense + (int64_t)m * a.code_stride)[w] = out;
+    }
 }
 
 static int check_select_layout(const qa_layout* L) {
@@ -411,7 +492,9 @@ extern "C" int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, 
   if (!aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(codes_out, 4)) return QA_ERR_ALIGNMENT;
   SelArgs a = base_args(layout);
   a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = sel_codes; a.dense = codes_out;
-  hipLaunchKernelGGL(decode_selected_kernel, dim3((unsigned)tiles_of(layout->d), (unsigned)layout->M),
+  hipLaunchKernelGGL(decode_selected_kernel,
+                     dim3((unsigned)((tiles_of(layout->d) + kWaves * kDecodeTiles - 1) / (kWaves * kDecodeTiles)),
+                          (unsigned)layout->M),
                      dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return launch_status();
 }
