@@ -132,6 +132,24 @@ __device__ __forceinline__ uint32_t segment_sum_u32(uint32_t v, int seg, uint32_
   return v;
 }
 
+// This thread's share of part[i0 .. i1): elements i0 + threadIdx.x + k*256, eight loads in
+// flight at a time (a fixed order: the result does not depend on scheduling).
+template <typename T>
+__device__ __forceinline__ double strided_partial_sum(const T* __restrict__ part, int64_t i0,
+                                                      int64_t i1) {
+  double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+  int64_t i = i0 + threadIdx.x;
+  for (; i + 7 * kThreads < i1; i += 8 * kThreads) {
+    T v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = part[i + u * kThreads];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] += (double)v[u];
+  }
+  for (; i < i1; i += kThreads) acc[0] += (double)part[i];
+  return ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+}
+
 // Threshold and scale from the binary64 sums, rounded once (Sections 3.4-3.5).
 __device__ __forceinline__ float threshold_from_sum(double S1, float thr_coef, int64_t n) {
   return (float)(((double)thr_coef * S1) / (double)n);

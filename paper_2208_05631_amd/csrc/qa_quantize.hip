@@ -447,8 +447,7 @@ __global__ __launch_bounds__(kThreads) void quantize_threshold_finalize_kernel(Q
   const int m = blockIdx.y;
   const int64_t t0 = k * a.tiles_per_bucket;
   const int64_t t1 = (t0 + a.tiles_per_bucket) < a.ntiles ? (t0 + a.tiles_per_bucket) : a.ntiles;
-  double s = 0.0;
-  for (int64_t i = t0 + threadIdx.x; i < t1; i += kThreads) s += a.part_sum[(int64_t)m * a.ntiles + i];
+  double s = strided_partial_sum(a.part_sum + (int64_t)m * a.ntiles, t0, t1);
   s = segment_sum(s, kThreads, lds_d);
   if (threadIdx.x == 0) {
     const int64_t lo = k * a.bucket_len;
@@ -498,11 +497,9 @@ __global__ __launch_bounds__(kThreads) void quantize_scale_finalize_kernel(Quant
   const int m = blockIdx.y;
   const int64_t t0 = k * a.tiles_per_bucket;
   const int64_t t1 = (t0 + a.tiles_per_bucket) < a.ntiles ? (t0 + a.tiles_per_bucket) : a.ntiles;
-  double s = 0.0, c = 0.0;   // counts are integers < 2^53: exact in binary64
-  for (int64_t i = t0 + threadIdx.x; i < t1; i += kThreads) {
-    s += a.part_sum[(int64_t)m * a.ntiles + i];
-    c += (double)a.part_cnt[(int64_t)m * a.ntiles + i];
-  }
+  // counts are integers < 2^53: exact in binary64
+  double s = strided_partial_sum(a.part_sum + (int64_t)m * a.ntiles, t0, t1);
+  double c = strided_partial_sum(a.part_cnt + (int64_t)m * a.ntiles, t0, t1);
   s = segment_sum(s, kThreads, lds_d);
   c = segment_sum(c, kThreads, lds_c);
   if (threadIdx.x == 0)

@@ -75,8 +75,7 @@ __global__ __launch_bounds__(kThreads) void seg_threshold_finalize_kernel(SegQua
   const int m = blockIdx.y;
   int64_t p0, p1;
   piece_range(a.seg, s, &p0, &p1);
-  double sum = 0.0;
-  for (int64_t i = p0 + threadIdx.x; i < p1; i += kThreads) sum += a.part_sum[(int64_t)m * a.seg.n_pieces + i];
+  double sum = strided_partial_sum(a.part_sum + (int64_t)m * a.seg.n_pieces, p0, p1);
   sum = segment_sum(sum, kThreads, lds_d);
   if (threadIdx.x == 0) {
     const int64_t n = a.seg.length[s];
@@ -137,11 +136,9 @@ __global__ __launch_bounds__(kThreads) void seg_scale_finalize_kernel(SegQuantAr
   const int m = blockIdx.y;
   int64_t p0, p1;
   piece_range(a.seg, s, &p0, &p1);
-  double sum = 0.0, cnt = 0.0;     // counts are integers < 2^53: exact in binary64
-  for (int64_t i = p0 + threadIdx.x; i < p1; i += kThreads) {
-    sum += a.part_sum[(int64_t)m * a.seg.n_pieces + i];
-    cnt += (double)a.part_cnt[(int64_t)m * a.seg.n_pieces + i];
-  }
+  // counts are integers < 2^53: exact in binary64
+  double sum = strided_partial_sum(a.part_sum + (int64_t)m * a.seg.n_pieces, p0, p1);
+  double cnt = strided_partial_sum(a.part_cnt + (int64_t)m * a.seg.n_pieces, p0, p1);
   sum = segment_sum(sum, kThreads, lds_d);
   cnt = segment_sum(cnt, kThreads, lds_c);
   if (threadIdx.x == 0)

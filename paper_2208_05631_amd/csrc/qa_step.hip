@@ -255,13 +255,14 @@ __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t 
     for (int c = 0; c < 4; ++c) acc[4 * r + c] += T[(zq[c] >> (8 * r)) & 0xFFu];
 }
 
-// NGT > 0: M is a multiple of 4*NGT, workers are taken 4*NGT at a time and every chunk has all
+// NGT > 1: M is a multiple of 4*NGT, workers are taken 4*NGT at a time and every chunk has all
 // NGT groups (straight-line code, registers and LDS sized for NGT).  NGT == 0: any M, chunks of
-// 64 workers with run-time guards.
+// 64 workers with run-time guards.  NGT == 1: any M, chunks of 4 workers with run-time guards
+// (for M <= 4, e.g. the one-worker message of a separately formed second quantization).
 template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
 __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
-  constexpr bool FULL = NGT > 0;
-  constexpr int kGroupsPerChunk = FULL ? NGT : kMaxGroups;
+  constexpr bool FULL = NGT > 1;
+  constexpr int kGroupsPerChunk = NGT >= 1 ? NGT : kMaxGroups;
   constexpr int kChunk = 4 * kGroupsPerChunk;
   constexpr int kTabEntries = kGroupsPerChunk * 256 > kTile / 2 ? kGroupsPerChunk * 256 : kTile / 2;
   __shared__ double tab[kTabEntries];                   // also carries q (4096 floats) at the end
@@ -528,6 +529,7 @@ static void launch_one(const StepArgs& a, int which, hipStream_t stream) {
     case 8: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 8>), grid, block, 0, stream, a); break;
     case 4: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 4>), grid, block, 0, stream, a); break;
     case 2: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 2>), grid, block, 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 1>), grid, block, 0, stream, a); break;
     case 0: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 0>), grid, block, 0, stream, a); break;
     default: hipLaunchKernelGGL((step_kernel<MODE, TRACK_Z, REQUANT>), grid, block, 0, stream, a); break;
   }
@@ -537,7 +539,8 @@ template <int MODE>
 static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
   int which = -1;
   if (use_lut(a))
-    which = a.M % 64 == 0 ? 16 : a.M % 32 == 0 ? 8 : a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2 : 0;
+    which = a.M % 64 == 0 ? 16 : a.M % 32 == 0 ? 8 : a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2
+            : a.M <= 4 ? 1 : 0;
   if (requant) {
     if (track_z) launch_one<MODE, true, true>(a, which, stream);
     else launch_one<MODE, false, true>(a, which, stream);
