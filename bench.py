@@ -94,9 +94,23 @@ def train_bench(args, wl, qa, synth, torch, np, dev):
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
+    graph = None
+    if args.graph:
+        # the K timed steps as ONE HIP graph (every call only enqueues kernels): one launch
+        keep = [v.clone() for v in (x, G, z)]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for t in range(args.warmup, total):
+                step(t)
+        for v, k in zip((x, G, z), keep):       # capture does not run the steps; start from the
+            v.copy_(k)                          # state after the warm-up all the same
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(args.warmup, total):
-        step(t)
+    if graph is not None:
+        graph.replay()
+    else:
+        for t in range(args.warmup, total):
+            step(t)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     out = {"metric": "full Algorithm-1 step (M local gradients + quantize+pack + fused QCMD): coordinates/s",
@@ -104,7 +118,8 @@ def train_bench(args, wl, qa, synth, torch, np, dev):
            "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{args.workload}: d={d}, n={n}, M={M}, B={B}, bucket={bucket}, "
-                                  f"{wl['train']} rows", "launches_per_step": (4 if csr else 2) + 2},
+                                  f"{wl['train']} rows", "launches_per_step": (4 if csr else 2) + 2,
+                      "hip_graph": bool(args.graph)},
            "nnz_x_after": int((x != 0).sum().item())}
     print(json.dumps(out))
 
@@ -279,6 +294,8 @@ def main():
                          "next multiple of 64 words, so that every worker's stream starts on a "
                          "256-byte boundary)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="tiny_train / sparse_train: replay the timed steps from one HIP graph")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (workers and server are slices of "

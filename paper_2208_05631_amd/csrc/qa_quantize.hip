@@ -641,6 +641,7 @@ static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 size_t quantize_workspace_bytes(const qa_layout* L) {
   if (L->bucket != 0 && L->bucket <= kTile) return 0;
+  if (L->bucket == 0 && tiles_of(L->d) == 1) return 0;   // one tile: one pass
   const int64_t nt = tiles_of(L->d), nb = buckets_of(L->d, L->bucket);
   return align256((size_t)L->M * nt * sizeof(double)) + align256((size_t)L->M * nt * sizeof(uint32_t)) +
          align256((size_t)L->M * nb * sizeof(float));
@@ -672,6 +673,12 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
     a.bucket_len = L->bucket;
     if (L->bucket == kTile) hipLaunchKernelGGL(quantize_tile_kernel, grid_tiles, block, 0, stream, a);
     else hipLaunchKernelGGL(quantize_small_bucket_kernel, grid_tiles, block, 0, stream, a);
+    return launch_status();
+  }
+  if (L->bucket == 0 && a.ntiles == 1) {                 // the whole vector is one tile: one pass
+    a.log2b = ilog2(kTile);
+    a.bucket_len = kTile;
+    hipLaunchKernelGGL(quantize_tile_kernel, grid_tiles, block, 0, stream, a);
     return launch_status();
   }
 

@@ -474,8 +474,18 @@ static qa_layout requant_layout(const qa_layout* L, int requant) {
   return R;
 }
 
+static bool forced_ordered() {
+  const char* e = getenv("QA_STEP_KERNEL");
+  return e && e[0] == 'o';
+}
+
+// Can Q(SynQ) be formed inside the step kernel?  Buckets that fit a tile; also one scale for a
+// vector that is a single tile (table-driven kernel only).
 static bool requant_in_tile(const qa_layout* L, int requant) {
-  return requant == QA_REQUANT_BUCKET && L->bucket != 0 && L->bucket <= kTile;
+  if (requant == QA_REQUANT_BUCKET) return L->bucket != 0 && L->bucket <= kTile;
+  if (requant == QA_REQUANT_GLOBAL)
+    return tiles_of(L->d) == 1 && (L->bucket == 0 || L->bucket >= kTile) && !forced_ordered();
+  return false;
 }
 
 static size_t requant_need(const qa_layout* L, const qa_layout* R) {
@@ -516,8 +526,7 @@ static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float
 static bool use_lut(const StepArgs& a) {
   if (a.seg.piece_tile) return true;                     // pieces exist only in that kernel
   if (!a.tile_uniform) return false;
-  const char* e = getenv("QA_STEP_KERNEL");
-  return !(e && e[0] == 'o');
+  return !forced_ordered();
 }
 
 // which: -1 = worker-ordered kernel, otherwise the NGT of the table-driven kernel

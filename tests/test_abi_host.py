@@ -67,8 +67,9 @@ def test_step_argument_checks():
     assert _step(ok, requant=7) == -1
     assert _step(ok, requant=qa.QA_REQUANT_BUCKET) == -1             # no buckets in this layout
     assert _step(ok, x=FAKE + 4) == -2
-    assert _step(ok, requant=qa.QA_REQUANT_GLOBAL) == -3             # needs a workspace
-    assert _step(ok, requant=qa.QA_REQUANT_GLOBAL, ws=FAKE, wsb=16) == -3
+    big = qa.Layout.make(10000, 4, 0)                                # more than one tile
+    assert _step(big, requant=qa.QA_REQUANT_GLOBAL) == -3            # needs a workspace
+    assert _step(big, requant=qa.QA_REQUANT_GLOBAL, ws=FAKE, wsb=16) == -3
     for bad in (qa.Layout.make(0, 4, 0), qa.Layout.make(1000, 0, 0), qa.Layout.make(1000, 4, 100),
                 qa.Layout.make(1000, 4, 32), qa.Layout.make(1000, 4, 0, code_stride=10),
                 qa.Layout.make(1000, 4, 64, scale_stride=3), qa.Layout.make(1000, 4, 0, thr_coef=0.0)):
@@ -90,7 +91,8 @@ def test_quantize_and_aggregate_argument_checks():
     assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 2, FAKE, 1 << 20, None) == -1   # exact, null
     assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, FAKE, 3, FAKE, 1 << 20, None) == -1   # given and exact
     assert q(C.byref(ok), FAKE + 4, 1000, FAKE, FAKE, None, 0, FAKE, 1 << 20, None) == -2
-    assert q(C.byref(ok), FAKE, 1000, FAKE, FAKE, None, 0, None, 0, None) == -3
+    big = qa.Layout.make(10000, 4, 0)                                # more than one tile: two passes
+    assert q(C.byref(big), FAKE, 10000, FAKE, FAKE, None, 0, None, 0, None) == -3
     assert B._lib.qa_aggregate_unpack(C.byref(ok), FAKE, FAKE, None, None) == -1
     assert B._lib.qa_aggregate_unpack(C.byref(ok), FAKE, FAKE, FAKE + 8, None) == -2
 

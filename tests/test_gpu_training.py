@@ -173,3 +173,54 @@ def test_sparse_highdim_logistic_regression(sparse_problem, method):
     eval_rows = rng.integers(0, p.n, 4096).astype(np.int32)
     run_parity(p, p.d, 16, 256, 4096, True, method, T, 0.1, 1e-4, 1e-8, 0, seed=1,
                eval_rows=eval_rows)
+
+
+@pytest.mark.parametrize("method,requant,bucket", [("qcmd", 0, 0), ("qrda", 2, 0), ("qcmd", 1, 256)])
+def test_training_steps_replay_identically_from_a_hip_graph(tiny_problem, method, requant, bucket):
+    """Every entry point only enqueues kernels on the given stream (no allocation, no memset, no
+    synchronisation), so T whole steps can be captured into one HIP graph.  Each of several replays,
+    with eager work and synchronisations between them, must reproduce the eager run bit for bit."""
+    prob = tiny_problem
+    d, M, B, T = 1000, 4, 64, 6
+    eta, lam, delta = 0.1, 1e-3, 1e-8
+    tr = GpuTrainer(prob, d, M, bucket, csr=False)
+    rows = [dev(synth.minibatch_rows(prob.A.shape[0], M, B, t, 0)) for t in range(1, T + 1)]
+    fmt = qa.QA_DENSE
+
+    def run_steps():
+        for t in range(1, T + 1):
+            qa.qa_local_grad_batched(fmt, tr.A, None, None, tr.n, d, tr.y, rows[t - 1], B, M, tr.x,
+                                     tr.g, tr.gs, None, tr.ws_g)
+            qa.qa_quantize_pack(tr.L, tr.g, tr.gs, tr.codes, tr.scales, None, 0, tr.ws_q)
+            if method == "qcmd":
+                qa.qa_step_qcmd(tr.L, tr.codes, tr.scales, tr.x, tr.G, tr.z, eta, lam, delta, requant,
+                                tr.ws_s)
+            else:
+                qa.qa_step_qrda(tr.L, tr.codes, tr.scales, tr.x, tr.G, tr.z, t, eta, lam, delta,
+                                requant, tr.ws_s)
+
+    def reset():
+        for v in (tr.x, tr.G, tr.z):
+            v.zero_()
+
+    reset()
+    run_steps()
+    torch.cuda.synchronize()
+    want = [host(v).copy() for v in (tr.x, tr.G, tr.z, tr.codes, tr.scales)]
+    assert np.count_nonzero(want[0]) > 0
+
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_steps()
+    for replay in range(3):
+        reset()
+        tr.codes.fill_(-1)                      # eager work between the replays
+        tr.scales.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [host(v) for v in (tr.x, tr.G, tr.z, tr.codes, tr.scales)]
+        for name, a, b in zip(("x", "G", "z", "codes", "scales"), got, want):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (replay, name)
