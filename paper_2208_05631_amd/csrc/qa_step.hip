@@ -187,15 +187,22 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 // All global loads of a tile (up to 64 code words per lane, then G, x, z in the coalesced
 // float4 mapping f = j*256 + t) are issued before any dependent work, so that the scale test,
 // the table build and the lookups run under the memory latency.
-constexpr int kMaxGroups = 16;                          // 64 workers per table set: 32 KiB of LDS
+constexpr int kMaxGroups = 4;                           // 16 workers per table set: 8 KiB of LDS
 
 struct State4 { float4 v[4]; };
 
 // Codes are read exactly once and the state is not touched again before the next step:
 // both bypass the caches' retention (nontemporal), which measurably raises HBM throughput here.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint32_t stream_load(const uint32_t* p) {
-  return __builtin_nontemporal_load(p);
+// One code word per lane through a buffer descriptor: `row` is the same for the whole wave and
+// stays in scalar registers (stepping from one worker's row to the next is scalar arithmetic),
+// byte_off is this lane's offset, offsets at or beyond row_bytes read as 0.  Streaming
+// (non-temporal) access: every code word is read exactly once.
+__device__ __forceinline__ uint32_t stream_load(const uint32_t* row, uint32_t byte_off,
+                                                uint32_t row_bytes) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(row), 0, (int)row_bytes, 0x00020000 /* 32-bit data, raw addressing */);
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 2 /* nt */);
 }
 __device__ __forceinline__ void stream_store4(float* p, const float4& v) {
   floatx4 t = {v.x, v.y, v.z, v.w};
@@ -210,7 +217,8 @@ __device__ __forceinline__ void load_state(const float* __restrict__ p, int64_t 
   for (int j = 0; j < 4; ++j) {
     const int64_t i = tile_base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
     if (full_tile || (i >= lo && i + 3 < hi)) {
-      s.v[j] = *reinterpret_cast<const float4*>(p + i);
+      const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p + i));
+      s.v[j] = make_float4(v.x, v.y, v.z, v.w);
     } else {
       float e[4];
 #pragma unroll
@@ -255,10 +263,14 @@ __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t 
     for (int c = 0; c < 4; ++c) acc[4 * r + c] += T[(zq[c] >> (8 * r)) & 0xFFu];
 }
 
-// NGT > 1: M is a multiple of 4*NGT, workers are taken 4*NGT at a time and every chunk has all
-// NGT groups (straight-line code, registers and LDS sized for NGT).  NGT == 0: any M, chunks of
-// 64 workers with run-time guards.  NGT == 1: any M, chunks of 4 workers with run-time guards
-// (for M <= 4, e.g. the one-worker message of a separately formed second quantization).
+// Workers are taken in chunks of 4*G (G groups of four, one table per group).
+//   NGT = 4 or 2: G = NGT and M is a multiple of 4*NGT: every chunk is complete, straight-line code.
+//   NGT = 0: any M, chunks of 16 workers with run-time guards.
+//   NGT = 1: any M, chunks of 4 workers with run-time guards (for M <= 4, e.g. the one-worker
+//            message of a separately formed second quantization).
+// Chunks of 16 rather than 64 workers, and the state requested only after the look-ups, keep the
+// kernel at about 100-120 vector registers, i.e. four waves per SIMD: measured faster than
+// holding all 64 code words (and the state) in registers with two waves per SIMD.
 template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
 __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   constexpr bool FULL = NGT > 1;
@@ -288,6 +300,8 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   // words of this tile that exist; lanes beyond read the last one (in bounds) and are masked
   const int64_t words_here = a.W - tile * kTileWords;
   const int tw = words_here >= kTileWords ? t : (t < (int)words_here ? t : (int)words_here - 1);
+  const uint32_t tw4 = (uint32_t)tw * 4u;
+  const uint32_t row_bytes = 4u * (uint32_t)(words_here >= kTileWords ? kTileWords : words_here);
   const bool live = t < words_here;
   const uint32_t* ctile = a.codes + tile * kTileWords;                 // uniform base
 
@@ -297,13 +311,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     const int left = a.M;
 #pragma unroll
     for (int i = 0; i < kChunk; ++i)
-      w[i] = (FULL || i < left) ? stream_load(ctile + (int64_t)i * a.code_stride + tw) : 0u;
-  }
-  State4 sG, sx, sz;
-  if (MODE != kAggregate) {
-    load_state(a.G, tile_base, lo, hi, full_tile, sG);
-    if (MODE == kQcmd) load_state(a.x, tile_base, lo, hi, full_tile, sx);
-    if (MODE == kQrda || TRACK_Z) load_state(a.z, tile_base, lo, hi, full_tile, sz);
+      w[i] = (FULL || i < left) ? stream_load(ctile + (int64_t)i * a.code_stride, tw4, row_bytes) : 0u;
   }
 
   // ---- can the sum over workers be reordered? (exponent span of the tile's scales) ----
@@ -347,16 +355,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       const int f = (t >> (2 * j)) & 3;
       dj[j] = f == 1 ? 1.0 : (f == 3 ? -1.0 : 0.0);
     }
-    for (int m0 = 0; m0 < a.M; m0 += kChunk) {
+    // tables of the chunk that starts at worker m0, then the look-ups of its code words wc
+    auto chunk = [&](const uint32_t (&wc)[kChunk], int m0) {
       const int left = a.M - m0;
       const int ng = (FULL || left >= kChunk) ? kGroupsPerChunk : (left + 3) / 4;
-      if (m0 > 0) {
-        const uint32_t* cc = ctile + (int64_t)m0 * a.code_stride;
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i)
-          w[i] = (FULL || i < left) ? stream_load(cc + (int64_t)i * a.code_stride + tw) : 0u;
-        __syncthreads();                                 // readers of the previous tables are done
-      }
+      if (m0 > 0) __syncthreads();                       // readers of the previous tables are done
       if (t < kChunk) s_scale[t] = t < left ? (double)sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0;
       __syncthreads();
       for (int g = 0; g < ng; ++g) {
@@ -369,7 +372,17 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 #pragma unroll
       for (int g = 0; g < kGroupsPerChunk; ++g)
         if (FULL || g < ng)
-          lookup_group(w[4 * g], w[4 * g + 1], w[4 * g + 2], w[4 * g + 3], tab + g * 256, acc);
+          lookup_group(wc[4 * g], wc[4 * g + 1], wc[4 * g + 2], wc[4 * g + 3], tab + g * 256, acc);
+    };
+    for (int m0 = 0; m0 < a.M; m0 += kChunk) {
+      if (m0 > 0) {
+        const int left = a.M - m0;
+        const uint32_t* cc = ctile + (int64_t)m0 * a.code_stride;
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+          w[i] = (FULL || i < left) ? stream_load(cc + (int64_t)i * a.code_stride, tw4, row_bytes) : 0u;
+      }
+      chunk(w, m0);
     }
   } else {
     // ordered loop, as the sum is written: worker 0, 1, 2, ...
@@ -382,6 +395,15 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
         acc[j] = fma((double)c, s, acc[j]);
       }
     }
+  }
+
+  // The state is requested only now: held in registers during the look-ups it would cost a wave
+  // per SIMD, and the other waves of the SIMD cover its latency.
+  State4 sG, sx, sz;
+  if (MODE != kAggregate) {
+    load_state(a.G, tile_base, lo, hi, full_tile, sG);
+    if (MODE == kQcmd) load_state(a.x, tile_base, lo, hi, full_tile, sx);
+    if (MODE == kQrda || TRACK_Z) load_state(a.z, tile_base, lo, hi, full_tile, sz);
   }
 
   float q[16];
@@ -429,6 +451,25 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     *reinterpret_cast<float4*>(qt + 16 * t + 4 * v) =
         make_float4(q[4 * v], q[4 * v + 1], q[4 * v + 2], q[4 * v + 3]);
   __syncthreads();
+  if (full_tile && MODE != kAggregate) {
+    // whole tile: each float4 group is updated and stored as soon as its q is read back
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 qv = *reinterpret_cast<const float4*>(qt + 4 * (j * kThreads + t));
+      const float qq[4] = {qv.x, qv.y, qv.z, qv.w};
+      float G[4] = {sG.v[j].x, sG.v[j].y, sG.v[j].z, sG.v[j].w};
+      float x[4] = {0.f, 0.f, 0.f, 0.f}, z[4] = {0.f, 0.f, 0.f, 0.f};
+      if (MODE == kQcmd) { x[0] = sx.v[j].x; x[1] = sx.v[j].y; x[2] = sx.v[j].z; x[3] = sx.v[j].w; }
+      if (MODE == kQrda || TRACK_Z) { z[0] = sz.v[j].x; z[1] = sz.v[j].y; z[2] = sz.v[j].z; z[3] = sz.v[j].w; }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) update_coordinate<MODE, TRACK_Z>(a, qq[e], x[e], G[e], z[e]);
+      const int64_t i = tile_base + (int64_t)(j * kThreads + t) * 4;
+      stream_store4(a.G + i, make_float4(G[0], G[1], G[2], G[3]));
+      stream_store4(a.x + i, make_float4(x[0], x[1], x[2], x[3]));
+      if (MODE == kQrda || TRACK_Z) stream_store4(a.z + i, make_float4(z[0], z[1], z[2], z[3]));
+    }
+    return;
+  }
   State4 sq;
 #pragma unroll
   for (int j = 0; j < 4; ++j) sq.v[j] = *reinterpret_cast<const float4*>(qt + 4 * (j * kThreads + t));
@@ -530,16 +571,19 @@ static bool use_lut(const StepArgs& a) {
 }
 
 // which: -1 = worker-ordered kernel, otherwise the NGT of the table-driven kernel
+template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
+static void launch_lut(const StepArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
+  hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, NGT>), grid, block, 0, stream, a);
+}
+
 template <int MODE, bool TRACK_Z, bool REQUANT>
 static void launch_one(const StepArgs& a, int which, hipStream_t stream) {
   const dim3 grid((unsigned)(a.seg.piece_tile ? a.seg.n_pieces : tiles_of(a.d))), block(kThreads);
   switch (which) {
-    case 16: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 16>), grid, block, 0, stream, a); break;
-    case 8: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 8>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 4>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 2>), grid, block, 0, stream, a); break;
-    case 1: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 1>), grid, block, 0, stream, a); break;
-    case 0: hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, 0>), grid, block, 0, stream, a); break;
+    case 4: launch_lut<MODE, TRACK_Z, REQUANT, 4>(a, grid, block, stream); break;
+    case 2: launch_lut<MODE, TRACK_Z, REQUANT, 2>(a, grid, block, stream); break;
+    case 1: launch_lut<MODE, TRACK_Z, REQUANT, 1>(a, grid, block, stream); break;
+    case 0: launch_lut<MODE, TRACK_Z, REQUANT, 0>(a, grid, block, stream); break;
     default: hipLaunchKernelGGL((step_kernel<MODE, TRACK_Z, REQUANT>), grid, block, 0, stream, a); break;
   }
 }
@@ -548,8 +592,7 @@ template <int MODE>
 static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
   int which = -1;
   if (use_lut(a))
-    which = a.M % 64 == 0 ? 16 : a.M % 32 == 0 ? 8 : a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2
-            : a.M <= 4 ? 1 : 0;
+    which = a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2 : a.M <= 4 ? 1 : 0;
   if (requant) {
     if (track_z) launch_one<MODE, true, true>(a, which, stream);
     else launch_one<MODE, false, true>(a, which, stream);
