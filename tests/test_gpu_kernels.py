@@ -176,6 +176,8 @@ STEP_CASES = [
     (70001, 64, 4096, 0), (70001, 32, 4096, 1), (70001, 6, 4096, 2), (70001, 4, 16384, 1),
     (70001, 4, 16384, 0), (300001, 8, 4096, 0), (50001, 130, 4096, 0), (50001, 67, 4096, 1),
     (20000, 128, 4096, 1),
+    # chunking of the table-driven kernel: 3 chunks of 8, 3 chunks of 16, guarded chunks (20 = 16 + 4, 12)
+    (9000, 24, 4096, 0), (9000, 48, 4096, 1), (9000, 20, 0, 0), (9000, 12, 4096, 2), (9000, 40, 8192, 0),
 ]
 
 
