@@ -419,6 +419,19 @@ def main():
         bpc = algorithmic_bytes_per_coord("qcmd", M)
         also["qcmd"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
                         "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+        # the paper's double quantization at bucket granularity, formed inside the same kernel
+        if 0 < bucket <= 4096:
+            rq = qa.QA_REQUANT_BUCKET
+            qa.qa_step_qcmd(L, codes, scales, x, G, z, eta, lam, delta, rq, None)
+            e0.record()
+            for _ in range(3):
+                qa.qa_step_qcmd(L, codes, scales, x, G, z, eta, lam, delta, rq, None)
+            e1.record()
+            torch.cuda.synchronize()
+            avg = e0.elapsed_time(e1) / 3
+            bpc = algorithmic_bytes_per_coord("qcmd_z", M)
+            also["qcmd_z_requant_bucket"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
+                                             "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
 
     out = {
         "metric": "fused QCMD/QRDA step: coordinates/s and achieved HBM GB/s (% peak), 1 MI355X",
