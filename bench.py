@@ -397,8 +397,9 @@ def main():
     for k, ms in per_kind.items():
         avg = float(np.mean(ms))
         bpc = algorithmic_bytes_per_coord(k, M)
-        if requant:      # separate passes: average out (M/4 + 4), quantize it (8.25), update from it
-            bpc = (M / 4 + 4) + 8.25 + (bpc - M / 4 + 0.25)
+        if requant:      # separate passes: average out (M/4 + 4; also leaves the quantizer's tile
+            # sums), quantize it (4.25: one pass over it), update from its codes (0.25 + state)
+            bpc = (M / 4 + 4) + 4.25 + (bpc - M / 4 + 0.25)
         kernels[k] = {"avg_ms": avg, "launches": len(ms), "bytes_per_coord": bpc,
                       "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])

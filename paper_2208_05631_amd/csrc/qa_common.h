@@ -37,6 +37,11 @@ inline int check_layout(const qa_layout* L) {
   return QA_OK;
 }
 
+// Internal flag of quantize_launch (never accepted from the C ABI): the tile sums of |v| are
+// already in the workspace, whose first M*ntiles doubles hold them (worker-major), so the first
+// pass over the input is skipped.  Used when the producer of the input computed them on the way.
+constexpr uint32_t kQuantAbsPartialsGiven = 0x80000000u;
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? QA_OK : QA_ERR_LAUNCH; }
 
 // ---- device-side reductions (binary64, fixed order: run-to-run deterministic) -----------

@@ -697,7 +697,8 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   const dim3 grid_buckets((unsigned)a.nb, (unsigned)L->M);
 
   if (!a.thresh_given) {
-    hipLaunchKernelGGL(quantize_abs_partial_kernel, grid_tiles, block, 0, stream, a);
+    if (!(flags & kQuantAbsPartialsGiven))
+      hipLaunchKernelGGL(quantize_abs_partial_kernel, grid_tiles, block, 0, stream, a);
     hipLaunchKernelGGL(quantize_threshold_finalize_kernel, grid_buckets, block, 0, stream, a);
   }
   hipLaunchKernelGGL(quantize_codes_partial_kernel, grid_tiles, block, 0, stream, a);

@@ -26,6 +26,7 @@ struct StepArgs {
   int tile_uniform;   // all coordinates of a 4096-tile share their scales
   int span_limit;     // max exponent span of a tile's scales for which any order is exact
   float* x; float* G; float* z; float* gbar;
+  double* abs_partials;   // aggregate mode, optional: sum of |gbar| of each tile (first pass of a quantizer)
   float eta, lam_eta, delta, t_lam, thr_coef;
   SegTable seg;       // tensor-list launches: work-group = piece, one scale column per tensor
 };
@@ -422,6 +423,14 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       if (i0 + j < lo || i0 + j >= hi) q[j] = 0.0f;
   }
 
+  if (MODE == kAggregate && a.abs_partials) {             // uniform
+    double s1 = 0.0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);
+    s1 = block_sum_f64(s1, lds_d);
+    if (t == 0) a.abs_partials[tile] = s1;
+  }
+
   if (REQUANT) {                                          // bucket == 4096 == the tile
     double s1 = 0.0;
 #pragma unroll
@@ -642,9 +651,14 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
       const size_t qws = quantize_workspace_bytes(&R);
       StepArgs ag = make_args(L, codes, scales);
       ag.gbar = gbar;
+      // the table-driven kernel also leaves the quantizer's first pass (tile sums of |gbar|) in
+      // the quantizer's workspace
+      const bool fuse_abs = qws != 0 && use_lut(ag);
+      if (fuse_abs) ag.abs_partials = reinterpret_cast<double*>(p);
       launch_mode<kAggregate>(ag, false, false, stream);
       const int64_t gs = (L->d + 3) & ~int64_t(3);
-      rc = quantize_launch(&R, gbar, gs, c1, s1, th1, 0, qws ? p : nullptr, qws, stream);
+      rc = quantize_launch(&R, gbar, gs, c1, s1, th1, fuse_abs ? kQuantAbsPartialsGiven : 0u,
+                           qws ? p : nullptr, qws, stream);
       if (rc != QA_OK) return rc;
       use = &R; use_codes = c1; use_scales = s1;
     }
