@@ -303,10 +303,9 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   const int tw = words_here >= kTileWords ? t : (t < (int)words_here ? t : (int)words_here - 1);
   const uint32_t tw4 = (uint32_t)tw * 4u;
   const uint32_t row_bytes = 4u * (uint32_t)(words_here >= kTileWords ? kTileWords : words_here);
-  const bool live = t < words_here;
   const uint32_t* ctile = a.codes + tile * kTileWords;                 // uniform base
 
-  // ---- issue the global loads: first chunk of code words, then the state ----
+  // ---- request the first chunk of code words ----
   uint32_t w[kChunk];
   {
     const int left = a.M;
