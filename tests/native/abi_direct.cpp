@@ -1,0 +1,137 @@
+// Calls libqadagrad through its C ABI from a plain C++ host program: no Python, no torch, device
+// memory from hipMalloc.  One worker-side quantize+pack and T fused QCMD and QRDA steps are
+// compared bit for bit with the CPU checker (oracle/liboracle.so), which this TEST links as well.
+// Exit status 0 = identical.  Built by __graft_entry__.build(); run by tests/test_gpu_native.py.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "qadagrad.h"
+
+extern "C" {
+void orc_quantize_pack(const float* g, int64_t g_stride, int64_t d, int M, int64_t bucket,
+                       float thr_coef, uint32_t* codes, int64_t code_stride, float* scales,
+                       float* thresholds, int64_t scale_stride, int thresholds_given);
+void orc_step_qcmd(const uint32_t* codes, int64_t code_stride, const float* scales,
+                   int64_t scale_stride, int64_t d, int M, int64_t bucket, float thr_coef, float* x,
+                   float* G, float* z_or_null, float eta, float lambda, float delta, int requant);
+void orc_step_qrda(const uint32_t* codes, int64_t code_stride, const float* scales,
+                   int64_t scale_stride, int64_t d, int M, int64_t bucket, float thr_coef, float* x,
+                   float* G, float* z, int64_t t, float eta, float lambda, float delta, int requant);
+}
+
+#define HIP_OK(call)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      std::fprintf(stderr, "%s:%d %s\n", __FILE__, __LINE__, hipGetErrorString(e_));   \
+      return 2;                                                                        \
+    }                                                                                  \
+  } while (0)
+#define QA_CALL(call)                                                                  \
+  do {                                                                                 \
+    int rc_ = (call);                                                                  \
+    if (rc_ != QA_OK) {                                                                \
+      std::fprintf(stderr, "%s:%d %s\n", __FILE__, __LINE__, qa_strerror(rc_));        \
+      return 3;                                                                        \
+    }                                                                                  \
+  } while (0)
+
+// seeded, synthetic: a sparse heavy-tailed gradient from a 64-bit LCG
+static void fill_gradient(std::vector<float>& g, uint64_t seed) {
+  uint64_t s = seed * 0x9E3779B97F4A7C15ull + 1;
+  for (auto& v : g) {
+    s = s * 6364136223846793005ull + 1442695040888963407ull;
+    const uint32_t r = (uint32_t)(s >> 33);
+    const float u = (float)(r & 0xFFFF) / 65536.0f - 0.5f;
+    v = (r >> 16) % 10 < 3 ? u * u * u * 0.08f : 0.0f;
+  }
+}
+
+template <typename T>
+static bool same(const std::vector<T>& a, const std::vector<T>& b, const char* what) {
+  if (a.size() == b.size() && std::memcmp(a.data(), b.data(), a.size() * sizeof(T)) == 0) return true;
+  std::fprintf(stderr, "MISMATCH in %s\n", what);
+  return false;
+}
+
+int main() {
+  const int64_t d = 70001;
+  const int M = 8, bucket = 4096, T = 4;
+  const float eta = 0.1f, lambda = 2e-4f, delta = 1e-8f;
+  qa_layout L;
+  L.d = d; L.M = M; L.bucket = bucket; L.thr_coef = 0.75f;
+  L.code_stride = (d + 15) / 16 + 5;                       // padded rows on purpose
+  L.scale_stride = (d + bucket - 1) / bucket + 3;
+  const int64_t gs = (d + 3) / 4 * 4;
+
+  float *dg, *dx, *dG, *dz, *dscales;
+  uint32_t* dcodes;
+  HIP_OK(hipMalloc(&dg, sizeof(float) * M * gs));
+  HIP_OK(hipMalloc(&dcodes, sizeof(uint32_t) * M * L.code_stride));
+  HIP_OK(hipMalloc(&dscales, sizeof(float) * M * L.scale_stride));
+  HIP_OK(hipMalloc(&dx, sizeof(float) * d));
+  HIP_OK(hipMalloc(&dG, sizeof(float) * d));
+  HIP_OK(hipMalloc(&dz, sizeof(float) * d));
+  HIP_OK(hipMemset(dx, 0, sizeof(float) * d));
+  HIP_OK(hipMemset(dG, 0, sizeof(float) * d));
+  HIP_OK(hipMemset(dz, 0, sizeof(float) * d));
+  HIP_OK(hipMemset(dcodes, 0, sizeof(uint32_t) * M * L.code_stride));
+  HIP_OK(hipMemset(dscales, 0, sizeof(float) * M * L.scale_stride));
+  hipStream_t stream;
+  HIP_OK(hipStreamCreate(&stream));
+  if (qa_version() != QA_VERSION) { std::fprintf(stderr, "version\n"); return 4; }
+  if (qa_workspace_bytes(&L, QA_OP_QUANTIZE) != 0) { std::fprintf(stderr, "workspace\n"); return 4; }
+
+  std::vector<float> g((size_t)M * gs), ox(d, 0.f), oG(d, 0.f), oz(d, 0.f);
+  std::vector<uint32_t> oc((size_t)M * L.code_stride, 0u), hc(oc.size());
+  std::vector<float> os((size_t)M * L.scale_stride, 0.f), hs(os.size()), hx(d), hG(d), hz(d);
+  bool ok = true;
+  for (int t = 1; t <= T && ok; ++t) {
+    fill_gradient(g, (uint64_t)t);
+    HIP_OK(hipMemcpyAsync(dg, g.data(), sizeof(float) * g.size(), hipMemcpyHostToDevice, stream));
+    QA_CALL(qa_quantize_pack(&L, dg, gs, dcodes, dscales, nullptr, 0, nullptr, 0, stream));
+    if (t % 2)
+      QA_CALL(qa_step_qcmd(&L, dcodes, dscales, dx, dG, dz, eta, lambda, delta, QA_REQUANT_BUCKET,
+                           nullptr, 0, stream));
+    else
+      QA_CALL(qa_step_qrda(&L, dcodes, dscales, dx, dG, dz, t, eta, lambda, delta, QA_REQUANT_NONE,
+                           nullptr, 0, stream));
+    HIP_OK(hipMemcpyAsync(hc.data(), dcodes, sizeof(uint32_t) * hc.size(), hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(hs.data(), dscales, sizeof(float) * hs.size(), hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(hx.data(), dx, sizeof(float) * d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(hG.data(), dG, sizeof(float) * d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(hz.data(), dz, sizeof(float) * d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipStreamSynchronize(stream));
+
+    orc_quantize_pack(g.data(), gs, d, M, bucket, 0.75f, oc.data(), L.code_stride, os.data(), nullptr,
+                      L.scale_stride, 0);
+    if (t % 2)
+      orc_step_qcmd(oc.data(), L.code_stride, os.data(), L.scale_stride, d, M, bucket, 0.75f, ox.data(),
+                    oG.data(), oz.data(), eta, lambda, delta, 1);
+    else
+      orc_step_qrda(oc.data(), L.code_stride, os.data(), L.scale_stride, d, M, bucket, 0.75f, ox.data(),
+                    oG.data(), oz.data(), t, eta, lambda, delta, 0);
+    // rows are padded: compare what the layout defines
+    for (int m = 0; m < M && ok; ++m) {
+      const size_t W = (size_t)((d + 15) / 16), nb = (size_t)((d + bucket - 1) / bucket);
+      ok = ok && std::memcmp(&hc[m * L.code_stride], &oc[m * L.code_stride], W * 4) == 0 &&
+           std::memcmp(&hs[m * L.scale_stride], &os[m * L.scale_stride], nb * 4) == 0;
+      if (!ok) std::fprintf(stderr, "MISMATCH in codes/scales of worker %d, step %d\n", m, t);
+    }
+    ok = ok && same(hx, ox, "x") && same(hG, oG, "G") && same(hz, oz, "z");
+    size_t nz = 0;
+    for (float v : hx) nz += v != 0.0f;
+    std::printf("step %d: %s, %zu non-zero parameters\n", t, ok ? "identical" : "DIFFERENT", nz);
+  }
+  // error path through the same ABI: nothing is launched
+  if (qa_step_qcmd(&L, dcodes, dscales, dx, dG, nullptr, -1.0f, lambda, delta, 0, nullptr, 0, stream) !=
+      QA_ERR_INVALID_ARG) { std::fprintf(stderr, "error path\n"); ok = false; }
+  (void)hipStreamDestroy(stream);
+  (void)hipFree(dg); (void)hipFree(dcodes); (void)hipFree(dscales);
+  (void)hipFree(dx); (void)hipFree(dG); (void)hipFree(dz);
+  return ok ? 0 : 1;
+}
