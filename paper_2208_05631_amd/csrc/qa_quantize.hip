@@ -85,88 +85,195 @@ __device__ __forceinline__ void kept_sums(const float v[4], float Delta, double*
   *s_out = s; *c_out = c;
 }
 
-// ---- bucket <= 4096 : single pass ----------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void quantize_small_bucket_kernel(QuantArgs a) {
-  __shared__ double lds_d[kWaves];
-  __shared__ uint32_t lds_u[kWaves];
+// ---- 64 <= bucket < 4096 : single pass, several buckets per tile --------------------------------
+//
+// Slice j of the tile (elements j*1024 .. j*1024+1023) is held four elements per thread, so a
+// bucket of b <= 1024 elements is SEG = b/4 consecutive threads of one slice, and a bucket of 2048
+// is two whole slices.  Sums over 16 lanes use DPP, 32 and 64 lanes one more cross-row step, and
+// larger segments one LDS exchange for all four slices at once: no barrier for b <= 256, one per
+// phase otherwise.  Every thread receives the sums of its own buckets.
+template <int SEG>
+__device__ __forceinline__ double lanes_sum_f64(double v) {
+  v += dpp_f64<kDppQuadXor1>(v);
+  v += dpp_f64<kDppQuadXor2>(v);
+  v += dpp_f64<kDppRowHalfMirror>(v);
+  v += dpp_f64<kDppRowMirror>(v);                        // sum of the row of 16
+  if (SEG == 32) v += shfl_xor_f64(v, 16);
+  if (SEG >= 64)
+    v = (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
+  return v;
+}
+template <int SEG>
+__device__ __forceinline__ uint32_t lanes_sum_u32(uint32_t v) {
+  v += (uint32_t)dpp_i32<kDppQuadXor1>((int)v);
+  v += (uint32_t)dpp_i32<kDppQuadXor2>((int)v);
+  v += (uint32_t)dpp_i32<kDppRowHalfMirror>((int)v);
+  v += (uint32_t)dpp_i32<kDppRowMirror>((int)v);
+  if (SEG == 32) v += (uint32_t)__shfl_xor((int)v, 16, kWave);
+  if (SEG >= 64)
+    v = (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+        (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return v;
+}
+
+// s[j], c[j]: this thread's part of slice j -> the sums over its bucket.  LOG2B = log2(bucket).
+// lds: 16 doubles and 16 words nobody else uses; the caller's threads all take part.
+template <int LOG2B, bool WITH_COUNT>
+__device__ __forceinline__ void bucket_sums(double s[4], uint32_t c[4], double* lds_s, uint32_t* lds_c) {
+  constexpr int SEG = LOG2B >= 10 ? 256 : (1 << LOG2B) / 4;     // threads per bucket within a slice
+  constexpr int LANES = SEG < 64 ? SEG : 64;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    s[j] = lanes_sum_f64<LANES>(s[j]);
+    if (WITH_COUNT) c[j] = lanes_sum_u32<LANES>(c[j]);
+  }
+  if (SEG > 64) {
+    const int wave = threadIdx.x / kWave;
+    __syncthreads();                                     // earlier readers of lds are done
+    if ((threadIdx.x % kWave) == 0) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lds_s[j * kWaves + wave] = s[j];
+        if (WITH_COUNT) lds_c[j * kWaves + wave] = c[j];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (SEG == 128) {                                  // waves {0,1} and {2,3}
+        const int w0 = wave & ~1;
+        s[j] = lds_s[j * kWaves + w0] + lds_s[j * kWaves + w0 + 1];
+        if (WITH_COUNT) c[j] = lds_c[j * kWaves + w0] + lds_c[j * kWaves + w0 + 1];
+      } else {
+        s[j] = (lds_s[j * kWaves] + lds_s[j * kWaves + 1]) + (lds_s[j * kWaves + 2] + lds_s[j * kWaves + 3]);
+        if (WITH_COUNT)
+          c[j] = lds_c[j * kWaves] + lds_c[j * kWaves + 1] + lds_c[j * kWaves + 2] + lds_c[j * kWaves + 3];
+      }
+    }
+    if (LOG2B == 11) {                                   // a bucket is two slices
+      const double s01 = s[0] + s[1], s23 = s[2] + s[3];
+      s[0] = s[1] = s01; s[2] = s[3] = s23;
+      if (WITH_COUNT) {
+        const uint32_t c01 = c[0] + c[1], c23 = c[2] + c[3];
+        c[0] = c[1] = c01; c[2] = c[3] = c23;
+      }
+    }
+  }
+}
+
+template <int LOG2B>
+__global__ __launch_bounds__(kThreads) void quantize_bucket_kernel(QuantArgs a) {
+  __shared__ double lds_s[4 * kWaves];
+  __shared__ uint32_t lds_c[4 * kWaves];
+  constexpr int b = 1 << LOG2B;
   const int64_t tile = blockIdx.x;
   const int m = blockIdx.y;
   const float* g = a.g + (int64_t)m * a.g_stride;
   const int t = threadIdx.x;
-  const int b = 1 << a.log2b;
+  const bool whole = (tile + 1) * kTile <= a.d;          // the vector does not end inside the tile
 
   float v[4][4];
-  load_tile(g, a.d, tile, v);
-
-  // threads per bucket inside one j-slice (a slice is 1024 consecutive elements)
-  const int seg = b >= 1024 ? kThreads : b / 4;
-  float Delta[4];
-  int64_t kidx[4];
+  if (whole) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    kidx[j] = (tile * kTile + (int64_t)(j * kThreads + t) * 4) >> a.log2b;
+    for (int j = 0; j < 4; ++j) {
+      typedef float floatx4 __attribute__((ext_vector_type(4)));
+      const floatx4 q = __builtin_nontemporal_load(
+          reinterpret_cast<const floatx4*>(g + tile * kTile + (j * kThreads + t) * 4));
+      v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    }
+  } else {
+    load_tile(g, a.d, tile, v);
+  }
+  float Delta[4];
+  const int64_t k0 = tile * (kTile >> LOG2B);            // first bucket of the tile
+  int kb[4];                                             // bucket of slice j within the tile
+#pragma unroll
+  for (int j = 0; j < 4; ++j) kb[j] = ((j * kThreads + t) * 4) >> LOG2B;
 
   if (!a.thresh_given) {
     double S1[4];
+    uint32_t unused[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      double s = 0.0;
+      S1[j] = (double)fabsf(v[j][0]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
-      S1[j] = segment_sum(s, seg, lds_d);
+      for (int e = 1; e < 4; ++e) S1[j] += (double)fabsf(v[j][e]);
     }
-    if (b == 2048) {
-      const double s01 = S1[0] + S1[1], s23 = S1[2] + S1[3];
-      S1[0] = S1[1] = s01; S1[2] = S1[3] = s23;
-    } else if (b == 4096) {
-      const double s = (S1[0] + S1[1]) + (S1[2] + S1[3]);
-      S1[0] = S1[1] = S1[2] = S1[3] = s;
-    }
+    bucket_sums<LOG2B, false>(S1, unused, lds_s, lds_c);
+    // Every bucket of the tile is complete unless the vector ends inside the tile; dividing by
+    // the power of two b is then an exact scaling, the same value as the division.
+    if (whole) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int64_t lo = kidx[j] << a.log2b;
-      const int64_t n = (a.d - lo) < (int64_t)b ? (a.d - lo) : (int64_t)b;   // true length
-      Delta[j] = n > 0 ? threshold_from_sum(S1[j], a.thr_coef, n) : 0.0f;
+      for (int j = 0; j < 4; ++j)
+        Delta[j] = (float)(((double)a.thr_coef * S1[j]) * (1.0 / (double)b));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int64_t lo = (k0 + kb[j]) << LOG2B;
+        const int64_t n = (a.d - lo) < (int64_t)b ? (a.d - lo) : (int64_t)b;   // true length
+        Delta[j] = n > 0 ? threshold_from_sum(S1[j], a.thr_coef, n) : 0.0f;
+      }
     }
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      Delta[j] = kidx[j] < a.nb ? a.thresholds[(int64_t)m * a.scale_stride + kidx[j]] : 0.0f;
+      Delta[j] = k0 + kb[j] < a.nb ? a.thresholds[(int64_t)m * a.scale_stride + k0 + kb[j]] : 0.0f;
   }
 
+  // kept sums, counts and 2-bit fields; for Delta >= 0 the field of a kept element is
+  // 01 | sign << 1, a negative (given) threshold takes the two plain comparisons
   double S2[4];
   uint32_t C[4];
+  uint32_t mine = 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    double s; uint32_t c;
-    kept_sums(v[j], Delta[j], &s, &c);
-    S2[j] = segment_sum(s, seg, lds_d);
-    C[j] = segment_sum_u32(c, seg, lds_u);
+    const bool plain = Delta[j] < 0.0f;
+    double s2 = 0.0;
+    uint32_t c = 0, bits = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float av = fabsf(v[j][e]);
+      const bool keep = av > Delta[j];
+      s2 += (double)(keep ? av : 0.0f);
+      c += keep ? 1u : 0u;
+      const uint32_t pat = 1u | ((__float_as_uint(v[j][e]) >> 30) & 2u);
+      const uint32_t f = plain ? ternary_field(v[j][e], Delta[j]) : (keep ? pat : 0u);
+      bits |= f << (2 * e);
+    }
+    S2[j] = s2; C[j] = c;
+    uint32_t w = bits << (8 * (t & 3));
+    w |= (uint32_t)dpp_i32<kDppQuadXor1>((int)w);
+    w |= (uint32_t)dpp_i32<kDppQuadXor2>((int)w);
+    if ((t & 3) == j) mine = w;
   }
-  if (b == 2048) {
-    const double s01 = S2[0] + S2[1], s23 = S2[2] + S2[3];
-    S2[0] = S2[1] = s01; S2[2] = S2[3] = s23;
-    const uint32_t c01 = C[0] + C[1], c23 = C[2] + C[3];
-    C[0] = C[1] = c01; C[2] = C[3] = c23;
-  } else if (b == 4096) {
-    const double s = (S2[0] + S2[1]) + (S2[2] + S2[3]);
-    S2[0] = S2[1] = S2[2] = S2[3] = s;
-    const uint32_t c = C[0] + C[1] + C[2] + C[3];
-    C[0] = C[1] = C[2] = C[3] = c;
+  {
+    const int64_t widx = tile * kTileWords + (t & 3) * 64 + (t >> 2);
+    if (widx < a.W) (a.codes + (int64_t)m * a.code_stride)[widx] = mine;
   }
+  bucket_sums<LOG2B, true>(S2, C, lds_s, lds_c);
 
-  // the thread holding a bucket's first element writes its scale and threshold
+  // The thread holding a bucket's first element hands (sum, count, threshold) of the bucket to
+  // LDS; thread k of the work-group then divides for bucket k of the tile, so that a wave runs
+  // the binary64 division once instead of once per slice.
+  constexpr int kBucketsPerTile = kTile >> LOG2B;
+  __shared__ double out_s[kBucketsPerTile];
+  __shared__ uint32_t out_c[kBucketsPerTile];
+  __shared__ float out_d[kBucketsPerTile];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int64_t first_elem = kidx[j] << a.log2b;
-    const int64_t my_elem = tile * kTile + (int64_t)(j * kThreads + t) * 4;
-    if (my_elem == first_elem && kidx[j] < a.nb) {
-      a.scales[(int64_t)m * a.scale_stride + kidx[j]] = scale_from_sum(S2[j], C[j]);
-      if (a.thresholds && !a.thresh_given)
-        a.thresholds[(int64_t)m * a.scale_stride + kidx[j]] = Delta[j];
+    const int e0 = (j * kThreads + t) * 4;               // first element of this thread in slice j
+    if ((e0 & (b - 1)) == 0) {
+      out_s[e0 >> LOG2B] = S2[j]; out_c[e0 >> LOG2B] = C[j]; out_d[e0 >> LOG2B] = Delta[j];
     }
   }
-  pack_and_store(v, Delta, a.codes + (int64_t)m * a.code_stride, tile, a.W);
+  __syncthreads();
+  if (t < kBucketsPerTile) {
+    const int64_t k = tile * kBucketsPerTile + t;
+    if (k < a.nb) {
+      a.scales[(int64_t)m * a.scale_stride + k] = scale_from_sum(out_s[t], out_c[t]);
+      if (a.thresholds && !a.thresh_given) a.thresholds[(int64_t)m * a.scale_stride + k] = out_d[t];
+    }
+  }
 }
 
 // ---- bucket == 4096 == the tile : single pass, two work-group reductions ---------------------
@@ -671,8 +778,15 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   if (L->bucket != 0 && L->bucket <= kTile) {
     a.log2b = ilog2(L->bucket);
     a.bucket_len = L->bucket;
-    if (L->bucket == kTile) hipLaunchKernelGGL(quantize_tile_kernel, grid_tiles, block, 0, stream, a);
-    else hipLaunchKernelGGL(quantize_small_bucket_kernel, grid_tiles, block, 0, stream, a);
+    switch (a.log2b) {
+      case 6: hipLaunchKernelGGL(quantize_bucket_kernel<6>, grid_tiles, block, 0, stream, a); break;
+      case 7: hipLaunchKernelGGL(quantize_bucket_kernel<7>, grid_tiles, block, 0, stream, a); break;
+      case 8: hipLaunchKernelGGL(quantize_bucket_kernel<8>, grid_tiles, block, 0, stream, a); break;
+      case 9: hipLaunchKernelGGL(quantize_bucket_kernel<9>, grid_tiles, block, 0, stream, a); break;
+      case 10: hipLaunchKernelGGL(quantize_bucket_kernel<10>, grid_tiles, block, 0, stream, a); break;
+      case 11: hipLaunchKernelGGL(quantize_bucket_kernel<11>, grid_tiles, block, 0, stream, a); break;
+      default: hipLaunchKernelGGL(quantize_tile_kernel, grid_tiles, block, 0, stream, a); break;
+    }
     return launch_status();
   }
   if (L->bucket == 0 && a.ntiles == 1) {                 // the whole vector is one tile: one pass
