@@ -234,6 +234,17 @@ int qa_quantize_pack_selected(const qa_layout* layout, const float* g, int64_t g
 int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
                        const uint32_t* sel_codes, uint32_t* codes_out, void* stream);
 
+/* S applied to coded messages (Algorithm 1, server: "Push S(q_t, I^Syn) and I^Syn to every
+ * worker"): for each of the M messages codes[m*code_stride + w] (dense 2-bit layout, e.g. the
+ * one-worker message that qa_aggregate_unpack followed by qa_quantize_pack produces for q_t), the
+ * codes of the marked components, in index order, are packed per bucket exactly like the output of
+ * qa_quantize_pack_selected: from bit 0 of word sel_codes[m*code_stride + k*256], only the first
+ * ceil(count/16) words of an area are written; counts[m*scale_stride + k] = marked components of
+ * bucket k.  ind_stride = 0 applies the same indicator (the synchronous one) to every message.
+ * qa_decode_selected is the inverse on the marked components.  Not in place. */
+int qa_select_codes(const qa_layout* layout, const uint32_t* codes, const uint32_t* ind,
+                    int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts, void* stream);
+
 /* ---- a list of parameter tensors in one flat vector --------------------------------------------
  *
  * For models whose parameters are many tensors of very different sizes (the convolutional

@@ -81,6 +81,7 @@ def _declare(L):
     L.orc_indicator_or.argtypes = [_u32p, _i64, _i32, _i64, _u32p]
     L.orc_quantize_selected.argtypes = [_f32p, _u32p, _i64, _i64, _f32, _u32p, _u32p, _f32p, _f32p]
     L.orc_decode_selected.argtypes = [_u32p, _u32p, _i64, _i64, _u32p]
+    L.orc_select_codes.argtypes = [_u32p, _u32p, _i64, _i64, _u32p, _u32p]
     L.orc_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
     L.orc_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, _i64]
     L.orc_uniform.restype = _f32
@@ -349,6 +350,19 @@ def quantize_selected(g, ind, bucket=0, thr_coef=0.75):
     th = np.zeros(nb, np.float32)
     lib().orc_quantize_selected(g, ind, d, bucket, thr_coef, sel, cnt, sc, th)
     return sel, cnt, sc, th
+
+
+def select_codes(dense_words, ind, d, bucket=0):
+    """Codes of the marked components of one dense message -> (sel_codes u32[nb*area], counts)."""
+    dense_words = np.ascontiguousarray(dense_words, np.uint32)
+    ind = np.ascontiguousarray(ind, np.uint32)
+    nb = n_buckets(d, bucket)
+    b = bucket if bucket > 0 else d
+    area = (b + 15) // 16
+    sel = np.zeros(nb * area, np.uint32)
+    cnt = np.zeros(nb, np.uint32)
+    lib().orc_select_codes(dense_words, ind, d, bucket, sel, cnt)
+    return sel, cnt
 
 
 def decode_selected(ind, sel_codes, d, bucket=0):

@@ -445,6 +445,25 @@ void orc_quantize_selected(const float* g, const uint32_t* ind, int64_t d, int64
   }
 }
 
+// S applied to codes (Algorithm 1, server: "Push S(q_t, I^Syn) and I^Syn to every worker"): the
+// 2-bit codes of the marked components of one dense message, in index order, packed per bucket
+// exactly like the output of orc_quantize_selected; count[k] = marked components of bucket k.
+void orc_select_codes(const uint32_t* dense_words, const uint32_t* ind, int64_t d, int64_t bucket,
+                      uint32_t* sel_codes, uint32_t* count) {
+  const int64_t b = bucket_len(d, bucket), nb = n_buckets(d, bucket);
+  const int64_t area = (b + 15) / 16;
+  std::vector<int8_t> code;
+  for (int64_t k = 0; k < nb; ++k) {
+    const int64_t lo = k * b, hi = std::min(lo + b, d);
+    code.clear();
+    for (int64_t i = lo; i < hi; ++i)
+      if ((ind[i / 32] >> (i % 32)) & 1u)
+        code.push_back((int8_t)decode_field(dense_words[i / 16], (int)(i % 16)));
+    count[k] = (uint32_t)code.size();
+    if (!code.empty()) pack_codes(code.data(), (int64_t)code.size(), sel_codes + k * area);
+  }
+}
+
 // S^{-1}: put the codes of the marked components back at their coordinates (unmarked -> 0) in
 // the dense 2-bit layout of one worker.
 void orc_decode_selected(const uint32_t* ind, const uint32_t* sel_codes, int64_t d, int64_t bucket,

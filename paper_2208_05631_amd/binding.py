@@ -243,3 +243,9 @@ def qa_step_qrda_segments(layout, plan, codes, scales, x, G, z, t, eta, lam, del
     _check(_lib.qa_step_qrda_segments(C.byref(layout), C.byref(plan), _p(codes), _p(scales), _p(x),
                                       _p(G), _p(z), t, eta, lam, delta, requant, _p(ws), _nbytes(ws),
                                       _stream(stream)), "qa_step_qrda_segments")
+
+
+def qa_select_codes(layout, codes, ind, ind_stride, sel_codes, counts, stream=None):
+    _lib.qa_select_codes.argtypes = [C.POINTER(Layout), _vp, _vp, C.c_int64, _vp, _vp, _vp]
+    _check(_lib.qa_select_codes(C.byref(layout), _p(codes), _p(ind), ind_stride, _p(sel_codes),
+                                _p(counts), _stream(stream)), "qa_select_codes")

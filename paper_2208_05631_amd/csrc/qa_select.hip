@@ -408,6 +408,87 @@ __global__ __launch_bounds__(kThreads) void decode_selected_kernel(SelArgs a) {
     }
 }
 
+// Extract table, the inverse of the deposit table: entry [nib][s] packs the 2-bit fields of byte s
+// at the set bits of nib towards bit 0 (lowest set bit first).
+constexpr DepositLut make_extract_lut() {
+  DepositLut t{};
+  for (int nib = 0; nib < 16; ++nib)
+    for (int s = 0; s < 256; ++s) {
+      uint32_t out = 0;
+      int n = 0;
+      for (int b = 0; b < 4; ++b)
+        if ((nib >> b) & 1) { out |= (((uint32_t)s >> (2 * b)) & 3u) << (2 * n); ++n; }
+      t.v[nib * 256 + s] = (uint8_t)out;
+    }
+  return t;
+}
+__device__ const DepositLut kExtractLut = make_extract_lut();
+
+// S applied to a coded message: one wave per 4096-tile, lane l holds code words j*64 + l of the
+// tile (as in the decoder).  Each word's marked codes are packed through the extract table and
+// appended at their position in the tile's compact stream, which is assembled in LDS (one area
+// per wave) and written out in whole words.
+__global__ __launch_bounds__(kThreads) void select_codes_kernel(SelArgs a) {
+  __shared__ uint8_t lut[16 * 256];
+  __shared__ uint32_t stream_all[kWaves][kTileWords + 1];
+  reinterpret_cast<uint4*>(lut)[threadIdx.x] = reinterpret_cast<const uint4*>(kExtractLut.v)[threadIdx.x];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  uint32_t* stream = stream_all[wave];
+  const int64_t tile_raw = (int64_t)blockIdx.x * kWaves + wave;
+  const bool exists = tile_raw * kTile < a.d;
+  const int64_t tile = exists ? tile_raw : 0;            // clamped: every wave runs the same code
+  const int m = blockIdx.y;
+  const uint32_t* ind = a.ind_in + (int64_t)m * a.ind_stride;
+  const uint32_t* dense = a.sel_in + (int64_t)m * a.code_stride + tile * kTileWords;
+  uint32_t mask[4], word[4], incl[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int wl = j * 64 + lane;
+    const int64_t iw = tile * (kTile / 32) + wl / 2;
+    const uint32_t iv = iw < a.NW ? ind[iw] : 0u;
+    mask[j] = (iv >> (16 * (wl & 1))) & 0xFFFFu;
+    const int64_t left = a.d - (tile * kTile + (int64_t)wl * 16);
+    if (left < 16) mask[j] = left > 0 ? (mask[j] & ((1u << left) - 1u)) : 0u;
+    const int64_t w = tile * kTileWords + wl;
+    const uint32_t raw = w < a.W ? dense[wl] : 0u;
+    const uint32_t lo = raw & 0x55555555u;
+    word[j] = lo | (raw & (lo << 1));                    // reserved pattern 10 reads as 0
+    stream[wl] = 0u;
+  }
+  if (lane == 0) stream[kTileWords] = 0u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) incl[j] = wave_inclusive_scan_u32((uint32_t)__popc(mask[j]));
+  __syncthreads();                                       // table and zeroed streams are in LDS
+  uint32_t start = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t n = (uint32_t)__popc(mask[j]);
+    const uint32_t before = start + incl[j] - n;
+    start += (uint32_t)__builtin_amdgcn_readlane((int)incl[j], kWave - 1);
+    uint32_t bits = 0, filled = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t nib = (mask[j] >> (4 * q)) & 15u;
+      bits |= (uint32_t)lut[nib * 256 + ((word[j] >> (8 * q)) & 0xFFu)] << filled;
+      filled += 2 * __popc(nib);
+    }
+    if (n) {
+      const uint32_t w0 = before / 16, sh = 2 * (before % 16);
+      atomicOr(&stream[w0], bits << sh);
+      if (sh && 2 * n + sh > 32) atomicOr(&stream[w0 + 1], bits >> (32 - sh));
+    }
+  }
+  __syncthreads();
+  if (exists) {
+    const uint32_t K = start, nwords = (K + 15) / 16;
+    uint32_t* out = a.sel_codes + (int64_t)m * a.code_stride + tile * kTileWords;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if ((uint32_t)(j * 64 + lane) < nwords) out[j * 64 + lane] = stream[j * 64 + lane];
+    if (lane == 0) a.counts[(int64_t)m * a.scale_stride + tile] = K;
+  }
+}
+
 static int check_select_layout(const qa_layout* L) {
   int rc = check_layout(L);
   if (rc != QA_OK) return rc;
@@ -495,6 +576,25 @@ extern "C" int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, 
   hipLaunchKernelGGL(decode_selected_kernel,
                      dim3((unsigned)((tiles_of(layout->d) + kWaves * kDecodeTiles - 1) / (kWaves * kDecodeTiles)),
                           (unsigned)layout->M),
+                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  return launch_status();
+}
+
+extern "C" int qa_select_codes(const qa_layout* layout, const uint32_t* codes, const uint32_t* ind,
+                               int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts,
+                               void* stream) {
+  using namespace qa;
+  int rc = check_select_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!codes || !ind || !sel_codes || !counts) return QA_ERR_INVALID_ARG;
+  if (ind_stride != 0 && ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
+  if (!aligned(codes, 4) || !aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(counts, 4))
+    return QA_ERR_ALIGNMENT;
+  if (codes == sel_codes) return QA_ERR_INVALID_ARG;       // not in place
+  SelArgs a = base_args(layout);
+  a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = codes; a.sel_codes = sel_codes; a.counts = counts;
+  hipLaunchKernelGGL(select_codes_kernel,
+                     dim3((unsigned)((tiles_of(layout->d) + kWaves - 1) / kWaves), (unsigned)layout->M),
                      dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
   return launch_status();
 }

@@ -133,6 +133,103 @@ def test_quantize_selected_and_decode_match_oracle(d, M, bucket, p):
         assert np.array_equal(host(dense).view(np.uint32)[m, :W], oracle.decode_selected(ind[m], o_sel, d, bucket=bucket))
 
 
+@pytest.mark.parametrize("shared", [False, True])
+@pytest.mark.parametrize("d,M,bucket,p", [(1, 1, 0, 1.0), (1000, 2, 0, 0.3), (4096, 1, 4096, 0.5),
+                                          (4097, 2, 4096, 0.02), (70001, 3, 4096, 0.2),
+                                          (70001, 1, 4096, 1.0), (20000, 2, 4096, 0.0)])
+def test_select_codes_matches_oracle_and_decode_inverts_it(d, M, bucket, p, shared):
+    """S(q, I) on coded messages (the server's push): bit-exact with the checker, only the words
+    that hold codes are written, and the decoder restores the marked components."""
+    rng = np.random.default_rng(7 * d + M)
+    L = qa.Layout.make(d, M, bucket)
+    nb, W, NW = L.n_buckets, L.words, (d + 31) // 32
+    codes = rng.integers(0, 2 ** 32, (M, L.code_stride), dtype=np.uint64).astype(np.uint32)   # incl. pattern 10
+    ind = random_indicator(rng, 1 if shared else M, d, p)
+    sel = torch.full((M, L.code_stride), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+    cnt = torch.full((M, nb), -1, dtype=torch.int32, device=DEV)
+    back = torch.full((M, L.code_stride), -1, dtype=torch.int32, device=DEV)
+    codes_d, ind_d = dev(codes.view(np.int32)), dev(ind.view(np.int32))
+    qa.qa_select_codes(L, codes_d, ind_d, 0 if shared else NW, sel, cnt)
+    if not shared:
+        qa.qa_decode_selected(L, ind_d, NW, sel, back)
+    torch.cuda.synchronize()
+    sel_h, cnt_h = host(sel).view(np.uint32), host(cnt).view(np.uint32)
+    area = 256 if bucket else (d + 15) // 16
+    for m in range(M):
+        im = ind[0 if shared else m]
+        o_sel, o_cnt = oracle.select_codes(codes[m, :W], im, d, bucket=bucket)
+        assert np.array_equal(cnt_h[m], o_cnt)
+        for k in range(nb):
+            nwk = (int(o_cnt[k]) + 15) // 16
+            assert np.array_equal(sel_h[m, k * 256: k * 256 + nwk], o_sel[k * area: k * area + nwk]), (m, k)
+            assert np.all(sel_h[m, k * 256 + nwk: min((k + 1) * 256, L.code_stride)] == 0x5A5A5A5A)
+        if not shared:
+            want = oracle.decode_selected(im, o_sel, d, bucket=bucket)
+            assert np.array_equal(host(back).view(np.uint32)[m, :W], want)
+            bits = np.unpackbits(im.view(np.uint8), bitorder="little")[:d].astype(bool)
+            assert np.array_equal(oracle.unpack(want, d), np.where(bits, oracle.unpack(codes[m, :W], d), 0))
+
+
+@pytest.mark.parametrize("method", ["qcmd", "qrda"])
+def test_pull_direction_through_the_sparse_message_equals_the_fused_step(method):
+    """Algorithm 1 end to end on the server's side: decode the workers' sparse messages, average,
+    q_t = Q(SynQ_t) as a one-worker message, push S(q_t, I_syn) + I_syn, workers decode and
+    update.  Components outside I_syn have q_t = 0, so the result must equal the fused step with
+    the same second quantization, bit for bit."""
+    rng = np.random.default_rng(11)
+    d, M, b = 70001, 4, 4096
+    eta, lam, delta, t = 0.1, 1e-3, 1e-8, 3
+    L = qa.Layout.make(d, M, b)
+    L1 = qa.Layout.make(d, 1, b)
+    nb, NW, gs = L.n_buckets, (d + 31) // 32, ((d + 3) // 4) * 4
+    x0, G0, z0 = rand_state(rng, d, nz=0.05)
+    g = np.zeros((M, gs), np.float32)
+    g[:, :d] = rng.standard_normal((M, d)) * rng.choice([1e-4, 0.05], (M, d), p=[0.9, 0.1])
+    gd, xd, Gd, zd = dev(g), dev(x0), dev(G0), dev(z0)
+    ind = torch.zeros((M, NW), dtype=torch.int32, device=DEV)
+    syn = torch.zeros(NW, dtype=torch.int32, device=DEV)
+    sel = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((M, nb), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((M, nb), dtype=torch.float32, device=DEV)
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    mth = 0 if method == "qcmd" else 1
+    # workers -> server
+    qa.qa_indicator(L, mth, gd, gs, xd, Gd, zd, t, eta, lam, delta, ind, NW)
+    qa.qa_indicator_or(L, ind, NW, syn)
+    qa.qa_quantize_pack_selected(L, gd, gs, ind, NW, sel, cnt, sc, None)
+    qa.qa_decode_selected(L, ind, NW, sel, codes)
+
+    def step(LL, c, s, xx, GG, zz, requant):
+        if method == "qcmd":
+            qa.qa_step_qcmd(LL, c, s, xx, GG, zz, eta, lam, delta, requant, None)
+        else:
+            qa.qa_step_qrda(LL, c, s, xx, GG, zz, t, eta, lam, delta, requant, None)
+
+    # A: fused step with the per-bucket second quantization
+    xa, Ga, za = xd.clone(), Gd.clone(), zd.clone()
+    step(L, codes, sc, xa, Ga, za, qa.QA_REQUANT_BUCKET)
+    # B: q_t as a message, through the sparse encoding and back
+    gbar = torch.zeros(gs, dtype=torch.float32, device=DEV)
+    qc = torch.zeros((1, L1.code_stride), dtype=torch.int32, device=DEV)
+    qs = torch.zeros((1, nb), dtype=torch.float32, device=DEV)
+    qa.qa_aggregate_unpack(L, codes, sc, gbar)
+    qa.qa_quantize_pack(L1, gbar, gs, qc, qs, None, 0, None)
+    push = torch.zeros((1, L1.code_stride), dtype=torch.int32, device=DEV)
+    push_cnt = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
+    qa.qa_select_codes(L1, qc, syn, 0, push, push_cnt)
+    pulled = torch.full((1, L1.code_stride), -1, dtype=torch.int32, device=DEV)
+    qa.qa_decode_selected(L1, syn, NW, push, pulled)
+    xb, Gb, zb = xd.clone(), Gd.clone(), zd.clone()
+    step(L1, pulled, qs, xb, Gb, zb, qa.QA_REQUANT_NONE)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(pulled)[0, :L1.words], host(qc)[0, :L1.words])     # nothing lost
+    for u, v in ((xa, xb), (Ga, Gb), (za, zb)):
+        assert np.array_equal(host(u).view(np.uint32), host(v).view(np.uint32))
+    k_syn = int(host(push_cnt).sum())
+    assert 0 < k_syn < d                                                         # a sparse message
+    assert np.count_nonzero(host(xa)) > 0
+
+
 def test_unsupported_bucket_sizes_are_refused():
     L = qa.Layout.make(100000, 2, 1024)
     t = torch.zeros(8, dtype=torch.int32, device=DEV)

@@ -50,6 +50,8 @@ MUTATIONS = [
      "orc_step_qcmd(codes + b / 16, code_stride, scales,"),
     ("tensor_step_skips_second_quantization", "x + b, G + b, zs, t, eta, lambda, delta, requant ? 2 : 0);",
      "x + b, G + b, zs, t, eta, lambda, delta, 0);"),
+    ("select_codes_takes_unmarked_components", "if ((ind[i / 32] >> (i % 32)) & 1u)\n        code.push_back(",
+     "if (!((ind[i / 32] >> (i % 32)) & 1u))\n        code.push_back("),
     ("csr_gradient_uses_row_position", "acc[indices[k]] += (double)coef[b] * (double)vals[k];",
      "acc[indices[k]] += (double)coef[b] * (double)vals[indptr[r]];"),
     ("indicator_needs_both", "if (x[i] != 0.0f || xh != 0.0f) ind_out", "if (x[i] != 0.0f && xh != 0.0f) ind_out"),

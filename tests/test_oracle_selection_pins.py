@@ -98,3 +98,37 @@ def test_indicator_or():
     rng = np.random.default_rng(6)
     ind = rng.integers(0, 2 ** 32, (5, 10), dtype=np.uint64).astype(np.uint32)
     assert np.array_equal(oracle.indicator_or(ind, 320), np.bitwise_or.reduce(ind, axis=0))
+
+
+@pytest.mark.parametrize("d,bucket", [(37, 0), (1000, 256), (9000, 4096)])
+def test_select_codes_is_numpy_compaction_and_inverts_under_decode(d, bucket):
+    """S(q, I) on a coded message: the marked components' codes in index order (numpy boolean
+    indexing is the definition), per bucket; decode puts them back, zeros elsewhere."""
+    rng = np.random.default_rng(d)
+    code = rng.integers(-1, 2, d).astype(np.int8)
+    dense = oracle.pack(code)
+    mask = rng.random(d) < 0.3
+    if bucket:
+        mask[:bucket] = False                                      # an empty bucket
+    ind = np.zeros(oracle.n_ind_words(d), np.uint32)
+    for i in np.nonzero(mask)[0]:
+        ind[i // 32] |= np.uint32(1 << (i % 32))
+    sel, cnt = oracle.select_codes(dense, ind, d, bucket=bucket)
+    b = bucket or d
+    area = (b + 15) // 16
+    for k in range(oracle.n_buckets(d, bucket)):
+        lo, hi = k * b, min((k + 1) * b, d)
+        want = code[lo:hi][mask[lo:hi]]
+        assert cnt[k] == want.size
+        assert np.array_equal(oracle.unpack(sel[k * area:], want.size), want)
+        nw = (want.size + 15) // 16
+        assert np.array_equal(sel[k * area:k * area + nw], oracle.pack(want))   # unused bits zero
+    back = oracle.unpack(oracle.decode_selected(ind, sel, d, bucket=bucket), d)
+    assert np.array_equal(back, np.where(mask, code, 0))
+    # the reserved pattern 10 is read as 0
+    dense2 = dense.copy()
+    dense2[0] = (dense2[0] & ~np.uint32(3)) | np.uint32(2)
+    ind2 = ind.copy()
+    ind2[0] |= np.uint32(1)
+    sel2, _ = oracle.select_codes(dense2, ind2, d, bucket=bucket)
+    assert oracle.unpack(sel2, 1)[0] == 0
