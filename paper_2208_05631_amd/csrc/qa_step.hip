@@ -185,9 +185,9 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 // 256-entry binary64 table (built per tile in LDS) holding the exact partial sum of those four
 // workers.  Tiles that fail the span test (or hold Inf/NaN scales) take the ordered loop.
 //
-// All global loads of a tile (up to 64 code words per lane, then G, x, z in the coalesced
-// float4 mapping f = j*256 + t) are issued before any dependent work, so that the scale test,
-// the table build and the lookups run under the memory latency.
+// The code words of a chunk of workers are requested together, before the scale test and the
+// table build; G, x, z (coalesced float4 mapping f = j*256 + t) are requested after the last
+// look-up.  Four waves per SIMD cover each other's latencies.
 constexpr int kMaxGroups = 4;                           // 16 workers per table set: 8 KiB of LDS
 
 struct State4 { float4 v[4]; };
