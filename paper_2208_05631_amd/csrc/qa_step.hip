@@ -7,7 +7,6 @@
 // Per coordinate the kernel forms  acc = sum_m s_m * c_m  in binary64 (each product is exact),
 // gbar = (float)(acc / M), optionally re-quantizes gbar per bucket inside the tile, and applies
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
-#include <stdlib.h>
 #include "qa_segments.h"
 
 namespace qa {
@@ -37,34 +36,6 @@ __device__ __forceinline__ uint32_t sanitize(uint32_t w) {
   return lo | ((w & (lo << 1)));
 }
 
-__device__ __forceinline__ void load16(const float* __restrict__ p, int64_t i0, int64_t d,
-                                       float out[16]) {
-  if (i0 + 16 <= d) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 v = *reinterpret_cast<const float4*>(p + i0 + 4 * q);
-      out[4 * q] = v.x; out[4 * q + 1] = v.y; out[4 * q + 2] = v.z; out[4 * q + 3] = v.w;
-    }
-  } else {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) out[j] = (i0 + j < d) ? p[i0 + j] : 0.0f;
-  }
-}
-
-__device__ __forceinline__ void store16(float* __restrict__ p, int64_t i0, int64_t d,
-                                        const float v[16]) {
-  if (i0 + 16 <= d) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      *reinterpret_cast<float4*>(p + i0 + 4 * q) =
-          make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-  } else {
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if (i0 + j < d) p[i0 + j] = v[j];
-  }
-}
-
 // Accumulator and closed-form update of one coordinate (equations Hq, QCMD, QRDA): binary32,
 // one rounding per operation, in this order.
 template <int MODE, bool TRACK_Z>
@@ -88,102 +59,18 @@ __device__ __forceinline__ void update_coordinate(const StepArgs& a, float q, fl
   }
 }
 
-template <int MODE, bool TRACK_Z, bool REQUANT>
-__global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
-  __shared__ double lds_d[kWaves];
-  __shared__ uint32_t lds_u[kWaves];
-  const int t = threadIdx.x;
-  const int64_t wi = (int64_t)blockIdx.x * kTileWords + t;   // code word of this thread
-  const int64_t i0 = wi * 16;                                // its first coordinate
-  const bool live = wi < a.W;
-  const int64_t k = a.log2b >= 0 ? (i0 >> a.log2b) : 0;      // its bucket
-
-  // ---- unpack + sum over workers (binary64; every product s*c is exact) ----
-  double acc[16];
-#pragma unroll
-  for (int j = 0; j < 16; ++j) acc[j] = 0.0;
-  if (live) {
-    const uint32_t* cw = a.codes + wi;
-    const float* sc = a.scales + k;
-    for (int m = 0; m < a.M; ++m) {
-      const uint32_t w = sanitize(cw[(int64_t)m * a.code_stride]);
-      const double s = (double)sc[(int64_t)m * a.scale_stride];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int c = ((int)(w << (30 - 2 * j))) >> 30;      // sign-extended 2-bit field
-        acc[j] = fma((double)c, s, acc[j]);
-      }
-    }
-  }
-  float q[16];
-  if (a.M_pow2) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] * a.inv_M);
-  } else {
-    const double Md = (double)a.M;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] / Md);
-  }
-
-  if (i0 + 16 > a.d) {                                       // last word: ignore tail bits
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if (i0 + j >= a.d) q[j] = 0.0f;
-  }
-
-  // ---- second quantization inside the tile (bucket <= 4096) ----
-  if (REQUANT) {
-    const int b = 1 << a.log2b;
-    const int seg = b / 16;                                  // threads per bucket: 4..256
-    double s1 = 0.0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);  // dead lanes hold zeros
-    s1 = segment_sum(s1, seg, lds_d);
-    const int64_t lo = k << a.log2b;
-    const int64_t n = (a.d - lo) < (int64_t)b ? (a.d - lo) : (int64_t)b;
-    const float Delta = n > 0 ? threshold_from_sum(s1, a.thr_coef, n) : 0.0f;
-    double s2 = 0.0;
-    uint32_t cnt = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const float av = fabsf(q[j]);
-      if (av > Delta) { s2 += (double)av; ++cnt; }
-    }
-    s2 = segment_sum(s2, seg, lds_d);
-    cnt = segment_sum_u32(cnt, seg, lds_u);
-    const float s = scale_from_sum(s2, cnt);
-#pragma unroll
-    for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
-  }
-
-  if (!live) return;
-
-  if (MODE == kAggregate) {
-    store16(a.gbar, i0, a.d, q);
-    return;
-  }
-
-  // ---- accumulator and closed-form update ----
-  float G[16], x[16], z[16];
-  load16(a.G, i0, a.d, G);
-  if (MODE == kQcmd) load16(a.x, i0, a.d, x);
-  if (MODE == kQrda || TRACK_Z) load16(a.z, i0, a.d, z);
-#pragma unroll
-  for (int j = 0; j < 16; ++j) update_coordinate<MODE, TRACK_Z>(a, q[j], x[j], G[j], z[j]);
-  store16(a.G, i0, a.d, G);
-  store16(a.x, i0, a.d, x);
-  if (MODE == kQrda || TRACK_Z) store16(a.z, i0, a.d, z);
-}
-
-// ---- table-driven kernel for tile-uniform scales (bucket >= 4096 or one scale per vector) ----
+// ---- the step kernel ----------------------------------------------------------------------------
 //
+// Tile-uniform scales (bucket >= 4096 or one scale per vector): table-driven sum over the workers.
 // When the exponents of the non-zero scales of the tile's bucket span few enough binades, every
 // partial sum of  sum_m s_m*c_m  is exactly representable in binary64 (all are multiples of
 // 2^(e_min-23) and below M*2^(e_max+1)), so the order of the additions does not matter.  The
 // kernel then sums workers four at a time: the 2-bit codes of workers 4g..4g+3 for one
 // coordinate are gathered into one byte by word-wide bit operations and the byte indexes a
 // 256-entry binary64 table (built per tile in LDS) holding the exact partial sum of those four
-// workers.  Tiles that fail the span test (or hold Inf/NaN scales) take the ordered loop.
+// workers.  Tiles that fail the span test (or hold Inf/NaN scales) take the ordered loop, and so
+// do launches with buckets smaller than the tile (each thread's 16 coordinates share a bucket,
+// the tile does not: per-thread scales, second quantization by segmented sums).
 //
 // The code words of a chunk of workers are requested together, before the scale test and the
 // table build; G, x, z (coalesced float4 mapping f = j*256 + t) are requested after the last
@@ -297,10 +184,13 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   }
   const int64_t tile_base = tile * kTile;
   const bool full_tile = hi - lo == kTile;
-  const float* sc = a.scales + k;
   // words of this tile that exist; lanes beyond read the last one (in bounds) and are masked
   const int64_t words_here = a.W - tile * kTileWords;
   const int tw = words_here >= kTileWords ? t : (t < (int)words_here ? t : (int)words_here - 1);
+  // Buckets smaller than the tile: every thread's 16 coordinates still share one bucket, but the
+  // tile does not; such launches take the worker-ordered sum below with per-thread scales.
+  const bool own_scales = !a.tile_uniform;               // uniform over the launch
+  const float* sc = a.scales + (own_scales ? ((tile_base + 16 * (int64_t)tw) >> a.log2b) : k);
   const uint32_t tw4 = (uint32_t)tw * 4u;
   const uint32_t row_bytes = 4u * (uint32_t)(words_here >= kTileWords ? kTileWords : words_here);
   const uint32_t* ctile = a.codes + tile * kTileWords;                 // uniform base
@@ -308,15 +198,16 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   // ---- request the first chunk of code words ----
   uint32_t w[kChunk];
   {
-    const int left = a.M;
+    const int left = own_scales ? 0 : a.M;
 #pragma unroll
     for (int i = 0; i < kChunk; ++i)
-      w[i] = (FULL || i < left) ? stream_load(ctile + (int64_t)i * a.code_stride, tw4, row_bytes) : 0u;
+      w[i] = ((FULL && !own_scales) || i < left)
+                 ? stream_load(ctile + (int64_t)i * a.code_stride, tw4, row_bytes) : 0u;
   }
 
   // ---- can the sum over workers be reordered? (exponent span of the tile's scales) ----
-  int emax = 0, emin = 255, bad = 0;
-  for (int m = t; m < a.M; m += kThreads) {
+  int emax = 0, emin = 255, bad = own_scales ? 1 : 0;
+  for (int m = t; m < (own_scales ? 0 : a.M); m += kThreads) {
     const uint32_t u = __float_as_uint(sc[(int64_t)m * a.scale_stride]);
     if ((u << 1) == 0u) continue;
     int f = (int)((u >> 23) & 0xFFu);
@@ -385,15 +276,26 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       chunk(w, m0);
     }
   } else {
-    // ordered loop, as the sum is written: worker 0, 1, 2, ...
-    for (int m = 0; m < a.M; ++m) {
-      const uint32_t wv = sanitize((ctile + (int64_t)m * a.code_stride)[tw]);
-      const double s = (double)sc[(int64_t)m * a.scale_stride];
+    // ordered loop, as the sum is written: worker 0, 1, 2, ...; eight code words are requested
+    // at a time so that their latencies overlap
+    for (int m0 = 0; m0 < a.M; m0 += 8) {
+      uint32_t wv[8];
+      double sv[8];
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int c = ((int)(wv << (30 - 2 * j))) >> 30;
-        acc[j] = fma((double)c, s, acc[j]);
+      for (int u = 0; u < 8; ++u) {
+        const bool in = m0 + u < a.M;
+        const int m = in ? m0 + u : a.M - 1;
+        wv[u] = sanitize(stream_load(ctile + (int64_t)m * a.code_stride, tw4, row_bytes));
+        sv[u] = (double)sc[(int64_t)m * a.scale_stride];
+        if (!in) { wv[u] = 0u; sv[u] = 0.0; }             // adds +0
       }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int c = ((int)(wv[u] << (30 - 2 * j))) >> 30;
+          acc[j] = fma((double)c, sv[u], acc[j]);
+        }
     }
   }
 
@@ -430,13 +332,21 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     if (t == 0) a.abs_partials[tile] = s1;
   }
 
-  if (REQUANT) {                                          // bucket == 4096 == the tile
+  if (REQUANT) {
+    // second quantization of the average, per bucket: the whole tile, or (buckets smaller than
+    // the tile) a segment of bucket/16 consecutive threads
+    const int seg = own_scales ? (1 << a.log2b) / 16 : kThreads;
+    int64_t n = hi - lo;
+    if (own_scales) {
+      const int64_t b = (int64_t)1 << a.log2b;
+      const int64_t blo = ((tile_base + 16 * (int64_t)t) >> a.log2b) << a.log2b;
+      n = (a.d - blo) < b ? (a.d - blo) : b;              // true length of the thread's bucket
+    }
     double s1 = 0.0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);
-    s1 = segment_sum(s1, kThreads, lds_d);
-    const int64_t n = hi - lo;
-    const float Delta = threshold_from_sum(s1, a.thr_coef, n);
+    for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);   // dead lanes hold zeros
+    s1 = segment_sum(s1, seg, lds_d);
+    const float Delta = n > 0 ? threshold_from_sum(s1, a.thr_coef, n) : 0.0f;
     double s2 = 0.0;
     uint32_t cnt = 0;
 #pragma unroll
@@ -444,8 +354,8 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       const float av = fabsf(q[j]);
       if (av > Delta) { s2 += (double)av; ++cnt; }
     }
-    s2 = segment_sum(s2, kThreads, lds_d);
-    cnt = segment_sum_u32(cnt, kThreads, lds_u);
+    s2 = segment_sum(s2, seg, lds_d);
+    cnt = segment_sum_u32(cnt, seg, lds_u);
     const float s = scale_from_sum(s2, cnt);
 #pragma unroll
     for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
@@ -523,17 +433,12 @@ static qa_layout requant_layout(const qa_layout* L, int requant) {
   return R;
 }
 
-static bool forced_ordered() {
-  const char* e = getenv("QA_STEP_KERNEL");
-  return e && e[0] == 'o';
-}
-
 // Can Q(SynQ) be formed inside the step kernel?  Buckets that fit a tile; also one scale for a
 // vector that is a single tile (table-driven kernel only).
 static bool requant_in_tile(const qa_layout* L, int requant) {
   if (requant == QA_REQUANT_BUCKET) return L->bucket != 0 && L->bucket <= kTile;
   if (requant == QA_REQUANT_GLOBAL)
-    return tiles_of(L->d) == 1 && (L->bucket == 0 || L->bucket >= kTile) && !forced_ordered();
+    return tiles_of(L->d) == 1 && (L->bucket == 0 || L->bucket >= kTile);
   return false;
 }
 
@@ -570,37 +475,27 @@ static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float
   return a;
 }
 
-// QA_STEP_KERNEL=ordered forces the worker-ordered kernel (diagnostics); default: table-driven
-// kernel whenever a tile's coordinates share their scales.
-static bool use_lut(const StepArgs& a) {
-  if (a.seg.piece_tile) return true;                     // pieces exist only in that kernel
-  if (!a.tile_uniform) return false;
-  return !forced_ordered();
-}
-
-// which: -1 = worker-ordered kernel, otherwise the NGT of the table-driven kernel
 template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
 static void launch_lut(const StepArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
   hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, NGT>), grid, block, 0, stream, a);
 }
 
+// ngt: the NGT of the kernel variant
 template <int MODE, bool TRACK_Z, bool REQUANT>
-static void launch_one(const StepArgs& a, int which, hipStream_t stream) {
+static void launch_one(const StepArgs& a, int ngt, hipStream_t stream) {
   const dim3 grid((unsigned)(a.seg.piece_tile ? a.seg.n_pieces : tiles_of(a.d))), block(kThreads);
-  switch (which) {
+  switch (ngt) {
     case 4: launch_lut<MODE, TRACK_Z, REQUANT, 4>(a, grid, block, stream); break;
     case 2: launch_lut<MODE, TRACK_Z, REQUANT, 2>(a, grid, block, stream); break;
     case 1: launch_lut<MODE, TRACK_Z, REQUANT, 1>(a, grid, block, stream); break;
-    case 0: launch_lut<MODE, TRACK_Z, REQUANT, 0>(a, grid, block, stream); break;
-    default: hipLaunchKernelGGL((step_kernel<MODE, TRACK_Z, REQUANT>), grid, block, 0, stream, a); break;
+    default: launch_lut<MODE, TRACK_Z, REQUANT, 0>(a, grid, block, stream); break;
   }
 }
 
 template <int MODE>
 static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
-  int which = -1;
-  if (use_lut(a))
-    which = a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2 : a.M <= 4 ? 1 : 0;
+  // buckets smaller than the tile take the ordered sum: the variant with the fewest registers
+  const int which = !a.tile_uniform ? 1 : a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2 : a.M <= 4 ? 1 : 0;
   if (requant) {
     if (track_z) launch_one<MODE, true, true>(a, which, stream);
     else launch_one<MODE, false, true>(a, which, stream);
@@ -652,7 +547,7 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
       ag.gbar = gbar;
       // the table-driven kernel also leaves the quantizer's first pass (tile sums of |gbar|) in
       // the quantizer's workspace
-      const bool fuse_abs = qws != 0 && use_lut(ag);
+      const bool fuse_abs = qws != 0;
       if (fuse_abs) ag.abs_partials = reinterpret_cast<double*>(p);
       launch_mode<kAggregate>(ag, false, false, stream);
       const int64_t gs = (L->d + 3) & ~int64_t(3);
