@@ -446,7 +446,7 @@ def main():
                                f"{wl['gen']} gradients as packed 2-bit codes, schedule={wl['schedule']}, "
                                f"requant={wl.get('requant', 'none')}", "d": d, "M": M, "bucket": bucket,
                    "code_pad_words": args.code_pad_words},
-        "roofline": {"bound": "hbm", "kernel": f"step_kernel[{dominant}]",
+        "roofline": {"bound": "hbm", "kernel": f"step_lut_kernel[{dominant}]",
                      "achieved": dk["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dk["achieved_GBps"] / HBM_PEAK_GBPS,
                      "algorithmic_bytes": dk["bytes_per_coord"] * d,

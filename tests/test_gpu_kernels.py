@@ -159,7 +159,7 @@ def test_aggregate_reads_reserved_pattern_as_zero_and_ignores_tail_bits():
     rng = np.random.default_rng(3)
     words = rng.integers(0, 2 ** 32, (M, 3), dtype=np.uint64).astype(np.uint32)   # all 4 patterns
     scales = np.array([[0.5], [0.25]], np.float32)
-    for bucket in (0, 64):                 # table-driven kernel / worker-ordered kernel
+    for bucket in (0, 64):                 # table-driven sum / worker-ordered sum
         L = qa.Layout.make(d, M, bucket)
         out = torch.zeros(d, dtype=torch.float32, device=DEV)
         qa.qa_aggregate_unpack(L, dev(words.view(np.int32)), dev(scales), out)
