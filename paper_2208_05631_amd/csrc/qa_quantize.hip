@@ -393,12 +393,17 @@ template <int OWN> __device__ __forceinline__ int sort_position(int t, int r) {
 
 // The stages of phase P (blocks of 2^P positions, alternately descending and ascending) that
 // exchange across the lowest NST free bits of ownership OWN, highest first.  A block that must
-// come out ascending is sorted descending on complemented keys.
-template <int OWN, int P, int NST>
+// come out ascending is sorted descending on complemented keys.  FLIP: complement here, around
+// the stages (phases 1-4, where the block bit is a compile-time bit of r or t & 1); otherwise the
+// caller keeps the keys of ascending blocks complemented for the whole phase (an exchange never
+// leaves its block, so a key's state stays right for the position it moves to).
+template <int OWN, int P, int NST, bool FLIP>
 __device__ __forceinline__ void sort_stages(uint32_t (&e)[16], int t) {
+  if (FLIP) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r)
-    e[r] ^= (uint32_t)(-((sort_position<OWN>(t, r) >> P) & 1));
+    for (int r = 0; r < 16; ++r)
+      e[r] ^= (uint32_t)(-((sort_position<OWN>(t, r) >> P) & 1));
+  }
 #pragma unroll
   for (int lb = NST - 1; lb >= 0; --lb)
 #pragma unroll
@@ -408,9 +413,11 @@ __device__ __forceinline__ void sort_stages(uint32_t (&e)[16], int t) {
         e[r] = x > y ? x : y;
         e[r | (1 << lb)] = x > y ? y : x;
       }
+  if (FLIP) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r)
-    e[r] ^= (uint32_t)(-((sort_position<OWN>(t, r) >> P) & 1));
+    for (int r = 0; r < 16; ++r)
+      e[r] ^= (uint32_t)(-((sort_position<OWN>(t, r) >> P) & 1));
+  }
 }
 
 template <int FROM, int TO>
@@ -428,22 +435,31 @@ __device__ __forceinline__ void sort_move(uint32_t (&e)[16], int t, uint32_t* bu
   }
 }
 
-// Phase P of the network for P >= 5, entered and left in ownership 0.  n counts the moves made
-// so far and picks the buffer.
-template <int P>
+// Phase P of the network for P >= 5, entered and left in ownership 0 (positions 16t + r: the
+// block bit P is bit P-4 of t, the same for the thread's 16 keys).  On entry the keys carry the
+// complement state of phase P-1 (PREV_FLIPPED) or none; they leave in the state of phase P, which
+// for P = 12 is "none" (one block, descending).  n counts the moves made so far and picks the
+// buffer.
+template <int P, bool PREV_FLIPPED>
 __device__ __forceinline__ void sort_phase(uint32_t (&e)[16], int t, uint32_t (*buf)[kSortPitch],
                                            int& n) {
+  {
+    const uint32_t now = (t >> (P - 4)) & 1u, before = PREV_FLIPPED ? (t >> (P - 5)) & 1u : 0u;
+    const uint32_t m = (uint32_t)(-(int)(now ^ before));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) e[r] ^= m;
+  }
   if constexpr (P > 8) {
     sort_move<0, 2>(e, t, buf[n++ & 1]);
-    sort_stages<2, P, P - 8>(e, t);
+    sort_stages<2, P, P - 8, false>(e, t);
     sort_move<2, 1>(e, t, buf[n++ & 1]);
-    sort_stages<1, P, 4>(e, t);
+    sort_stages<1, P, 4, false>(e, t);
   } else {
     sort_move<0, 1>(e, t, buf[n++ & 1]);
-    sort_stages<1, P, P - 4>(e, t);
+    sort_stages<1, P, P - 4, false>(e, t);
   }
   sort_move<1, 0>(e, t, buf[n++ & 1]);
-  sort_stages<0, P, 4>(e, t);
+  sort_stages<0, P, 4, false>(e, t);
 }
 
 __global__ __launch_bounds__(kThreads) void exact_threshold_kernel(QuantArgs a) {
@@ -465,19 +481,19 @@ __global__ __launch_bounds__(kThreads) void exact_threshold_kernel(QuantArgs a) 
 #pragma unroll
       for (int c = 0; c < 4; ++c) e[j * 4 + c] = __float_as_uint(fabsf(v[j][c]));
   }
-  sort_stages<0, 1, 1>(e, t);
-  sort_stages<0, 2, 2>(e, t);
-  sort_stages<0, 3, 3>(e, t);
-  sort_stages<0, 4, 4>(e, t);
+  sort_stages<0, 1, 1, true>(e, t);
+  sort_stages<0, 2, 2, true>(e, t);
+  sort_stages<0, 3, 3, true>(e, t);
+  sort_stages<0, 4, 4, true>(e, t);
   int n = 0;
-  sort_phase<5>(e, t, buf, n);
-  sort_phase<6>(e, t, buf, n);
-  sort_phase<7>(e, t, buf, n);
-  sort_phase<8>(e, t, buf, n);
-  sort_phase<9>(e, t, buf, n);
-  sort_phase<10>(e, t, buf, n);
-  sort_phase<11>(e, t, buf, n);
-  sort_phase<12>(e, t, buf, n);
+  sort_phase<5, false>(e, t, buf, n);
+  sort_phase<6, true>(e, t, buf, n);
+  sort_phase<7, true>(e, t, buf, n);
+  sort_phase<8, true>(e, t, buf, n);
+  sort_phase<9, true>(e, t, buf, n);
+  sort_phase<10, true>(e, t, buf, n);
+  sort_phase<11, true>(e, t, buf, n);
+  sort_phase<12, true>(e, t, buf, n);
   // the thread now holds positions 16t .. 16t+15 of the descending order
   lds_first[t] = e[0];
   __syncthreads();
