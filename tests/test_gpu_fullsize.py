@@ -26,6 +26,8 @@ CASES = {
     "opt_qrda_2.5e8_M32": (250_000_000, 32, synth.grad_gaussian_biased, 1e-5, "qrda", 0),
     "opt_qrda_2.5e8_M32_requant": (250_000_000, 32, synth.grad_gaussian_biased, 1e-5, "qrda", 1),
     "largest_2^30_M64": (1 << 30, 64, synth.grad_laplace_sparse, 1e-6, "alternate", 0),
+    # more than 2^32 coordinates: every index and byte offset past 32 bits, ragged last bucket
+    "beyond_2^32_M2": ((1 << 32) + 3 * 4096 + 76, 2, synth.grad_laplace_sparse, 1e-6, "alternate", 1),
 }
 
 
