@@ -88,3 +88,56 @@ def test_sampled_buckets_at_full_size(name):
         assert nonzero_codes > 0
     # a property that holds at any size: coordinates never touched by any worker keep G == 0
     assert float(G.min().item()) >= 0.0
+
+
+def test_sparse_encoding_beyond_2_32_coordinates():
+    """Indicator, selected quantizer, code selection and decoder with every index past 32 bits:
+    all four are local to a 4096-bucket, so sampled buckets are checked against the oracle."""
+    d, M, b = (1 << 32) + 5 * 4096 + 40, 1, 4096
+    eta, lam, delta, t = 0.1, 1e-4, 1e-8, 7
+    nb, NW = (d + b - 1) // b, (d + 31) // 32
+    L = qa.Layout.make(d, M, b)
+    gen = torch.Generator(device=DEV); gen.manual_seed(3)
+    g = torch.empty(d, dtype=torch.float32, device=DEV)
+    synth.grad_laplace_sparse(d, 0, 1, device=DEV, out=g)
+    x = torch.zeros(d, dtype=torch.float32, device=DEV)
+    G = torch.zeros(d, dtype=torch.float32, device=DEV)
+    z = torch.zeros(d, dtype=torch.float32, device=DEV)
+    rng = np.random.default_rng(23)
+    sample = np.unique(np.concatenate([[0, 1], np.arange(nb - 6, nb), rng.integers(0, nb, 20)]))   # the last six lie past 2^32
+    for k in sample:                                       # a state worth marking, in the samples
+        n = min(b, d - k * b)
+        x[k * b:k * b + n] = torch.from_numpy((rng.standard_normal(n) * 0.1 * (rng.random(n) < 0.1)).astype(np.float32)).to(DEV)
+        G[k * b:k * b + n] = torch.from_numpy((rng.random(n) * 1e-6).astype(np.float32)).to(DEV)
+        z[k * b:k * b + n] = torch.from_numpy((rng.standard_normal(n) * 7e-4).astype(np.float32)).to(DEV)
+    ind = torch.zeros((1, NW), dtype=torch.int32, device=DEV)
+    sel = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((1, nb), dtype=torch.float32, device=DEV)
+    dense = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
+    again = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
+    cnt2 = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
+    for method in (0, 1):
+        qa.qa_indicator(L, method, g, d, x, G, z, t, eta, lam, delta, ind, NW)
+        qa.qa_quantize_pack_selected(L, g, d, ind, NW, sel, cnt, sc, None)
+        qa.qa_decode_selected(L, ind, NW, sel, dense)
+        qa.qa_select_codes(L, dense, ind, NW, again, cnt2)
+        torch.cuda.synchronize()
+        marked = 0
+        for k in sample:
+            n = min(b, d - k * b)
+            lo = int(k) * b
+            gs, xs, Gs, zs = (host(v[lo:lo + n]) for v in (g, x, G, z))
+            o_ind = oracle.indicator(method, gs, xs, Gs, zs, t, eta, lam, delta)
+            nw = (n + 31) // 32
+            assert np.array_equal(host(ind[0, k * 128:k * 128 + nw]).view(np.uint32), o_ind), (method, k)
+            o_sel, o_cnt, o_sc, _ = oracle.quantize_selected(gs, o_ind, bucket=0)
+            assert int(host(cnt[0, k])) == int(o_cnt[0]) and host(sc[0, k]) == o_sc[0]
+            nwk = (int(o_cnt[0]) + 15) // 16
+            assert np.array_equal(host(sel[0, k * 256:k * 256 + nwk]).view(np.uint32), o_sel[:nwk])
+            o_dense = oracle.decode_selected(o_ind, o_sel, n, bucket=0)
+            assert np.array_equal(host(dense[0, k * 256:k * 256 + (n + 15) // 16]).view(np.uint32), o_dense)
+            assert np.array_equal(host(again[0, k * 256:k * 256 + nwk]), host(sel[0, k * 256:k * 256 + nwk]))
+            assert int(host(cnt2[0, k])) == int(o_cnt[0])
+            marked += int(o_cnt[0])
+        assert marked > 0
