@@ -141,3 +141,65 @@ def test_sparse_encoding_beyond_2_32_coordinates():
             assert int(host(cnt2[0, k])) == int(o_cnt[0])
             marked += int(o_cnt[0])
         assert marked > 0
+
+
+def test_tensor_list_beyond_2_32_coordinates():
+    """Tensor-list quantizer and step on a flat vector longer than 2^32: one tensor of almost 2^32
+    elements (over a million pieces) and two small ones that start past 2^32.  The small tensors
+    are compared with the oracle exactly; the large one by its definition on the device in
+    binary64 (library reductions) and, given its threshold and scale, exactly on sampled elements."""
+    big = (1 << 32) - 1000
+    begin = np.array([0, 1 << 32, (1 << 32) + 8192], np.int64)
+    length = np.array([big, 5000, 77], np.int64)
+    d = int(begin[-1] + length[-1]) + 3
+    d += (-d) % 4
+    eta, lam, delta = 0.1, 1e-6, 1e-8
+    L = qa.Layout.make(d, 1, 0, 0.75, None, 3)
+    table = torch.zeros(qa.qa_segment_plan_bytes(d, 3), dtype=torch.uint8, device=DEV)
+    plan = qa.qa_segment_plan_init(d, begin, length, table)
+    assert plan.n_pieces == (big + 4095) // 4096 + 2 + 1
+    g = torch.empty(d, dtype=torch.float32, device=DEV)
+    synth.grad_laplace_sparse(d, 0, 1, device=DEV, out=g)
+    codes = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
+    scales = torch.zeros((1, 3), dtype=torch.float32, device=DEV)
+    th = torch.zeros((1, 3), dtype=torch.float32, device=DEV)
+    wq = torch.empty(qa.qa_segment_workspace_bytes(plan, 1, qa.QA_OP_QUANTIZE), dtype=torch.uint8, device=DEV)
+    x = torch.zeros(d, dtype=torch.float32, device=DEV)
+    G = torch.zeros(d, dtype=torch.float32, device=DEV)
+    qa.qa_quantize_pack_segments(L, plan, g, d, codes, scales, th, wq)
+    qa.qa_step_qcmd_segments(L, plan, codes, scales, x, G, None, eta, lam, delta, 0, None)
+    torch.cuda.synchronize()
+    s_h, th_h = host(scales)[0], host(th)[0]
+    # small tensors, past 2^32: exact
+    for k in (1, 2):
+        b0, n = int(begin[k]), int(length[k])
+        gs = host(g[b0:b0 + n])[None, :]
+        oc, osc, oth = oracle.quantize_pack(gs, bucket=0)
+        assert np.array_equal(host(codes[0, b0 // 16:b0 // 16 + (n + 15) // 16]).view(np.uint32), oc[0])
+        assert s_h[k] == osc[0, 0] and th_h[k] == oth[0, 0]
+        ox, oG = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        oracle.step_qcmd(oc, osc, n, 0, ox, oG, None, eta, lam, delta)
+        assert np.array_equal(host(x[b0:b0 + n]), ox) and np.array_equal(host(G[b0:b0 + n]), oG)
+    # the large tensor: threshold and scale from their definitions, in binary64 on the device
+    a = g[:big].abs()
+    D = 0.75 * float(a.sum(dtype=torch.float64).item()) / big
+    assert abs(th_h[0] - D) <= 1e-6 * D
+    kept = a > float(th_h[0])
+    s_def = float(torch.where(kept, a, torch.zeros((), device=DEV)).sum(dtype=torch.float64).item()) / \
+        int(kept.sum(dtype=torch.int64).item())
+    assert abs(s_h[0] - s_def) <= 1e-6 * s_def
+    del a, kept
+    rng = np.random.default_rng(5)
+    idx = np.unique(np.concatenate([[0, 1, big - 2, big - 1], rng.integers(0, big, 4000)]))
+    it = torch.from_numpy(idx).to(DEV)
+    gv = host(g[it])
+    words = host(codes[0][it // 16]).view(np.uint32)
+    field = (words >> (2 * (idx % 16)).astype(np.uint32)) & 3
+    want = np.where(gv > th_h[0], 1, np.where(gv < -th_h[0], 3, 0))
+    assert np.array_equal(field, want)
+    q = (np.where(field == 1, 1.0, np.where(field == 3, -1.0, 0.0)) * s_h[0]).astype(np.float32)
+    ox, oG = np.zeros(idx.size, np.float32), np.zeros(idx.size, np.float32)
+    oracle.update_qcmd(q, ox, oG, None, eta, lam, delta)
+    assert np.array_equal(host(x[it]), ox) and np.array_equal(host(G[it]), oG)
+    # between and after the tensors nothing is touched
+    assert not bool(x[big:1 << 32].any()) and not bool(x[int(begin[2]) + 77:].any())
