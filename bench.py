@@ -400,7 +400,8 @@ def main():
         if requant:      # separate passes: average out (M/4 + 4; also leaves the quantizer's tile
             # sums), quantize it (4.25: one pass over it), update from its codes (0.25 + state)
             bpc = (M / 4 + 4) + 4.25 + (bpc - M / 4 + 0.25)
-        kernels[k] = {"avg_ms": avg, "launches": len(ms), "bytes_per_coord": bpc,
+        kernels[k] = {"avg_ms": avg, "median_ms": float(np.median(ms)), "min_ms": float(np.min(ms)),
+                      "max_ms": float(np.max(ms)), "launches": len(ms), "bytes_per_coord": bpc,
                       "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
     dk = kernels[dominant]
@@ -457,6 +458,7 @@ def main():
                           "achieved_GBps": qbytes * d / (quant_ms * 1e-3) / 1e9,
                           "frac": qbytes * d / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "nnz_x_after": nnz_x,
+        "device": torch.cuda.get_device_name(0),
     }
 
     # ---- CPU baseline: the oracle as it stands, one host thread, on a bounded sample ----
