@@ -157,11 +157,14 @@ def select_bench(args, wl, qa, synth, torch, np, dev):
     t_ind = timed(lambda: qa.qa_indicator(L, qa.QA_METHOD_QCMD, g, d, x, G, z, 1, eta, lam, delta, ind, NW))
     t_q = timed(lambda: qa.qa_quantize_pack_selected(L, g, d, ind, NW, sel, cnt, sc, None))
     t_dec = timed(lambda: qa.qa_decode_selected(L, ind, NW, sel, dense))
+    again = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
+    cnt2 = torch.zeros((M, nb), dtype=torch.int32, device=dev)
+    t_selc = timed(lambda: qa.qa_select_codes(L, dense, ind, NW, again, cnt2))   # the pull direction's S
     k = int(cnt.sum().item())
     frac = k / (M * d)
     by = {"indicator": (4 * M + 8 + M / 8) * d, "quantize_selected": M * d * (4 + 1 / 8) + k / 4,
-          "decode": M * d * (1 / 8 + 1 / 4) + k / 4}
-    ms = {"indicator": t_ind, "quantize_selected": t_q, "decode": t_dec}
+          "decode": M * d * (1 / 8 + 1 / 4) + k / 4, "select_codes": M * d * (1 / 8 + 1 / 4) + k / 4}
+    ms = {"indicator": t_ind, "quantize_selected": t_q, "decode": t_dec, "select_codes": t_selc}
     out = {"metric": "sparse encoding kernels: worker-coordinates/s (indicator + Q(S(g,I)) + decode)",
            "value": M * d / ((t_ind + t_q + t_dec) * 1e-3), "unit": "worker-coordinates/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_ind + t_q + t_dec,
