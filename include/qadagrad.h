@@ -281,6 +281,15 @@ size_t qa_segment_plan_bytes(int64_t d, int64_t n_seg);
 int qa_segment_plan_init(int64_t d, int64_t n_seg, const int64_t* begin, const int64_t* length,
                          void* table, size_t table_bytes, qa_segment_plan* plan_out, void* stream);
 
+/* The same validation and table, on the HOST only (no device access): *n_pieces_out receives the
+ * number of pieces; if table_host is non-NULL (at least qa_segment_plan_bytes) it receives the
+ * table as int64 words: [0] tag, [1] d, [2] n_seg, [3] n_pieces, then begin[n_seg],
+ * length[n_seg], first_piece[n_seg + 1], piece_tile[n_pieces], piece_tensor[n_pieces]
+ * (piece p is the intersection of 4096-tile piece_tile[p] with tensor piece_tensor[p]; the pieces
+ * of tensor s are first_piece[s] .. first_piece[s+1]-1).  For sizing and for inspection. */
+int qa_segment_plan_host(int64_t d, int64_t n_seg, const int64_t* begin, const int64_t* length,
+                         int64_t* table_host, size_t table_bytes, int64_t* n_pieces_out);
+
 /* Workspace of the tensor-list calls below: op = QA_OP_QUANTIZE or QA_OP_STEP (the latter only
  * needed with requant != QA_REQUANT_NONE). */
 size_t qa_segment_workspace_bytes(const qa_segment_plan* plan, int32_t M, int op);

@@ -249,3 +249,17 @@ def qa_select_codes(layout, codes, ind, ind_stride, sel_codes, counts, stream=No
     _lib.qa_select_codes.argtypes = [C.POINTER(Layout), _vp, _vp, C.c_int64, _vp, _vp, _vp]
     _check(_lib.qa_select_codes(C.byref(layout), _p(codes), _p(ind), ind_stride, _p(sel_codes),
                                 _p(counts), _stream(stream)), "qa_select_codes")
+
+
+def qa_segment_plan_host(d, begin, length):
+    """Host-only validation and table of a tensor list -> (n_pieces, table as a list of int64)."""
+    n = len(begin)
+    nwords = qa_segment_plan_bytes(d, n) // 8
+    table = (C.c_int64 * max(nwords, 1))()
+    npieces = C.c_int64(0)
+    _lib.qa_segment_plan_host.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                          C.POINTER(C.c_int64), _sz, C.POINTER(C.c_int64)]
+    _check(_lib.qa_segment_plan_host(d, n, (C.c_int64 * max(n, 1))(*[int(v) for v in begin]),
+                                     (C.c_int64 * max(n, 1))(*[int(v) for v in length]), table,
+                                     nwords * 8, C.byref(npieces)), "qa_segment_plan_host")
+    return npieces.value, list(table)

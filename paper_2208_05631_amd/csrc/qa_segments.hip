@@ -187,14 +187,12 @@ extern "C" size_t qa_segment_plan_bytes(int64_t d, int64_t n_seg) {
   return (size_t)(kSegHeader + 2 * n_seg + (n_seg + 1) + 2 * np_max) * sizeof(int64_t);
 }
 
-extern "C" int qa_segment_plan_init(int64_t d, int64_t n_seg, const int64_t* begin,
-                                    const int64_t* length, void* table, size_t table_bytes,
-                                    qa_segment_plan* plan_out, void* stream) {
+// Validates the tensor list and writes the table (layout in qa_segments.h) into host memory.
+static int build_table(int64_t d, int64_t n_seg, const int64_t* begin, const int64_t* length,
+                       std::vector<int64_t>& h, int64_t* n_pieces_out) {
   using namespace qa;
-  if (!begin || !length || !table || !plan_out) return QA_ERR_INVALID_ARG;
-  const size_t need_max = qa_segment_plan_bytes(d, n_seg);
-  if (need_max == 0) return QA_ERR_INVALID_ARG;
-  if (!aligned(table, 8)) return QA_ERR_ALIGNMENT;
+  if (!begin || !length) return QA_ERR_INVALID_ARG;
+  if (qa_segment_plan_bytes(d, n_seg) == 0) return QA_ERR_INVALID_ARG;
   int64_t end_prev = 0, n_pieces = 0;
   for (int64_t s = 0; s < n_seg; ++s) {
     if (begin[s] < end_prev || (begin[s] & 15) != 0 || length[s] < 0) return QA_ERR_INVALID_ARG;
@@ -203,9 +201,7 @@ extern "C" int qa_segment_plan_init(int64_t d, int64_t n_seg, const int64_t* beg
     if (length[s] > 0) n_pieces += (end_prev - 1) / kTile - begin[s] / kTile + 1;
   }
   if (n_pieces > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
-  const size_t words = (size_t)(kSegHeader + 2 * n_seg + (n_seg + 1) + 2 * n_pieces);
-  if (table_bytes < words * sizeof(int64_t)) return QA_ERR_WORKSPACE;
-  std::vector<int64_t> h(words);
+  h.assign((size_t)(kSegHeader + 2 * n_seg + (n_seg + 1) + 2 * n_pieces), 0);
   h[0] = kSegMagic; h[1] = d; h[2] = n_seg; h[3] = n_pieces;
   int64_t* hb = h.data() + kSegHeader;
   int64_t* hl = hb + n_seg;
@@ -219,8 +215,38 @@ extern "C" int qa_segment_plan_init(int64_t d, int64_t n_seg, const int64_t* beg
       for (int64_t T = begin[s] / kTile; T <= (begin[s] + length[s] - 1) / kTile; ++T) { ht[p] = T; hs[p] = s; ++p; }
   }
   hf[n_seg] = p;
+  *n_pieces_out = n_pieces;
+  return QA_OK;
+}
+
+extern "C" int qa_segment_plan_host(int64_t d, int64_t n_seg, const int64_t* begin,
+                                    const int64_t* length, int64_t* table_host, size_t table_bytes,
+                                    int64_t* n_pieces_out) {
+  if (!n_pieces_out) return QA_ERR_INVALID_ARG;
+  std::vector<int64_t> h;
+  int rc = build_table(d, n_seg, begin, length, h, n_pieces_out);
+  if (rc != QA_OK) return rc;
+  if (table_host) {
+    if (table_bytes < h.size() * sizeof(int64_t)) return QA_ERR_WORKSPACE;
+    for (size_t i = 0; i < h.size(); ++i) table_host[i] = h[i];
+  }
+  return QA_OK;
+}
+
+extern "C" int qa_segment_plan_init(int64_t d, int64_t n_seg, const int64_t* begin,
+                                    const int64_t* length, void* table, size_t table_bytes,
+                                    qa_segment_plan* plan_out, void* stream) {
+  using namespace qa;
+  if (!begin || !length || !table || !plan_out) return QA_ERR_INVALID_ARG;
+  if (qa_segment_plan_bytes(d, n_seg) == 0) return QA_ERR_INVALID_ARG;
+  if (!aligned(table, 8)) return QA_ERR_ALIGNMENT;
+  std::vector<int64_t> h;
+  int64_t n_pieces = 0;
+  int rc = build_table(d, n_seg, begin, length, h, &n_pieces);
+  if (rc != QA_OK) return rc;
+  if (table_bytes < h.size() * sizeof(int64_t)) return QA_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (hipMemcpyAsync(table, h.data(), words * sizeof(int64_t), hipMemcpyHostToDevice, st) != hipSuccess)
+  if (hipMemcpyAsync(table, h.data(), h.size() * sizeof(int64_t), hipMemcpyHostToDevice, st) != hipSuccess)
     return QA_ERR_LAUNCH;
   if (hipStreamSynchronize(st) != hipSuccess) return QA_ERR_LAUNCH;
   plan_out->d = d; plan_out->n_seg = n_seg; plan_out->n_pieces = n_pieces; plan_out->table = table;

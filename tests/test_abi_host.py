@@ -138,3 +138,48 @@ def test_segment_plan_argument_checks():
                                                  C.c_size_t, C.c_void_p]
     assert B._lib.qa_quantize_pack_segments(C.byref(ok), C.byref(bad), FAKE, 1000, FAKE, FAKE, None, FAKE,
                                             1 << 20, None) == -1            # plan without table
+
+
+def _plan_host(d, begin, length):
+    f = B._lib.qa_segment_plan_host
+    f.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                  C.c_size_t, C.POINTER(C.c_int64)]
+    n = len(begin)
+    nbytes = qa.qa_segment_plan_bytes(d, n)
+    table = (C.c_int64 * (nbytes // 8))()
+    npieces = C.c_int64(-1)
+    rc = f(d, n, (C.c_int64 * max(n, 1))(*begin), (C.c_int64 * max(n, 1))(*length), table, nbytes,
+           C.byref(npieces))
+    return rc, npieces.value, list(table)
+
+
+def test_segment_table_against_a_python_reference():
+    """The piece table (built on the host, the same words that are copied to the device): every
+    (4096-tile, tensor) intersection exactly once, in order, for seeded random tensor lists."""
+    import random
+    rnd = random.Random(12)
+    for _ in range(200):
+        n = rnd.randint(1, 12)
+        begin, length, pos = [], [], rnd.choice([0, 16, 4096, 4080])
+        for _ in range(n):
+            begin.append(pos)
+            ln = rnd.choice([0, 1, 15, 16, 17, 4095, 4096, 4097, rnd.randint(0, 30000)])
+            length.append(ln)
+            pos = (pos + ln + 15) // 16 * 16 + 16 * rnd.choice([0, 0, 1, 300])
+        d = pos + rnd.randint(0, 5) if pos > 0 else 1
+        rc, npieces, t = _plan_host(d, begin, length)
+        assert rc == 0
+        want = [(T, s) for s in range(n) if length[s] > 0
+                for T in range(begin[s] // 4096, (begin[s] + length[s] - 1) // 4096 + 1)]
+        assert npieces == len(want) and npieces <= (d + 4095) // 4096 + n
+        assert t[1:4] == [d, n, npieces]
+        o = 4
+        assert t[o:o + n] == begin and t[o + n:o + 2 * n] == length
+        first = t[o + 2 * n:o + 3 * n + 1]
+        tiles = t[o + 3 * n + 1:o + 3 * n + 1 + npieces]
+        segs = t[o + 3 * n + 1 + npieces:o + 3 * n + 1 + 2 * npieces]
+        assert list(zip(tiles, segs)) == want
+        for s in range(n):
+            assert segs[first[s]:first[s + 1]] == [s] * (first[s + 1] - first[s])
+        assert first[0] == 0 and first[n] == npieces
+    assert _plan_host(1000, [0, 8], [4, 4])[0] == -1
