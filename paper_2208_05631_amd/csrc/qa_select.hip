@@ -98,44 +98,6 @@ __device__ __forceinline__ void indicator_slab_exact(const SelArgs& a, int m, in
 
 // wave w of the work-group owns coordinates [w*1024, (w+1)*1024) of the tile, lane l the
 // coordinates j*64 + l (j = 0..15): each ballot is 64 consecutive indicator bits.
-//
-// Slab that ends at or beyond d (last tile only): every access clamped or masked.
-__device__ __forceinline__ void indicator_wave_tail(const SelArgs& a, int64_t base, int lane) {
-  float x[16], G[16], z[16];
-#pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    const int64_t c = base + j * 64 + lane;
-    const int64_t cc = c < a.d ? c : a.d - 1;    // clamped: loads stay unconditional
-    x[j] = a.x[cc];
-    G[j] = a.G[cc];
-    z[j] = a.method == 1 ? a.z[cc] : 0.0f;
-  }
-  for (int m = 0; m < a.M; ++m) {
-    const float* g = a.g + (int64_t)m * a.g_stride;
-    uint32_t* out = a.ind + (int64_t)m * a.ind_stride;
-    bool undecided = false;
-    float gv[16];                                // all 16 loads in flight before any use
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int64_t c = base + j * 64 + lane;
-      gv[j] = g[c < a.d ? c : a.d - 1];
-    }
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int64_t c = base + j * 64 + lane;
-      bool mark = false;
-      const bool ok = a.method == 0 ? quick_indicator<0>(a, gv[j], x[j], G[j], z[j], &mark)
-                                    : quick_indicator<1>(a, gv[j], x[j], G[j], z[j], &mark);
-      undecided |= (c < a.d) && !ok;
-      mark = mark && (c < a.d);
-      const uint64_t bits = __ballot(mark);
-      const int64_t w0 = (base + j * 64) / 32;
-      if (lane < 2 && w0 + lane < a.NW) out[w0 + lane] = (uint32_t)(bits >> (32 * lane));
-    }
-    if (__any(undecided)) indicator_slab_exact(a, m, base, lane);   // overwrites the slab's words
-  }
-}
-
 // Slab that lies wholly below d: no clamps or masks; the next worker's gradient is requested
 // before the current one is examined; ballot j (64 indicator bits) is kept by lane j, and lanes
 // 0..15 store the slab's 128 bytes.
@@ -160,7 +122,7 @@ __device__ __forceinline__ void indicator_wave_full(const SelArgs& a, int64_t ba
     float gv[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) gv[j] = gn[j];
-    if (m + 1 < a.M) {
+    if (m + 1 < a.M) {                                   // the next worker's gradient, ahead of use
       const float* pn = pg + (int64_t)(m + 1) * a.g_stride;
 #pragma unroll
       for (int j = 0; j < 16; ++j) gn[j] = pn[j * 64];
@@ -184,15 +146,16 @@ __device__ __forceinline__ void indicator_wave_full(const SelArgs& a, int64_t ba
   }
 }
 
-__global__ __launch_bounds__(kThreads) void indicator_kernel(SelArgs a) {
+// Three waves per SIMD: measured best for this access pattern (2: 2.15 ms, 3: 1.91, 4: 1.98,
+// 6-8: 2.00 at d = 2^28, M = 8); the kernel needs only 58-77 registers and would otherwise run 6-8.
+template <int METHOD>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void indicator_kernel(SelArgs a) {
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int64_t base = (int64_t)blockIdx.x * kTile + wave * 1024;
-  if (base + 1024 <= a.d) {
-    if (a.method == 0) indicator_wave_full<0>(a, base, lane);
-    else indicator_wave_full<1>(a, base, lane);
-  } else if (base < a.d) {
-    indicator_wave_tail(a, base, lane);
-  }
+  if (base + 1024 <= a.d) indicator_wave_full<METHOD>(a, base, lane);
+  else if (base < a.d)                                   // the vector ends inside this slab: closed form
+    for (int m = 0; m < a.M; ++m) indicator_slab_exact(a, m, base, lane);
 }
 
 __global__ __launch_bounds__(kThreads) void indicator_or_kernel(SelArgs a) {
@@ -524,8 +487,9 @@ extern "C" int qa_indicator(const qa_layout* layout, int method, const float* g,
   a.method = method; a.g = g; a.g_stride = g_stride; a.x = x; a.G = G; a.z = z;
   a.ind = ind_out; a.ind_stride = ind_stride;
   a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta; a.t_lam = (float)t * lambda;
-  hipLaunchKernelGGL(indicator_kernel, dim3((unsigned)tiles_of(layout->d)), dim3(kThreads), 0,
-                     static_cast<hipStream_t>(stream), a);
+  const dim3 grid((unsigned)tiles_of(layout->d)), block(kThreads);
+  if (method == 0) hipLaunchKernelGGL(indicator_kernel<0>, grid, block, 0, static_cast<hipStream_t>(stream), a);
+  else hipLaunchKernelGGL(indicator_kernel<1>, grid, block, 0, static_cast<hipStream_t>(stream), a);
   return launch_status();
 }
 
