@@ -4,7 +4,9 @@
 //
 //   margins  : p_b = a_{r_b}.x in binary64 (work-group per row for dense, wave per row for CSR),
 //              then coef_b = -y/(1+exp(y p_b))/B and the row's loss, in binary64.
-//   gradient : dense -- one thread per 4 columns walks the batch in order, binary64 accumulator;
+//   gradient : dense -- one thread per 4 columns (one column when d is not a multiple of 4 or the
+//                       operands are not 16-byte aligned) walks the batch in order, binary64
+//                       accumulator;
 //              CSR   -- hardware binary64 atomic adds into a d-long accumulator that is cleared
 //                       only at the batch's columns, then rounded into the zero-filled g.
 //   Every product coef*a is exact in binary64, so only the order of the binary64 additions can
@@ -47,6 +49,13 @@ __device__ __forceinline__ GradArgs for_worker(GradArgs a) {
   return a;
 }
 
+// The matrix rows of a batch are read once per pass: streaming (non-temporal) 16-byte load.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float4* p) {
+  const floatx4 t = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+}
+
 // coef and loss of one sample from its binary32 margin term p = a.x
 __device__ __forceinline__ void logistic_terms(float p, float y, int B, float* coef, double* loss) {
   const double m = (double)y * (double)p;
@@ -56,6 +65,9 @@ __device__ __forceinline__ void logistic_terms(float p, float y, int B, float* c
   *coef = (float)((-(double)y * sig) / (double)B);
 }
 
+// Work-group per batch row.  VEC: d is a multiple of 4 and A, x are 16-byte aligned, so a row is
+// read as float4 with four loads in flight per thread.
+template <bool VEC>
 __global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a_all) {
   const GradArgs a = for_worker(a_all);
   __shared__ double lds_d[kWaves];
@@ -65,7 +77,38 @@ __global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a_all) 
   double s = 0.0;
   if (ok) {
     const float* row = a.A + r * a.d;
-    for (int64_t j = threadIdx.x; j < a.d; j += kThreads) s = fma((double)row[j], (double)a.x[j], s);
+    if (VEC) {
+      const float4* row4 = reinterpret_cast<const float4*>(row);
+      const float4* x4 = reinterpret_cast<const float4*>(a.x);
+      const int64_t n4 = a.d / 4;
+      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+      int64_t j = threadIdx.x;
+      for (; j + 3 * kThreads < n4; j += 4 * kThreads) {
+        float4 v[4], w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = stream_load4(row4 + j + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = x4[j + u * kThreads];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          s0 = fma((double)v[u].x, (double)w[u].x, s0);
+          s1 = fma((double)v[u].y, (double)w[u].y, s1);
+          s2 = fma((double)v[u].z, (double)w[u].z, s2);
+          s3 = fma((double)v[u].w, (double)w[u].w, s3);
+        }
+      }
+      for (; j < n4; j += kThreads) {
+        const float4 v = stream_load4(row4 + j), w = x4[j];
+        s0 = fma((double)v.x, (double)w.x, s0);
+        s1 = fma((double)v.y, (double)w.y, s1);
+        s2 = fma((double)v.z, (double)w.z, s2);
+        s3 = fma((double)v.w, (double)w.w, s3);
+      }
+      s = (s0 + s1) + (s2 + s3);
+    } else {
+      for (int64_t j = threadIdx.x; j < a.d; j += kThreads)
+        s = fma((double)row[j], (double)a.x[j], s);
+    }
   }
   s = segment_sum(s, kThreads, lds_d);
   if (threadIdx.x == 0) {
@@ -75,17 +118,50 @@ __global__ __launch_bounds__(kThreads) void dense_margin_kernel(GradArgs a_all) 
   }
 }
 
+// g_j = sum over the batch, in batch order, of coef_b * A[r_b][j].  VEC: thread per 4 columns,
+// eight rows' loads in flight; the row ids and coefficients are uniform over the work-group.
+template <bool VEC>
 __global__ __launch_bounds__(kThreads) void dense_colsum_kernel(GradArgs a_all) {
   const GradArgs a = for_worker(a_all);
-  const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j >= a.d) return;
-  double acc = 0.0;
-  for (int b = 0; b < a.B; ++b) {
-    const int64_t r = a.rows[b];
-    if (r < 0 || r >= a.n_rows) continue;
-    acc = fma((double)a.coef[b], (double)a.A[r * a.d + j], acc);
+  if (VEC) {
+    constexpr int kRows = 8;
+    const int64_t j4 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (j4 >= a.d / 4) return;
+    const float4* A4 = reinterpret_cast<const float4*>(a.A);
+    const int64_t pitch4 = a.d / 4;
+    double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+    for (int b0 = 0; b0 < a.B; b0 += kRows) {
+      float4 v[kRows];
+      double cf[kRows];
+#pragma unroll
+      for (int u = 0; u < kRows; ++u) {
+        const int b = b0 + u < a.B ? b0 + u : a.B - 1;
+        const int64_t r = a.rows[b];
+        const bool ok = b0 + u < a.B && r >= 0 && r < a.n_rows;
+        cf[u] = ok ? (double)a.coef[b] : 0.0;
+        v[u] = stream_load4(A4 + (ok ? r : 0) * pitch4 + j4);
+        if (!ok) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < kRows; ++u) {
+        acc0 = fma(cf[u], (double)v[u].x, acc0);
+        acc1 = fma(cf[u], (double)v[u].y, acc1);
+        acc2 = fma(cf[u], (double)v[u].z, acc2);
+        acc3 = fma(cf[u], (double)v[u].w, acc3);
+      }
+    }
+    reinterpret_cast<float4*>(a.g)[j4] = make_float4((float)acc0, (float)acc1, (float)acc2, (float)acc3);
+  } else {
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (j >= a.d) return;
+    double acc = 0.0;
+    for (int b = 0; b < a.B; ++b) {
+      const int64_t r = a.rows[b];
+      if (r < 0 || r >= a.n_rows) continue;
+      acc = fma((double)a.coef[b], (double)a.A[r * a.d + j], acc);
+    }
+    a.g[j] = (float)acc;
   }
-  a.g[j] = (float)acc;
 }
 
 __global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* p_all, int64_t n,
@@ -188,9 +264,15 @@ static int grad_launch(int format, const float* A_or_vals, const int64_t* indptr
   const dim3 block(kThreads);
   const unsigned Mu = (unsigned)M;
   if (!csr) {
-    hipLaunchKernelGGL(dense_margin_kernel, dim3(B, Mu), block, 0, stream, a);
-    hipLaunchKernelGGL(dense_colsum_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), Mu), block,
-                       0, stream, a);
+    if ((d % 4) == 0 && aligned(A_or_vals, 16) && aligned(x, 16)) {
+      hipLaunchKernelGGL((dense_margin_kernel<true>), dim3(B, Mu), block, 0, stream, a);
+      hipLaunchKernelGGL((dense_colsum_kernel<true>),
+                         dim3((unsigned)((d / 4 + kThreads - 1) / kThreads), Mu), block, 0, stream, a);
+    } else {
+      hipLaunchKernelGGL((dense_margin_kernel<false>), dim3(B, Mu), block, 0, stream, a);
+      hipLaunchKernelGGL((dense_colsum_kernel<false>),
+                         dim3((unsigned)((d + kThreads - 1) / kThreads), Mu), block, 0, stream, a);
+    }
   } else {
     const dim3 grid_rows((B + kWaves - 1) / kWaves, Mu);
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((d + 4 * kThreads - 1) / (4 * kThreads)), Mu),

@@ -251,9 +251,10 @@ def test_checkpoint_resume_is_bit_identical():
 
 # ------------------------------------------------------------------ local gradient
 
-def test_local_grad_dense_matches_oracle():
+@pytest.mark.parametrize("d,B", [(1000, 64), (1003, 64), (4100, 13), (6144, 1), (257, 50)])
+def test_local_grad_dense_matches_oracle(d, B):
     rng = np.random.default_rng(5)
-    n, d, B = 512, 1000, 64
+    n = 512
     A = rng.standard_normal((n, d)).astype(np.float32)
     y = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
     rows = rng.integers(0, n, B).astype(np.int32)
