@@ -160,11 +160,22 @@ def select_bench(args, wl, qa, synth, torch, np, dev):
     again = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
     cnt2 = torch.zeros((M, nb), dtype=torch.int32, device=dev)
     t_selc = timed(lambda: qa.qa_select_codes(L, dense, ind, NW, again, cnt2))   # the pull direction's S
+    # the server's update: dense step on the decoded codes vs the step that reads the sparse
+    # messages directly (state copies so that both start from the same x, G, z each time)
+    xs, Gs, zs = x.clone(), G.clone(), z.clone()
+    t_step_dense = timed(lambda: qa.qa_step_qcmd(L, dense, sc, xs, Gs, zs, eta, lam, delta,
+                                                 qa.QA_REQUANT_NONE, None))
+    xs.copy_(x); Gs.copy_(G); zs.copy_(z)
+    t_step_sparse = timed(lambda: qa.qa_step_qcmd_selected(L, ind, NW, sel, sc, xs, Gs, zs, eta, lam,
+                                                           delta, qa.QA_REQUANT_NONE, None))
     k = int(cnt.sum().item())
     frac = k / (M * d)
     by = {"indicator": (4 * M + 8 + M / 8) * d, "quantize_selected": M * d * (4 + 1 / 8) + k / 4,
           "decode": M * d * (1 / 8 + 1 / 4) + k / 4, "select_codes": M * d * (1 / 8 + 1 / 4) + k / 4}
-    ms = {"indicator": t_ind, "quantize_selected": t_q, "decode": t_dec, "select_codes": t_selc}
+    by["step_qcmd_dense_codes"] = d * (M / 4 + 24)
+    by["step_qcmd_selected"] = d * (M / 8 + 24) + k / 4
+    ms = {"indicator": t_ind, "quantize_selected": t_q, "decode": t_dec, "select_codes": t_selc,
+          "step_qcmd_dense_codes": t_step_dense, "step_qcmd_selected": t_step_sparse}
     out = {"metric": "sparse encoding kernels: worker-coordinates/s (indicator + Q(S(g,I)) + decode)",
            "value": M * d / ((t_ind + t_q + t_dec) * 1e-3), "unit": "worker-coordinates/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_ind + t_q + t_dec,

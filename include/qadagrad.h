@@ -245,6 +245,23 @@ int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind
 int qa_select_codes(const qa_layout* layout, const uint32_t* codes, const uint32_t* ind,
                     int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts, void* stream);
 
+/* The fused steps on sparse-encoded messages (Algorithm 1: the server's "Decode" followed by
+ * SynQ_t and the update; on a worker, the update from the pushed S(q_t, I^Syn) with M = 1):
+ * exactly qa_decode_selected into a dense code buffer followed by qa_step_qcmd / qa_step_qrda on
+ * it, without that buffer.  ind / ind_stride / sel_codes as for qa_decode_selected, scales as
+ * written by qa_quantize_pack_selected; ind_stride = 0 applies one indicator to all M messages.
+ * Only the first ceil(count/16) words of a bucket's area are read, count = marked components of
+ * the bucket.  Everything else (arguments, requant, workspace of QA_OP_STEP, errors) as for
+ * the dense steps; bucket restrictions as for the other calls of this group. */
+int qa_step_qcmd_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                          const uint32_t* sel_codes, const float* scales, float* x, float* G,
+                          float* z_or_null, float eta, float lambda, float delta, int requant,
+                          void* ws, size_t ws_bytes, void* stream);
+int qa_step_qrda_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                          const uint32_t* sel_codes, const float* scales, float* x, float* G,
+                          float* z, int64_t t, float eta, float lambda, float delta, int requant,
+                          void* ws, size_t ws_bytes, void* stream);
+
 /* ---- a list of parameter tensors in one flat vector --------------------------------------------
  *
  * For models whose parameters are many tensors of very different sizes (the convolutional

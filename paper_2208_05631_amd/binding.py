@@ -251,6 +251,25 @@ def qa_select_codes(layout, codes, ind, ind_stride, sel_codes, counts, stream=No
                                 _p(counts), _stream(stream)), "qa_select_codes")
 
 
+def qa_step_qcmd_selected(layout, ind, ind_stride, sel_codes, scales, x, G, z_or_null, eta, lam, delta,
+                          requant, ws, stream=None):
+    _lib.qa_step_qcmd_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp, _vp, _vp,
+                                           C.c_float, C.c_float, C.c_float, C.c_int, _vp, _sz, _vp]
+    _check(_lib.qa_step_qcmd_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes), _p(scales),
+                                      _p(x), _p(G), _p(z_or_null), eta, lam, delta, requant, _p(ws),
+                                      _nbytes(ws), _stream(stream)), "qa_step_qcmd_selected")
+
+
+def qa_step_qrda_selected(layout, ind, ind_stride, sel_codes, scales, x, G, z, t, eta, lam, delta,
+                          requant, ws, stream=None):
+    _lib.qa_step_qrda_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp, _vp, _vp,
+                                           C.c_int64, C.c_float, C.c_float, C.c_float, C.c_int, _vp,
+                                           _sz, _vp]
+    _check(_lib.qa_step_qrda_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes), _p(scales),
+                                      _p(x), _p(G), _p(z), t, eta, lam, delta, requant, _p(ws),
+                                      _nbytes(ws), _stream(stream)), "qa_step_qrda_selected")
+
+
 def qa_segment_plan_host(d, begin, length):
     """Host-only validation and table of a tensor list -> (n_pieces, table as a list of int64)."""
     n = len(begin)

@@ -8,6 +8,7 @@
 // gbar = (float)(acc / M), optionally re-quantizes gbar per bucket inside the tile, and applies
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
 #include "qa_segments.h"
+#include "qa_sparse.h"
 
 namespace qa {
 
@@ -28,6 +29,10 @@ struct StepArgs {
   double* abs_partials;   // aggregate mode, optional: sum of |gbar| of each tile (first pass of a quantizer)
   float eta, lam_eta, delta, t_lam, thr_coef;
   SegTable seg;       // tensor-list launches: work-group = piece, one scale column per tensor
+  // sparse-encoded messages (kernels with SPARSE): `codes` holds the compact per-bucket streams,
+  // worker m's indicator words start at ind + m*ind_stride (stride 0: one indicator for all)
+  const uint32_t* ind;
+  int64_t ind_stride;
 };
 
 // 10 -> 00 so that the reserved pattern reads as zero; 01 and 11 are unchanged.
@@ -91,6 +96,13 @@ __device__ __forceinline__ uint32_t stream_load(const uint32_t* row, uint32_t by
   const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint32_t*>(row), 0, (int)row_bytes, 0x00020000 /* 32-bit data, raw addressing */);
   return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 2 /* nt */);
+}
+// The same without the streaming hint, for words that several lanes or waves read.
+__device__ __forceinline__ uint32_t cached_load(const uint32_t* row, uint32_t byte_off,
+                                                uint32_t row_bytes) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(row), 0, (int)row_bytes, 0x00020000);
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0);
 }
 __device__ __forceinline__ void stream_store4(float* p, const float4& v) {
   floatx4 t = {v.x, v.y, v.z, v.w};
@@ -159,8 +171,17 @@ __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t 
 // Chunks of 16 rather than 64 workers, and the state requested only after the look-ups, keep the
 // kernel at about 100-120 vector registers, i.e. four waves per SIMD: measured faster than
 // holding all 64 code words (and the state) in registers with two waves per SIMD.
-template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
+//
+// SPARSE: the messages arrive in the sparse encoding (indicator + compact stream per 4096-bucket)
+// and are expanded to dense code words on the fly, a chunk of workers at a time: a thread's 16
+// coordinates are the 16 indicator bits of half an indicator word; the position of its first
+// marked component in the bucket's stream is the number of marked components before it (counts of
+// two workers share one 32-bit prefix scan over the work-group); the codes are fetched from the
+// stream and spread to the marked fields through the deposit table.  The result is the word the
+// stand-alone decoder would have written, and everything after it is the dense path.
+template <int MODE, bool TRACK_Z, bool REQUANT, int NGT, bool SPARSE = false>
 __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
+  static_assert(!SPARSE || NGT == 0, "sparse input: chunks of 16 workers with guards");
   constexpr bool FULL = NGT > 1;
   constexpr int kGroupsPerChunk = NGT >= 1 ? NGT : kMaxGroups;
   constexpr int kChunk = 4 * kGroupsPerChunk;
@@ -170,7 +191,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   __shared__ double lds_d[kWaves];
   __shared__ uint32_t lds_u[kWaves];
   __shared__ int lds_e[3 * kWaves];
+  __shared__ uint8_t dep[SPARSE ? 16 * 256 : 16];
+  __shared__ uint32_t lds_scan[kWaves][SPARSE ? kChunk / 2 : 1];
   const int t = threadIdx.x;
+  if (SPARSE)                                             // visible after the first barrier below
+    reinterpret_cast<uint4*>(dep)[t] = reinterpret_cast<const uint4*>(kDepositLut.v)[t];
   // the work-group's tile, its live coordinates [lo, hi) and its column of scales
   int64_t tile, lo, hi, k;
   if (a.seg.piece_tile) {
@@ -197,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 
   // ---- request the first chunk of code words ----
   uint32_t w[kChunk];
-  {
+  if (!SPARSE) {
     const int left = own_scales ? 0 : a.M;
 #pragma unroll
     for (int i = 0; i < kChunk; ++i)
@@ -238,33 +263,112 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 #pragma unroll
   for (int j = 0; j < 16; ++j) acc[j] = 0.0;
 
-  if (reorder_ok) {
-    // decoded values of the four 2-bit fields of byte t (reserved pattern 10 -> 0)
-    double dj[4];
+  // decoded values of the four 2-bit fields of byte t (reserved pattern 10 -> 0)
+  double dj[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int f = (t >> (2 * j)) & 3;
-      dj[j] = f == 1 ? 1.0 : (f == 3 ? -1.0 : 0.0);
+  for (int j = 0; j < 4; ++j) {
+    const int f = (t >> (2 * j)) & 3;
+    dj[j] = f == 1 ? 1.0 : (f == 3 ? -1.0 : 0.0);
+  }
+  // tables of the chunk that starts at worker m0, then the look-ups of its code words wc
+  auto chunk = [&](const uint32_t (&wc)[kChunk], int m0) {
+    const int left = a.M - m0;
+    const int ng = (FULL || left >= kChunk) ? kGroupsPerChunk : (left + 3) / 4;
+    if (m0 > 0) __syncthreads();                         // readers of the previous tables are done
+    if (t < kChunk) s_scale[t] = t < left ? (double)sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0;
+    __syncthreads();
+    for (int g = 0; g < ng; ++g) {
+      const double e = fma(dj[3], s_scale[4 * g + 3],
+                           fma(dj[2], s_scale[4 * g + 2],
+                               fma(dj[1], s_scale[4 * g + 1], dj[0] * s_scale[4 * g])));
+      tab[g * 256 + t] = e;
     }
-    // tables of the chunk that starts at worker m0, then the look-ups of its code words wc
-    auto chunk = [&](const uint32_t (&wc)[kChunk], int m0) {
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < kGroupsPerChunk; ++g)
+      if (FULL || g < ng)
+        lookup_group(wc[4 * g], wc[4 * g + 1], wc[4 * g + 2], wc[4 * g + 3], tab + g * 256, acc);
+  };
+
+  if (SPARSE) {
+    const int wave = t / kWave;
+    // indicator words of this tile that exist; half-word t&1 of word t/2 covers the thread's 16
+    // coordinates; bits at or beyond d are not components
+    const int64_t NW = (a.d + 31) / 32;
+    const int64_t iw_here = NW - tile * (kTile / 32);
+    const uint32_t ind_bytes = 4u * (uint32_t)(iw_here >= kTile / 32 ? kTile / 32 : iw_here);
+    const uint32_t* itile = a.ind + tile * (kTile / 32);
+    const uint32_t ind_off = (uint32_t)(t >> 1) * 4u;
+    const int64_t live = a.d - (tile_base + 16 * (int64_t)t);
+    const uint32_t live_mask = live >= 16 ? 0xFFFFu : (live > 0 ? (1u << live) - 1u : 0u);
+    for (int m0 = 0; m0 < a.M; m0 += kChunk) {
       const int left = a.M - m0;
-      const int ng = (FULL || left >= kChunk) ? kGroupsPerChunk : (left + 3) / 4;
-      if (m0 > 0) __syncthreads();                       // readers of the previous tables are done
-      if (t < kChunk) s_scale[t] = t < left ? (double)sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0;
-      __syncthreads();
-      for (int g = 0; g < ng; ++g) {
-        const double e = fma(dj[3], s_scale[4 * g + 3],
-                             fma(dj[2], s_scale[4 * g + 2],
-                                 fma(dj[1], s_scale[4 * g + 1], dj[0] * s_scale[4 * g])));
-        tab[g * 256 + t] = e;
+      uint32_t mk[kChunk];
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        const uint32_t iv =
+            i < left ? stream_load(itile + (int64_t)(m0 + i) * a.ind_stride, ind_off, ind_bytes) : 0u;
+        mk[i] = (iv >> (16 * (t & 1))) & live_mask;
+      }
+      // marked components before this thread's, per worker (two 16-bit counts per scan; a tile
+      // holds at most 4096)
+      uint32_t ex[kChunk / 2];
+      if (m0 > 0) __syncthreads();                       // readers of the previous totals are done
+#pragma unroll
+      for (int p = 0; p < kChunk / 2; ++p) {
+        const uint32_t own = (uint32_t)__popc(mk[2 * p]) | ((uint32_t)__popc(mk[2 * p + 1]) << 16);
+        const uint32_t incl = wave_inclusive_scan_u32(own);
+        if ((t % kWave) == kWave - 1) lds_scan[wave][p] = incl;
+        ex[p] = incl - own;
       }
       __syncthreads();
 #pragma unroll
-      for (int g = 0; g < kGroupsPerChunk; ++g)
-        if (FULL || g < ng)
-          lookup_group(wc[4 * g], wc[4 * g + 1], wc[4 * g + 2], wc[4 * g + 3], tab + g * 256, acc);
-    };
+      for (int p = 0; p < kChunk / 2; ++p)
+#pragma unroll
+        for (int v = 0; v < kWaves - 1; ++v) ex[p] += v < wave ? lds_scan[v][p] : 0u;
+      // the thread's n <= 16 codes start at code `before` of the worker's stream for this bucket:
+      // word before/16 and, if they cross a word boundary, the next one.  Offsets beyond the
+      // words that exist for this tile read as 0 (never needed: the stream holds every marked
+      // component of the tile)
+      uint32_t s_lo[kChunk], s_hi[kChunk];
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        const uint32_t before = (ex[i / 2] >> (16 * (i & 1))) & 0xFFFFu;
+        const uint32_t* area = ctile + (int64_t)(m0 + i) * a.code_stride;
+        s_lo[i] = i < left ? cached_load(area, (before >> 4) * 4u, row_bytes) : 0u;
+        s_hi[i] = i < left ? cached_load(area, (before >> 4) * 4u + 4u, row_bytes) : 0u;
+      }
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        const uint32_t before = (ex[i / 2] >> (16 * (i & 1))) & 0xFFFFu;
+        uint32_t win = __builtin_amdgcn_alignbit(s_hi[i], s_lo[i], 2u * (before & 15u));
+        uint32_t out = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t nib = (mk[i] >> (4 * q)) & 15u;
+          out |= (uint32_t)dep[nib * 256 + (win & 0xFFu)] << (8 * q);
+          win >>= 2 * __popc(nib);
+        }
+        w[i] = out;
+      }
+      if (reorder_ok) {
+        chunk(w, m0);
+      } else {
+        // ordered sum, as it is written: worker m0, m0+1, ...
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u)
+          if (u < left) {
+            const uint32_t wv = sanitize(w[u]);
+            const double sv = (double)sc[(int64_t)(m0 + u) * a.scale_stride];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int c = ((int)(wv << (30 - 2 * j))) >> 30;
+              acc[j] = fma((double)c, sv, acc[j]);
+            }
+          }
+      }
+    }
+  } else if (reorder_ok) {
     for (int m0 = 0; m0 < a.M; m0 += kChunk) {
       if (m0 > 0) {
         const int left = a.M - m0;
@@ -475,15 +579,19 @@ static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float
   return a;
 }
 
-template <int MODE, bool TRACK_Z, bool REQUANT, int NGT>
+template <int MODE, bool TRACK_Z, bool REQUANT, int NGT, bool SPARSE = false>
 static void launch_lut(const StepArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
-  hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, NGT>), grid, block, 0, stream, a);
+  hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, NGT, SPARSE>), grid, block, 0, stream, a);
 }
 
 // ngt: the NGT of the kernel variant
 template <int MODE, bool TRACK_Z, bool REQUANT>
 static void launch_one(const StepArgs& a, int ngt, hipStream_t stream) {
   const dim3 grid((unsigned)(a.seg.piece_tile ? a.seg.n_pieces : tiles_of(a.d))), block(kThreads);
+  if (a.ind) {                                           // sparse-encoded messages
+    launch_lut<MODE, TRACK_Z, REQUANT, 0, true>(a, grid, block, stream);
+    return;
+  }
   switch (ngt) {
     case 4: launch_lut<MODE, TRACK_Z, REQUANT, 4>(a, grid, block, stream); break;
     case 2: launch_lut<MODE, TRACK_Z, REQUANT, 2>(a, grid, block, stream); break;
@@ -505,13 +613,21 @@ static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream
   }
 }
 
+// sparse: `codes` are compact per-bucket streams to be expanded through the indicators `ind`
 static int step_common(int mode, const qa_layout* L, const uint32_t* codes, const float* scales,
                        float* x, float* G, float* z, bool track_z, int64_t t, float eta,
                        float lambda, float delta, int requant, void* ws, size_t ws_bytes,
-                       hipStream_t stream) {
+                       hipStream_t stream, bool sparse = false, const uint32_t* ind = nullptr,
+                       int64_t ind_stride = 0) {
   int rc = check_layout(L);
   if (rc != QA_OK) return rc;
   if (!codes || !scales || !x || !G) return QA_ERR_INVALID_ARG;
+  if (sparse) {
+    if (!ind) return QA_ERR_INVALID_ARG;
+    if (ind_stride != 0 && ind_stride < (L->d + 31) / 32) return QA_ERR_INVALID_ARG;
+    if (!aligned(ind, 4)) return QA_ERR_ALIGNMENT;
+    if (!(L->bucket == kTile || (L->bucket == 0 && L->d <= kTile))) return QA_ERR_UNSUPPORTED;
+  }
   if (mode == kQrda && !z) return QA_ERR_INVALID_ARG;
   if (!(eta > 0.0f) || !(lambda >= 0.0f) || !(delta > 0.0f)) return QA_ERR_INVALID_ARG;
   if (mode == kQrda && t < 1) return QA_ERR_INVALID_ARG;
@@ -545,6 +661,7 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
       const size_t qws = quantize_workspace_bytes(&R);
       StepArgs ag = make_args(L, codes, scales);
       ag.gbar = gbar;
+      if (sparse) { ag.ind = ind; ag.ind_stride = ind_stride; }
       // the table-driven kernel also leaves the quantizer's first pass (tile sums of |gbar|) in
       // the quantizer's workspace
       const bool fuse_abs = qws != 0;
@@ -559,6 +676,7 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
   }
 
   StepArgs a = make_args(use, use_codes, use_scales);
+  if (sparse && use == L) { a.ind = ind; a.ind_stride = ind_stride; }   // else: dense Q(SynQ) message
   a.x = x; a.G = G; a.z = z;
   a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta;
   a.t_lam = (float)t * lambda;
@@ -682,4 +800,23 @@ extern "C" int qa_step_qrda(const qa_layout* layout, const uint32_t* codes, cons
                             float delta, int requant, void* ws, size_t ws_bytes, void* stream) {
   return qa::step_common(qa::kQrda, layout, codes, scales, x, G, z, false, t, eta, lambda, delta,
                          requant, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int qa_step_qcmd_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                                     const uint32_t* sel_codes, const float* scales, float* x,
+                                     float* G, float* z_or_null, float eta, float lambda, float delta,
+                                     int requant, void* ws, size_t ws_bytes, void* stream) {
+  return qa::step_common(qa::kQcmd, layout, sel_codes, scales, x, G, z_or_null, z_or_null != nullptr,
+                         1, eta, lambda, delta, requant, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream), true, ind, ind_stride);
+}
+
+extern "C" int qa_step_qrda_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                                     const uint32_t* sel_codes, const float* scales, float* x,
+                                     float* G, float* z, int64_t t, float eta, float lambda,
+                                     float delta, int requant, void* ws, size_t ws_bytes,
+                                     void* stream) {
+  return qa::step_common(qa::kQrda, layout, sel_codes, scales, x, G, z, false, t, eta, lambda, delta,
+                         requant, ws, ws_bytes, static_cast<hipStream_t>(stream), true, ind,
+                         ind_stride);
 }

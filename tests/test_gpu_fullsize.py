@@ -91,8 +91,9 @@ def test_sampled_buckets_at_full_size(name):
 
 
 def test_sparse_encoding_beyond_2_32_coordinates():
-    """Indicator, selected quantizer, code selection and decoder with every index past 32 bits:
-    all four are local to a 4096-bucket, so sampled buckets are checked against the oracle."""
+    """Indicator, selected quantizer, code selection, decoder and the step on the sparse message
+    with every index past 32 bits: all are local to a 4096-bucket, so sampled buckets are checked
+    against the oracle."""
     d, M, b = (1 << 32) + 5 * 4096 + 40, 1, 4096
     eta, lam, delta, t = 0.1, 1e-4, 1e-8, 7
     nb, NW = (d + b - 1) // b, (d + 31) // 32
@@ -117,6 +118,7 @@ def test_sparse_encoding_beyond_2_32_coordinates():
     dense = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
     again = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
     cnt2 = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
+    kept = []
     for method in (0, 1):
         qa.qa_indicator(L, method, g, d, x, G, z, t, eta, lam, delta, ind, NW)
         qa.qa_quantize_pack_selected(L, g, d, ind, NW, sel, cnt, sc, None)
@@ -140,7 +142,18 @@ def test_sparse_encoding_beyond_2_32_coordinates():
             assert np.array_equal(host(again[0, k * 256:k * 256 + nwk]), host(sel[0, k * 256:k * 256 + nwk]))
             assert int(host(cnt2[0, k])) == int(o_cnt[0])
             marked += int(o_cnt[0])
+            if method == 1:
+                kept.append((int(k), n, o_dense, o_sc, xs.copy(), Gs.copy(), zs.copy()))
         assert marked > 0
+    # the step that reads the sparse message directly (in place, last: it changes the state)
+    qa.qa_step_qrda_selected(L, ind, NW, sel, sc, x, G, z, t, eta, lam, delta, qa.QA_REQUANT_NONE, None)
+    torch.cuda.synchronize()
+    for k, n, o_dense, o_sc, xs, Gs, zs in kept:
+        oracle.step_qrda(o_dense[None, :], np.asarray(o_sc, np.float32).reshape(1, 1), n, 0, xs, Gs, zs,
+                         t, eta, lam, delta)
+        lo = k * b
+        for got, ref in ((x, xs), (G, Gs), (z, zs)):
+            assert np.array_equal(host(got[lo:lo + n]).view(np.uint32), ref.view(np.uint32)), k
 
 
 def test_tensor_list_beyond_2_32_coordinates():

@@ -238,6 +238,87 @@ def test_unsupported_bucket_sizes_are_refused():
     assert e.value.code == -5
 
 
+SPARSE_STEP_CASES = [
+    # d, M, bucket, fraction marked, requant, one indicator for all, scales spread over many binades
+    (1, 1, 0, 1.0, 0, False, False), (1000, 3, 0, 0.3, 0, False, False), (1000, 2, 0, 0.3, 2, False, False),
+    (4096, 2, 4096, 0.5, 1, False, False), (4097, 5, 4096, 0.05, 0, False, False),
+    (70001, 4, 4096, 0.2, 0, False, False), (70001, 16, 4096, 0.3, 1, False, False),
+    (70001, 20, 4096, 1.0, 0, False, False), (70001, 40, 4096, 0.1, 0, False, False),
+    (70001, 3, 4096, 0.2, 2, False, False), (20000, 2, 4096, 0.0, 0, False, False),
+    (70001, 1, 4096, 0.2, 0, True, False), (70001, 4, 4096, 0.2, 1, True, False),
+    (70001, 20, 4096, 0.3, 0, False, True), (9000, 4, 4096, 0.4, 1, False, True),
+]
+
+
+@pytest.mark.parametrize("d,M,bucket,p,requant,shared,wide", SPARSE_STEP_CASES)
+def test_steps_on_sparse_messages_match_oracle_decode_then_step(d, M, bucket, p, requant, shared, wide):
+    """qa_step_*_selected against the oracle's decode followed by its step, three steps in a row
+    (QCMD with z, QCMD, QRDA).  Words of a bucket's area beyond ceil(count/16) hold garbage and
+    must not matter; `wide` scales force the worker-ordered sum."""
+    rng = np.random.default_rng(d + 7 * M + requant)
+    eta, lam, delta = 0.1, 2e-4, 1e-8
+    L = qa.Layout.make(d, M, bucket)
+    nb, W, NW = L.n_buckets, L.words, (d + 31) // 32
+    ox, oG, oz = rand_state(rng, d)
+    xd, Gd, zd = dev(ox), dev(oG), dev(oz)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
+    for t in (1, 2, 3):
+        g = (rng.standard_normal((M, d)) * rng.choice([1e-3, 0.02], (M, d))).astype(np.float32)
+        ind = random_indicator(rng, 1 if shared else M, d, p)
+        if d > 8192:
+            ind[0, 128:256] = 0                                      # an empty bucket
+        sel = np.full((M, L.code_stride), 0x5A5A5A5A, np.uint32)
+        sc = np.zeros((M, nb), np.float32)
+        dense = np.zeros((M, W), np.uint32)
+        for m in range(M):
+            im = ind[0 if shared else m]
+            o_sel, o_cnt, o_sc, _ = oracle.quantize_selected(g[m], im, bucket=bucket)
+            for k in range(nb):
+                nwk = (int(o_cnt[k]) + 15) // 16
+                lo = k * (256 if bucket else (d + 15) // 16)
+                sel[m, k * 256: k * 256 + nwk] = o_sel[lo: lo + nwk]
+            sc[m] = o_sc
+            dense[m] = oracle.decode_selected(im, o_sel, d, bucket=bucket)
+        if wide:
+            sc = (sc * np.exp2(rng.integers(-30, 31, sc.shape))).astype(np.float32)
+            if M > 2:
+                sc[1, 0] = np.inf                                    # a non-finite scale: ordered sum too
+        ind_d, sel_d, sc_d = dev(ind.view(np.int32)), dev(sel.view(np.int32)), dev(sc)
+        stride = 0 if shared else NW
+        with np.errstate(invalid="ignore", over="ignore"):
+            if t == 3:
+                oracle.step_qrda(dense, sc, d, bucket, ox, oG, oz, t, eta, lam, delta, requant)
+            else:
+                oracle.step_qcmd(dense, sc, d, bucket, ox, oG, oz if t == 1 else None, eta, lam, delta, requant)
+        if t == 3:
+            qa.qa_step_qrda_selected(L, ind_d, stride, sel_d, sc_d, xd, Gd, zd, t, eta, lam, delta, requant, ws)
+        else:
+            qa.qa_step_qcmd_selected(L, ind_d, stride, sel_d, sc_d, xd, Gd, zd if t == 1 else None,
+                                     eta, lam, delta, requant, ws)
+        torch.cuda.synchronize()
+        for got, ref, name in ((xd, ox, "x"), (Gd, oG, "G"), (zd, oz, "z")):
+            gh = host(got)
+            same = (gh.view(np.uint32) == ref.view(np.uint32)) | (np.isnan(gh) & np.isnan(ref))
+            assert same.all(), (name, t, int((~same).sum()))
+    assert p == 0.0 or wide or np.count_nonzero(ox) > 0
+
+
+def test_sparse_steps_check_their_arguments():
+    L = qa.Layout.make(100000, 2, 1024)
+    t = torch.zeros(8, dtype=torch.int32, device=DEV)
+    f = torch.zeros(8, dtype=torch.float32, device=DEV)
+    with pytest.raises(qa.QaError) as e:
+        qa.qa_step_qcmd_selected(L, t, 100000, t, f, f, f, None, 0.1, 0.0, 1e-8, 0, None)
+    assert e.value.code == -5
+    L = qa.Layout.make(100000, 2, 4096)
+    with pytest.raises(qa.QaError) as e:                             # indicator rows overlap
+        qa.qa_step_qrda_selected(L, t, 5, t, f, f, f, f, 1, 0.1, 0.0, 1e-8, 0, None)
+    assert e.value.code == -1
+    with pytest.raises(qa.QaError) as e:                             # no indicator
+        qa.qa_step_qrda_selected(L, None, 0, t, f, f, f, f, 1, 0.1, 0.0, 1e-8, 0, None)
+    assert e.value.code == -1
+
+
 @pytest.mark.parametrize("method", ["qcmd", "qrda"])
 def test_training_with_selection_matches_oracle(method):
     """Algorithm 1 with the indicator: local gradients -> indicator -> Q(S(g, I)) -> decode ->
