@@ -322,7 +322,8 @@ def test_sparse_steps_check_their_arguments():
 @pytest.mark.parametrize("method", ["qcmd", "qrda"])
 def test_training_with_selection_matches_oracle(method):
     """Algorithm 1 with the indicator: local gradients -> indicator -> Q(S(g, I)) -> decode ->
-    fused step, on the CSR stand-in (d = 2^18 here), T = 25.  Both sides run the whole loop."""
+    fused step (alternating with the step that decodes on the fly), on the CSR stand-in
+    (d = 2^18 here), T = 25.  Both sides run the whole loop."""
     d, M, B, b, T = 1 << 18, 8, 128, 4096, 25
     eta, lam, delta = 0.1, 1e-4, 1e-8
     p = synth.csr_problem(n=1 << 13, d=d, nnz_per_row=50, M=M, seed=3)
@@ -346,10 +347,16 @@ def test_training_with_selection_matches_oracle(method):
         qa.qa_indicator(L, mth, g, gs, x, G, z, t, eta, lam, delta, ind, NW)
         qa.qa_quantize_pack_selected(L, g, gs, ind, NW, sel, cnt, sc, None)
         qa.qa_decode_selected(L, ind, NW, sel, dense)
-        if method == "qcmd":
-            qa.qa_step_qcmd(L, dense, sc, x, G, z, eta, lam, delta, 0, None)
-        else:
-            qa.qa_step_qrda(L, dense, sc, x, G, z, t, eta, lam, delta, 0, None)
+        if t % 2:                                # odd steps: dense step on the decoded codes
+            if method == "qcmd":
+                qa.qa_step_qcmd(L, dense, sc, x, G, z, eta, lam, delta, 0, None)
+            else:
+                qa.qa_step_qrda(L, dense, sc, x, G, z, t, eta, lam, delta, 0, None)
+        else:                                    # even steps: the step reads the sparse messages itself
+            if method == "qcmd":
+                qa.qa_step_qcmd_selected(L, ind, NW, sel, sc, x, G, z, eta, lam, delta, 0, None)
+            else:
+                qa.qa_step_qrda_selected(L, ind, NW, sel, sc, x, G, z, t, eta, lam, delta, 0, None)
         # oracle side
         og = np.stack([oracle.local_grad_csr(p.vals, p.indptr, p.indices, d, p.y, rows[m], ox)[0] for m in range(M)])
         oind = np.stack([oracle.indicator(mth, og[m], ox, oG, oz, t, eta, lam, delta) for m in range(M)])
