@@ -180,6 +180,8 @@ STEP_CASES = [
     (9000, 24, 4096, 0), (9000, 48, 4096, 1), (9000, 20, 0, 0), (9000, 12, 4096, 2), (9000, 40, 8192, 0),
     # buckets smaller than the tile without in-kernel second quantization: per-thread scales
     (10000, 3, 64, 0), (10000, 9, 256, 0), (70001, 16, 1024, 0), (70001, 64, 2048, 2), (4100, 8, 512, 2),
+    # the largest worker count the layout accepts, and a large odd one
+    (5000, 4096, 4096, 0), (3000, 1001, 0, 2),
 ]
 
 

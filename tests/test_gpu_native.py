@@ -1,6 +1,6 @@
 """The C ABI used from a plain C++ host program (no Python, no torch in that process):
 tests/native/abi_direct.cpp, built by __graft_entry__.build(), links libqadagrad.so and the CPU
-checker and compares them bit for bit; this test runs it and reads its verdict."""
+checker and compares them bit for bit; this test runs it and reads its result."""
 import os
 import subprocess
 
