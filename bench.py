@@ -471,6 +471,12 @@ def main():
         "quantize_pack": {"ms_per_worker": quant_ms, "worker_coords_per_s": d / (quant_ms * 1e-3),
                           "achieved_GBps": qbytes * d / (quant_ms * 1e-3) / 1e9,
                           "frac": qbytes * d / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        # rows a2-a8 together for this configuration: M quantize+pack launches (measured above, one
+        # worker's fp32 gradient at a time: M of them do not fit beside the state) + the fused step
+        "quantize_plus_step": {"ms_per_step": M * quant_ms + wall * 1e3 / args.steps,
+                               "coordinates_per_s": d / ((M * quant_ms + wall * 1e3 / args.steps) * 1e-3),
+                               "algorithmic_bytes_per_coord": M * qbytes + sum(
+                                   v["bytes_per_coord"] * v["launches"] for v in kernels.values()) / args.steps},
         "nnz_x_after": nnz_x,
         "device": torch.cuda.get_device_name(0),
     }
