@@ -172,9 +172,20 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(float* p_all, int64
   else for (int e = 0; e < 4; ++e) if (i + e < n) p[i + e] = 0.0f;
 }
 
-// one wave per batch row: margin, coef, loss; also clears the accumulator at the row's columns
+// one wave per batch row: margin, coef, loss; also clears the accumulator at the row's columns.
+// ZERO_G: the work-groups of a worker first share out the zero-fill of its gradient vector (the
+// stores drain while the latency-bound margins are computed); otherwise fill_zero_kernel ran before.
+template <bool ZERO_G>
 __global__ __launch_bounds__(kThreads) void csr_margin_kernel(GradArgs a_all) {
   const GradArgs a = for_worker(a_all);
+  if (ZERO_G) {
+    const int64_t n4 = a.d / 4;
+    const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * per, hi = lo + per < n4 ? lo + per : n4;
+    float4* g4 = reinterpret_cast<float4*>(a.g);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) g4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && threadIdx.x < (a.d & 3)) a.g[4 * n4 + threadIdx.x] = 0.0f;
+  }
   const int b = blockIdx.x * kWaves + threadIdx.x / kWave;
   if (b >= a.B) return;
   const int lane = threadIdx.x % kWave;
@@ -275,9 +286,15 @@ static int grad_launch(int format, const float* A_or_vals, const int64_t* indptr
     }
   } else {
     const dim3 grid_rows((B + kWaves - 1) / kWaves, Mu);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((d + 4 * kThreads - 1) / (4 * kThreads)), Mu),
-                       block, 0, stream, g_out, d, g_stride);
-    hipLaunchKernelGGL(csr_margin_kernel, grid_rows, block, 0, stream, a);
+    // few rows for a long vector: the zero-fill gets a launch of its own
+    const bool fused_fill = d / 4 <= (int64_t)grid_rows.x * kThreads * 32;
+    if (fused_fill) {
+      hipLaunchKernelGGL(csr_margin_kernel<true>, grid_rows, block, 0, stream, a);
+    } else {
+      hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((d + 4 * kThreads - 1) / (4 * kThreads)), Mu),
+                         block, 0, stream, g_out, d, g_stride);
+      hipLaunchKernelGGL(csr_margin_kernel<false>, grid_rows, block, 0, stream, a);
+    }
     hipLaunchKernelGGL((csr_scatter_kernel<false>), grid_rows, block, 0, stream, a);
     hipLaunchKernelGGL((csr_scatter_kernel<true>), grid_rows, block, 0, stream, a);
   }
