@@ -60,8 +60,8 @@ extern "C" {
 #define QA_THRESH_GIVEN 1u /* thresholds[] is an INPUT; only scales and codes are computed   */
 #define QA_THRESH_EXACT 2u /* thresholds[] is an OUTPUT holding the exact least-squares optimum
                               found by ranking (Section 3.4) instead of the 0.75*mean|v| rule;
-                              needs bucket == 4096 or (bucket == 0 and d <= 4096), and a
-                              non-NULL thresholds array                                      */
+                              needs 64 <= bucket <= 4096 or (bucket == 0 and d <= 4096), and
+                              a non-NULL thresholds array                                    */
 
 /* operations for qa_workspace_bytes */
 #define QA_OP_QUANTIZE 1

@@ -438,13 +438,13 @@ __device__ __forceinline__ void sort_move(uint32_t (&e)[16], int t, uint32_t* bu
 // Phase P of the network for P >= 5, entered and left in ownership 0 (positions 16t + r: the
 // block bit P is bit P-4 of t, the same for the thread's 16 keys).  On entry the keys carry the
 // complement state of phase P-1 (PREV_FLIPPED) or none; they leave in the state of phase P, which
-// for P = 12 is "none" (one block, descending).  n counts the moves made so far and picks the
-// buffer.
-template <int P, bool PREV_FLIPPED>
+// for the last phase is "none" (FINAL: every block of 2^P comes out descending; for P = 12 that
+// is the one block there is).  n counts the moves made so far and picks the buffer.
+template <int P, bool PREV_FLIPPED, bool FINAL>
 __device__ __forceinline__ void sort_phase(uint32_t (&e)[16], int t, uint32_t (*buf)[kSortPitch],
                                            int& n) {
   {
-    const uint32_t now = (t >> (P - 4)) & 1u, before = PREV_FLIPPED ? (t >> (P - 5)) & 1u : 0u;
+    const uint32_t now = FINAL ? 0u : (t >> (P - 4)) & 1u, before = PREV_FLIPPED ? (t >> (P - 5)) & 1u : 0u;
     const uint32_t m = (uint32_t)(-(int)(now ^ before));
 #pragma unroll
     for (int r = 0; r < 16; ++r) e[r] ^= m;
@@ -462,7 +462,15 @@ __device__ __forceinline__ void sort_phase(uint32_t (&e)[16], int t, uint32_t (*
   sort_stages<0, P, 4, false>(e, t);
 }
 
+// LOG2B: log2 of the bucket (6..12): the network stops after phase LOG2B, which leaves every
+// bucket of the tile sorted on its own; the prefix sums and the search then run per bucket, over
+// the 2^(LOG2B-4) consecutive threads that hold it.
+template <int LOG2B>
 __global__ __launch_bounds__(kThreads) void exact_threshold_kernel(QuantArgs a) {
+  static_assert(LOG2B >= 6 && LOG2B <= 12, "bucket of 64 .. 4096 components");
+  constexpr int kSeg = 1 << (LOG2B - 4);                 // threads per bucket
+  constexpr int kSegLanes = kSeg < kWave ? kSeg : kWave; // ... of them inside one wave
+  constexpr int kSegWaves = kSeg / kSegLanes;            // waves per bucket: 1, 2 or 4
   __shared__ uint32_t buf[2][kSortPitch];
   __shared__ uint32_t lds_first[kThreads];
   __shared__ double lds_tot[kWaves];
@@ -481,67 +489,93 @@ __global__ __launch_bounds__(kThreads) void exact_threshold_kernel(QuantArgs a) 
 #pragma unroll
       for (int c = 0; c < 4; ++c) e[j * 4 + c] = __float_as_uint(fabsf(v[j][c]));
   }
+  // load_tile hands thread t the float4 groups j*256 + t, i.e. components of up to four buckets
+  // when the bucket is smaller than the tile: bring every key to ownership 0 (positions
+  // 16t .. 16t+15) first, so that a thread's keys and every later exchange stay inside a bucket
+  int n = 0;
+  if constexpr (LOG2B < 12) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = ((r >> 2) * kThreads + t) * 4 + (r & 3);
+      buf[0][i + (i >> 4)] = e[r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = 16 * t + r;
+      e[r] = buf[0][i + (i >> 4)];
+    }
+    n = 1;
+  }
   sort_stages<0, 1, 1, true>(e, t);
   sort_stages<0, 2, 2, true>(e, t);
   sort_stages<0, 3, 3, true>(e, t);
   sort_stages<0, 4, 4, true>(e, t);
-  int n = 0;
-  sort_phase<5, false>(e, t, buf, n);
-  sort_phase<6, true>(e, t, buf, n);
-  sort_phase<7, true>(e, t, buf, n);
-  sort_phase<8, true>(e, t, buf, n);
-  sort_phase<9, true>(e, t, buf, n);
-  sort_phase<10, true>(e, t, buf, n);
-  sort_phase<11, true>(e, t, buf, n);
-  sort_phase<12, true>(e, t, buf, n);
-  // the thread now holds positions 16t .. 16t+15 of the descending order
+  sort_phase<5, false, false>(e, t, buf, n);
+  sort_phase<6, true, LOG2B == 6>(e, t, buf, n);
+  if constexpr (LOG2B >= 7) sort_phase<7, true, LOG2B == 7>(e, t, buf, n);
+  if constexpr (LOG2B >= 8) sort_phase<8, true, LOG2B == 8>(e, t, buf, n);
+  if constexpr (LOG2B >= 9) sort_phase<9, true, LOG2B == 9>(e, t, buf, n);
+  if constexpr (LOG2B >= 10) sort_phase<10, true, LOG2B == 10>(e, t, buf, n);
+  if constexpr (LOG2B >= 11) sort_phase<11, true, LOG2B == 11>(e, t, buf, n);
+  if constexpr (LOG2B >= 12) sort_phase<12, true, true>(e, t, buf, n);
+  // the thread now holds positions 16t .. 16t+15 of the tile, each bucket in descending order
+  const int ts = t & (kSeg - 1);                         // this thread's place among its bucket's threads
   lds_first[t] = e[0];
   __syncthreads();
   float av[17];
 #pragma unroll
   for (int j = 0; j < 16; ++j) av[j] = __uint_as_float(e[j]);
-  av[16] = t < kThreads - 1 ? __uint_as_float(lds_first[t + 1]) : 0.0f;
+  av[16] = ts < kSeg - 1 ? __uint_as_float(lds_first[t + 1]) : 0.0f;
   double run[16];
   run[0] = (double)av[0];
 #pragma unroll
   for (int j = 1; j < 16; ++j) run[j] = run[j - 1] + (double)av[j];
   double incl = run[15];
-  for (int off = 1; off < kWave; off <<= 1) {
+#pragma unroll
+  for (int off = 1; off < kSegLanes; off <<= 1) {
     const double o = __shfl_up(incl, off, kWave);
-    if (lane >= off) incl += o;
+    if ((lane & (kSegLanes - 1)) >= off) incl += o;
   }
-  if (lane == kWave - 1) lds_tot[wave] = incl;
-  __syncthreads();
   double before = incl - run[15];
-  for (int w = 0; w < wave; ++w) before += lds_tot[w];
+  if constexpr (kSegWaves > 1) {
+    if (lane == kWave - 1) lds_tot[wave] = incl;
+    __syncthreads();
+    for (int w = wave & ~(kSegWaves - 1); w < wave; ++w) before += lds_tot[w];
+  }
   // best candidate of this thread (smallest k among equal objectives); k = 0: none
   double best = -1.0;
   int best_k = 0;
   float best_next = 0.0f;
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
-    const int k = 16 * t + j + 1;
+    const int k = 16 * ts + j + 1;
     if (av[j] > 0.0f && av[j] > av[j + 1]) {
       const double r = before + run[j];
       const double obj = r * r / (double)k;
       if (obj > best) { best = obj; best_k = k; best_next = av[j + 1]; }
     }
   }
-  for (int off = 1; off < kWave; off <<= 1) {
+#pragma unroll
+  for (int off = 1; off < kSegLanes; off <<= 1) {
     const double o = __shfl_xor(best, off, kWave);
     const int ok = __shfl_xor(best_k, off, kWave);
     const float on = __shfl_xor(best_next, off, kWave);
     if (o > best || (o == best && ok < best_k)) { best = o; best_k = ok; best_next = on; }
   }
-  if (lane == 0) { lds_obj[wave] = best; lds_k[wave] = best_k; lds_next[wave] = best_next; }
-  __syncthreads();
-  if (t == 0) {
-    for (int w = 1; w < kWaves; ++w) {
-      const double o = lds_obj[w];
-      const int ok = lds_k[w];
-      if (o > best || (o == best && ok < best_k)) { best = o; best_k = ok; best_next = lds_next[w]; }
-    }
-    a.thresholds[(int64_t)m * a.scale_stride + tile] = best_k > 0 ? best_next : 0.0f;
+  if constexpr (kSegWaves > 1) {
+    if (lane == 0) { lds_obj[wave] = best; lds_k[wave] = best_k; lds_next[wave] = best_next; }
+    __syncthreads();
+    if (ts == 0)
+      for (int w = wave + 1; w < wave + kSegWaves; ++w) {
+        const double o = lds_obj[w];
+        const int ok = lds_k[w];
+        if (o > best || (o == best && ok < best_k)) { best = o; best_k = ok; best_next = lds_next[w]; }
+      }
+  }
+  if (ts == 0) {
+    const int64_t k = tile * (kTile >> LOG2B) + (t >> (LOG2B - 4));   // bucket index
+    if (k < a.nb) a.thresholds[(int64_t)m * a.scale_stride + k] = best_k > 0 ? best_next : 0.0f;
   }
 }
 
@@ -785,9 +819,18 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   if (a.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
   const dim3 grid_tiles((unsigned)a.ntiles, (unsigned)L->M);
   if (flags & QA_THRESH_EXACT) {
-    // one ranking per tile: the tile must be the bucket
-    if (!(L->bucket == kTile || (L->bucket == 0 && a.ntiles == 1))) return QA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(exact_threshold_kernel, grid_tiles, block, 0, stream, a);
+    // one ranking network per tile: buckets that fit a tile
+    if (!((L->bucket != 0 && L->bucket <= kTile) || (L->bucket == 0 && a.ntiles == 1)))
+      return QA_ERR_UNSUPPORTED;
+    switch (L->bucket ? ilog2(L->bucket) : 12) {
+      case 6: hipLaunchKernelGGL(exact_threshold_kernel<6>, grid_tiles, block, 0, stream, a); break;
+      case 7: hipLaunchKernelGGL(exact_threshold_kernel<7>, grid_tiles, block, 0, stream, a); break;
+      case 8: hipLaunchKernelGGL(exact_threshold_kernel<8>, grid_tiles, block, 0, stream, a); break;
+      case 9: hipLaunchKernelGGL(exact_threshold_kernel<9>, grid_tiles, block, 0, stream, a); break;
+      case 10: hipLaunchKernelGGL(exact_threshold_kernel<10>, grid_tiles, block, 0, stream, a); break;
+      case 11: hipLaunchKernelGGL(exact_threshold_kernel<11>, grid_tiles, block, 0, stream, a); break;
+      default: hipLaunchKernelGGL(exact_threshold_kernel<12>, grid_tiles, block, 0, stream, a); break;
+    }
     a.thresh_given = 1;                                  // the passes below read what it wrote
   }
 

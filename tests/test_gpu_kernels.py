@@ -375,7 +375,10 @@ def test_stochastic_quantizer_refuses_small_buckets():
 # ---- exact least-squares threshold by ranking (Section 3.4) ------------------------------------
 
 @pytest.mark.parametrize("d,M,bucket", [(4096, 1, 0), (1000, 2, 0), (3, 1, 0), (4096 * 5, 3, 4096),
-                                        (4096 * 7 + 1234, 4, 4096), (4096 * 3 + 1, 2, 4096)])
+                                        (4096 * 7 + 1234, 4, 4096), (4096 * 3 + 1, 2, 4096),
+                                        # buckets smaller than the tile: the network stops early
+                                        (10000, 2, 64), (10000, 2, 128), (9001, 3, 256), (12289, 2, 512),
+                                        (10000, 2, 1024), (4096 * 3 + 77, 3, 2048), (70, 1, 64)])
 @pytest.mark.parametrize("kind", ["gauss", "student", "laplace_sparse"])
 def test_exact_threshold_quantizer_matches_oracle(d, M, bucket, kind):
     g = make_grad(kind, M, d, seed=d % 977 + M)
@@ -388,20 +391,22 @@ def test_exact_threshold_quantizer_matches_oracle(d, M, bucket, kind):
     assert np.array_equal(s[:, :nb].view(np.uint32), s_ref.view(np.uint32))
 
 
-def test_exact_threshold_never_splits_equal_magnitudes_and_handles_zeros():
+@pytest.mark.parametrize("bucket", [4096, 256, 64])
+def test_exact_threshold_never_splits_equal_magnitudes_and_handles_zeros(bucket):
     rng = np.random.default_rng(5)
     d = 4096 * 3
     g = np.zeros((3, d), np.float32)
     g[0] = rng.integers(-3, 4, d)                       # many ties, many zeros, sums exact
     g[1, ::7] = 2.5                                      # all kept magnitudes equal
-    g[2, :4096] = rng.standard_normal(4096)              # two all-zero buckets
-    th_ref = np.stack([oracle.exact_thresholds(g[m], 4096) for m in range(3)])
-    c_ref, s_ref, _ = oracle.quantize_pack(g, 4096, thresholds=th_ref)
-    c, s, th, L = gpu_quantize_pack(g, 4096, exact=True)
+    g[2, :4096] = rng.standard_normal(4096)              # all-zero buckets after the first tile
+    th_ref = np.stack([oracle.exact_thresholds(g[m], bucket) for m in range(3)])
+    c_ref, s_ref, _ = oracle.quantize_pack(g, bucket, thresholds=th_ref)
+    c, s, th, L = gpu_quantize_pack(g, bucket, exact=True)
     assert np.array_equal(th.view(np.uint32), th_ref.view(np.uint32))
     assert np.array_equal(c, c_ref)
     assert np.array_equal(s.view(np.uint32), s_ref.view(np.uint32))
-    assert th[2, 1] == 0 and s[2, 1] == 0 and not c[2, 256:].any()
+    first_empty = 4096 // bucket
+    assert th[2, first_empty] == 0 and s[2, first_empty] == 0 and not c[2, 256:].any()
 
 
 def test_exact_threshold_refuses_other_buckets_and_missing_output():
@@ -409,7 +414,7 @@ def test_exact_threshold_refuses_other_buckets_and_missing_output():
     codes = torch.zeros((1, 512), dtype=torch.int32, device=DEV)
     scales = torch.zeros((1, 128), dtype=torch.float32, device=DEV)
     th = torch.zeros((1, 128), dtype=torch.float32, device=DEV)
-    for bucket in (64, 512, 8192, 0):
+    for bucket in (8192, 0):                            # buckets beyond one tile
         L = qa.Layout.make(8192, 1, bucket)
         ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE))
         with pytest.raises(qa.QaError) as e:
