@@ -448,6 +448,20 @@ def main():
             bpc = algorithmic_bytes_per_coord("qcmd_z", M)
             also["qcmd_z_requant_bucket"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
                                              "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+            # the server's call alone: messages in, q_t = Q(SynQ_t) out as a one-worker message
+            qc = torch.zeros((1, L.code_stride), dtype=torch.int32, device=dev)
+            qs = torch.zeros((1, L.scale_stride), dtype=torch.float32, device=dev)
+            qa.qa_aggregate_quantize(L, codes, scales, rq, qc, qs, None, None)
+            e0.record()
+            for _ in range(3):
+                qa.qa_aggregate_quantize(L, codes, scales, rq, qc, qs, None, None)
+            e1.record()
+            torch.cuda.synchronize()
+            avg = e0.elapsed_time(e1) / 3
+            bpc = M / 4 + 0.25
+            also["aggregate_quantize_bucket"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
+                                                 "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+            del qc, qs
 
     out = {
         "metric": "fused QCMD/QRDA step: coordinates/s and achieved HBM GB/s (% peak), 1 MI355X",

@@ -181,6 +181,21 @@ int qa_step_qcmd(const qa_layout* layout, const uint32_t* codes, const float* sc
                  float* G, float* z_or_null, float eta, float lambda, float delta, int requant,
                  void* ws, size_t ws_bytes, void* stream);
 
+/* The server's part of Algorithm 1 as one call: SynQ_t = (1/M) sum_m Q(g^(m)) followed by
+ * q_t = Q(SynQ_t) (equations SynQ_t and Qt), returned as a one-worker message in the dense 2-bit
+ * encoding: q_codes[w], w < ceil(d/16), and q_scales[k] (q_thresholds[k] if not NULL), with
+ * k < ceil(d/bucket) buckets for QA_REQUANT_BUCKET and k = 0 for QA_REQUANT_GLOBAL (one threshold
+ * and scale for the whole vector).  The result equals qa_aggregate_unpack followed by
+ * qa_quantize_pack of that vector with M = 1 and the corresponding bucket; buckets of at most 4096
+ * components (and vectors of at most 4096 with one scale) are done in a single pass that never
+ * writes the average.  requant must be QA_REQUANT_BUCKET or QA_REQUANT_GLOBAL.
+ * ws: qa_workspace_bytes(layout, QA_OP_STEP) (may be NULL when the single pass applies).
+ * Stepping from the message (layout with M = 1, that bucket) gives the same state as the fused
+ * step with the same requant. */
+int qa_aggregate_quantize(const qa_layout* layout, const uint32_t* codes, const float* scales,
+                          int requant, uint32_t* q_codes, float* q_scales, float* q_thresholds,
+                          void* ws, size_t ws_bytes, void* stream);
+
 /* One fused QRDA adagrad step (equations SynQ_t, Qt, Hq and QRDA).  Per coordinate:
  *     G = G + q*q ;  H = delta + sqrt(G) ;  z = z + q
  *     r = |z| - (float)t*lambda
@@ -261,6 +276,15 @@ int qa_step_qrda_selected(const qa_layout* layout, const uint32_t* ind, int64_t 
                           const uint32_t* sel_codes, const float* scales, float* x, float* G,
                           float* z, int64_t t, float eta, float lambda, float delta, int requant,
                           void* ws, size_t ws_bytes, void* stream);
+
+/* qa_aggregate_quantize on sparse-encoded messages (Algorithm 1, server: "Decode", "Average",
+ * "Quantize the aggregated gradient" in one call); ind / ind_stride / sel_codes as for
+ * qa_decode_selected.  qa_select_codes with the synchronous indicator then turns q_codes into
+ * the message S(q_t, I^Syn) that is pushed to the workers. */
+int qa_aggregate_quantize_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                                   const uint32_t* sel_codes, const float* scales, int requant,
+                                   uint32_t* q_codes, float* q_scales, float* q_thresholds, void* ws,
+                                   size_t ws_bytes, void* stream);
 
 /* ---- a list of parameter tensors in one flat vector --------------------------------------------
  *

@@ -270,6 +270,23 @@ def qa_step_qrda_selected(layout, ind, ind_stride, sel_codes, scales, x, G, z, t
                                       _nbytes(ws), _stream(stream)), "qa_step_qrda_selected")
 
 
+def qa_aggregate_quantize(layout, codes, scales, requant, q_codes, q_scales, q_thresholds, ws, stream=None):
+    _lib.qa_aggregate_quantize.argtypes = [C.POINTER(Layout), _vp, _vp, C.c_int, _vp, _vp, _vp, _vp, _sz, _vp]
+    _check(_lib.qa_aggregate_quantize(C.byref(layout), _p(codes), _p(scales), requant, _p(q_codes),
+                                      _p(q_scales), _p(q_thresholds), _p(ws), _nbytes(ws),
+                                      _stream(stream)), "qa_aggregate_quantize")
+
+
+def qa_aggregate_quantize_selected(layout, ind, ind_stride, sel_codes, scales, requant, q_codes, q_scales,
+                                   q_thresholds, ws, stream=None):
+    _lib.qa_aggregate_quantize_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, C.c_int,
+                                                    _vp, _vp, _vp, _vp, _sz, _vp]
+    _check(_lib.qa_aggregate_quantize_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes),
+                                               _p(scales), requant, _p(q_codes), _p(q_scales),
+                                               _p(q_thresholds), _p(ws), _nbytes(ws), _stream(stream)),
+           "qa_aggregate_quantize_selected")
+
+
 def qa_segment_plan_host(d, begin, length):
     """Host-only validation and table of a tensor list -> (n_pieces, table as a list of int64)."""
     n = len(begin)

@@ -33,6 +33,10 @@ struct StepArgs {
   // worker m's indicator words start at ind + m*ind_stride (stride 0: one indicator for all)
   const uint32_t* ind;
   int64_t ind_stride;
+  // aggregate mode with the second quantization: q_t leaves as a one-worker message instead of gbar
+  uint32_t* q_codes;
+  float* q_scales;
+  float* q_thresholds;   // optional
 };
 
 // 10 -> 00 so that the reserved pattern reads as zero; 01 and 11 are unchanged.
@@ -461,6 +465,21 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     s2 = segment_sum(s2, seg, lds_d);
     cnt = segment_sum_u32(cnt, seg, lds_u);
     const float s = scale_from_sum(s2, cnt);
+    if (MODE == kAggregate) {
+      // the server's output: q_t = Q(SynQ_t) as a message (the thread's 16 coordinates are
+      // code word t of the tile), one scale per bucket written by the bucket's first thread
+      uint32_t word = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) word |= ternary_field(q[j], Delta) << (2 * j);
+      if ((int64_t)t < words_here) a.q_codes[tile * kTileWords + t] = word;
+      const bool leader = own_scales ? (t & (seg - 1)) == 0 : t == 0;
+      if (leader && n > 0) {
+        const int64_t kq = own_scales ? ((tile_base + 16 * (int64_t)t) >> a.log2b) : k;
+        a.q_scales[kq] = s;
+        if (a.q_thresholds) a.q_thresholds[kq] = Delta;
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
   }
@@ -685,6 +704,52 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
   return launch_status();
 }
 
+// The server's part of Algorithm 1 as one call: messages in, q_t = Q(SynQ_t) out as a one-worker
+// message.  One pass when the second quantization fits a tile; otherwise the average goes to the
+// workspace (with the quantizer's tile sums) and the quantizer finishes.
+static int aggregate_quantize_common(const qa_layout* L, const uint32_t* codes, const float* scales,
+                                     int requant, uint32_t* q_codes, float* q_scales,
+                                     float* q_thresholds, void* ws, size_t ws_bytes,
+                                     hipStream_t stream, bool sparse, const uint32_t* ind,
+                                     int64_t ind_stride) {
+  int rc = check_layout(L);
+  if (rc != QA_OK) return rc;
+  if (!codes || !scales || !q_codes || !q_scales) return QA_ERR_INVALID_ARG;
+  if (requant != QA_REQUANT_BUCKET && requant != QA_REQUANT_GLOBAL) return QA_ERR_INVALID_ARG;
+  if (requant == QA_REQUANT_BUCKET && L->bucket == 0) return QA_ERR_INVALID_ARG;
+  if (sparse) {
+    if (!ind) return QA_ERR_INVALID_ARG;
+    if (ind_stride != 0 && ind_stride < (L->d + 31) / 32) return QA_ERR_INVALID_ARG;
+    if (!aligned(ind, 4)) return QA_ERR_ALIGNMENT;
+    if (!(L->bucket == kTile || (L->bucket == 0 && L->d <= kTile))) return QA_ERR_UNSUPPORTED;
+  }
+  if (!aligned(codes, 4) || !aligned(scales, 4) || !aligned(q_codes, 4) || !aligned(q_scales, 4) ||
+      !aligned(q_thresholds, 4))
+    return QA_ERR_ALIGNMENT;
+  if (tiles_of(L->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+
+  StepArgs ag = make_args(L, codes, scales);
+  if (sparse) { ag.ind = ind; ag.ind_stride = ind_stride; }
+  if (requant_in_tile(L, requant)) {
+    ag.q_codes = q_codes; ag.q_scales = q_scales; ag.q_thresholds = q_thresholds;
+    launch_mode<kAggregate>(ag, false, true, stream);
+    return launch_status();
+  }
+  qa_layout R = requant_layout(L, requant);
+  const size_t qws = quantize_workspace_bytes(&R);
+  if (!ws || ws_bytes < align256((size_t)L->d * sizeof(float)) + qws) return QA_ERR_WORKSPACE;
+  if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+  char* p = static_cast<char*>(ws);
+  float* gbar = reinterpret_cast<float*>(p);            p += align256((size_t)L->d * sizeof(float));
+  ag.gbar = gbar;
+  const bool fuse_abs = qws != 0;
+  if (fuse_abs) ag.abs_partials = reinterpret_cast<double*>(p);
+  launch_mode<kAggregate>(ag, false, false, stream);
+  const int64_t gs = (L->d + 3) & ~int64_t(3);
+  return quantize_launch(&R, gbar, gs, q_codes, q_scales, q_thresholds,
+                         fuse_abs ? kQuantAbsPartialsGiven : 0u, qws ? p : nullptr, qws, stream);
+}
+
 // Tensor-list steps: the table-driven kernel with one work-group per piece.  The second
 // quantization runs as separate passes: average -> workspace, quantize it per tensor as a
 // one-worker message, update from that message.
@@ -819,4 +884,23 @@ extern "C" int qa_step_qrda_selected(const qa_layout* layout, const uint32_t* in
   return qa::step_common(qa::kQrda, layout, sel_codes, scales, x, G, z, false, t, eta, lambda, delta,
                          requant, ws, ws_bytes, static_cast<hipStream_t>(stream), true, ind,
                          ind_stride);
+}
+
+extern "C" int qa_aggregate_quantize(const qa_layout* layout, const uint32_t* codes,
+                                     const float* scales, int requant, uint32_t* q_codes,
+                                     float* q_scales, float* q_thresholds, void* ws, size_t ws_bytes,
+                                     void* stream) {
+  return qa::aggregate_quantize_common(layout, codes, scales, requant, q_codes, q_scales,
+                                       q_thresholds, ws, ws_bytes, static_cast<hipStream_t>(stream),
+                                       false, nullptr, 0);
+}
+
+extern "C" int qa_aggregate_quantize_selected(const qa_layout* layout, const uint32_t* ind,
+                                              int64_t ind_stride, const uint32_t* sel_codes,
+                                              const float* scales, int requant, uint32_t* q_codes,
+                                              float* q_scales, float* q_thresholds, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  return qa::aggregate_quantize_common(layout, sel_codes, scales, requant, q_codes, q_scales,
+                                       q_thresholds, ws, ws_bytes, static_cast<hipStream_t>(stream),
+                                       true, ind, ind_stride);
 }

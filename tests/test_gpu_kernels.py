@@ -372,6 +372,66 @@ def test_stochastic_quantizer_refuses_small_buckets():
     assert e.value.code == -5
 
 
+# ---- the server's call: messages in, q_t = Q(SynQ_t) out as a message ---------------------------
+
+AGGQ_CASES = [
+    # d, M, bucket, requant (1 = per bucket, 2 = one scale for the vector)
+    (1, 1, 0, 2), (1000, 4, 0, 2), (4096, 8, 4096, 1), (4097, 8, 4096, 1), (70001, 16, 4096, 1),
+    (70001, 20, 4096, 2), (10000, 3, 64, 1), (10000, 5, 256, 1), (70001, 6, 2048, 1),
+    (70001, 4, 16384, 1), (70001, 4, 0, 2), (9000, 48, 4096, 1), (4100, 8, 512, 2),
+]
+
+
+@pytest.mark.parametrize("d,M,bucket,requant", AGGQ_CASES)
+def test_aggregate_quantize_matches_oracle_and_the_fused_step(d, M, bucket, requant):
+    g = make_grad("gauss", M, d, seed=31 * d + M)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
+    L = qa.Layout.make(d, M, bucket)
+    bq = bucket if requant == 1 else 0
+    L1 = qa.Layout.make(d, 1, bq)
+    # oracle: the average, then the quantizer on it as a one-worker message
+    gbar = oracle.aggregate(oc, osc, d, bucket)
+    qc_ref, qs_ref, qt_ref = oracle.quantize_pack(gbar[None, :], bucket=bq)
+    codes, scales = dev(oc.view(np.int32)), dev(osc)
+    qc = torch.full((1, L1.code_stride), -1, dtype=torch.int32, device=DEV)
+    qs = torch.full((1, L1.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+    qt = torch.full((1, L1.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
+    qa.qa_aggregate_quantize(L, codes, scales, requant, qc, qs, qt, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(qc).view(np.uint32)[:, :L1.words], qc_ref)
+    assert np.array_equal(host(qs)[:, :L1.n_buckets].view(np.uint32), qs_ref.view(np.uint32))
+    assert np.array_equal(host(qt)[:, :L1.n_buckets].view(np.uint32), qt_ref.view(np.uint32))
+    # stepping from the message == the fused step with the same second quantization
+    rng = np.random.default_rng(d)
+    x0 = (rng.standard_normal(d) * 1e-2 * (rng.random(d) < 0.5)).astype(np.float32)
+    G0 = (rng.random(d) * 1e-4).astype(np.float32)
+    z0 = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+    xa, Ga, za = dev(x0), dev(G0), dev(z0)
+    xb, Gb, zb = dev(x0), dev(G0), dev(z0)
+    qa.qa_step_qrda(L, codes, scales, xa, Ga, za, 3, 0.1, 2e-4, 1e-8, requant, ws)
+    qa.qa_step_qrda(L1, qc, qs, xb, Gb, zb, 3, 0.1, 2e-4, 1e-8, qa.QA_REQUANT_NONE, None)
+    torch.cuda.synchronize()
+    for u, v in ((xa, xb), (Ga, Gb), (za, zb)):
+        assert np.array_equal(host(u).view(np.uint32), host(v).view(np.uint32))
+
+
+def test_aggregate_quantize_checks_its_arguments():
+    L = qa.Layout.make(100000, 2, 4096)
+    t = torch.zeros(8, dtype=torch.int32, device=DEV)
+    f = torch.zeros(8, dtype=torch.float32, device=DEV)
+    with pytest.raises(qa.QaError) as e:                 # NONE is not a quantization
+        qa.qa_aggregate_quantize(L, t, f, qa.QA_REQUANT_NONE, t, f, None, None)
+    assert e.value.code == -1
+    with pytest.raises(qa.QaError) as e:                 # one scale for 100000 components needs the workspace
+        qa.qa_aggregate_quantize(L, t, f, qa.QA_REQUANT_GLOBAL, t, f, None, None)
+    assert e.value.code == -3
+    L0 = qa.Layout.make(100000, 2, 0)
+    with pytest.raises(qa.QaError) as e:                 # per-bucket needs buckets
+        qa.qa_aggregate_quantize(L0, t, f, qa.QA_REQUANT_BUCKET, t, f, None, None)
+    assert e.value.code == -1
+
+
 # ---- exact least-squares threshold by ranking (Section 3.4) ------------------------------------
 
 @pytest.mark.parametrize("d,M,bucket", [(4096, 1, 0), (1000, 2, 0), (3, 1, 0), (4096 * 5, 3, 4096),

@@ -303,6 +303,59 @@ def test_steps_on_sparse_messages_match_oracle_decode_then_step(d, M, bucket, p,
     assert p == 0.0 or wide or np.count_nonzero(ox) > 0
 
 
+@pytest.mark.parametrize("d,M,bucket,p,requant,shared", [
+    (1000, 3, 0, 0.3, 2, False), (4097, 5, 4096, 0.05, 1, False), (70001, 16, 4096, 0.3, 1, False),
+    (70001, 3, 4096, 0.2, 2, False), (70001, 4, 4096, 0.2, 1, True), (20000, 2, 4096, 0.0, 1, False)])
+def test_server_call_on_sparse_messages_matches_oracle(d, M, bucket, p, requant, shared):
+    """qa_aggregate_quantize_selected == oracle decode, average, quantizer on the average; then
+    qa_select_codes with the synchronous indicator gives the pushed message."""
+    rng = np.random.default_rng(d + M)
+    L = qa.Layout.make(d, M, bucket)
+    nb, W, NW = L.n_buckets, L.words, (d + 31) // 32
+    g = (rng.standard_normal((M, d)) * rng.choice([1e-3, 0.02], (M, d))).astype(np.float32)
+    ind = random_indicator(rng, 1 if shared else M, d, p)
+    sel = np.full((M, L.code_stride), 0x5A5A5A5A, np.uint32)
+    sc = np.zeros((M, nb), np.float32)
+    dense = np.zeros((M, W), np.uint32)
+    for m in range(M):
+        im = ind[0 if shared else m]
+        o_sel, o_cnt, o_sc, _ = oracle.quantize_selected(g[m], im, bucket=bucket)
+        for k in range(nb):
+            nwk = (int(o_cnt[k]) + 15) // 16
+            lo = k * (256 if bucket else (d + 15) // 16)
+            sel[m, k * 256: k * 256 + nwk] = o_sel[lo: lo + nwk]
+        sc[m] = o_sc
+        dense[m] = oracle.decode_selected(im, o_sel, d, bucket=bucket)
+    bq = bucket if requant == 1 else 0
+    gbar = oracle.aggregate(dense, sc, d, bucket)
+    qc_ref, qs_ref, _ = oracle.quantize_pack(gbar[None, :], bucket=bq)
+    L1 = qa.Layout.make(d, 1, bq)
+    qc = torch.full((1, L1.code_stride), -1, dtype=torch.int32, device=DEV)
+    qs = torch.full((1, L1.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
+    ind_d = dev(ind.view(np.int32))
+    qa.qa_aggregate_quantize_selected(L, ind_d, 0 if shared else NW, dev(sel.view(np.int32)), dev(sc),
+                                      requant, qc, qs, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(qc).view(np.uint32)[:, :W], qc_ref)
+    assert np.array_equal(host(qs)[:, :L1.n_buckets].view(np.uint32), qs_ref.view(np.uint32))
+    if bq == bucket:                                     # the pushed message S(q_t, I_syn)
+        syn = torch.zeros(NW, dtype=torch.int32, device=DEV)
+        ind_all = ind_d if not shared else ind_d.repeat(M, 1)
+        qa.qa_indicator_or(L, ind_all, NW, syn)
+        L1s = qa.Layout.make(d, 1, bucket)
+        push = torch.zeros((1, L1s.code_stride), dtype=torch.int32, device=DEV)
+        cnt = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
+        qa.qa_select_codes(L1s, qc, syn, 0, push, cnt)
+        torch.cuda.synchronize()
+        o_push, o_cnt = oracle.select_codes(qc_ref[0], oracle.indicator_or(ind if not shared else np.repeat(ind, M, 0), d), d, bucket)
+        assert np.array_equal(host(cnt).view(np.uint32)[0], o_cnt)
+        area = 256 if bucket else (d + 15) // 16
+        for k in range(nb):
+            nwk = (int(o_cnt[k]) + 15) // 16
+            assert np.array_equal(host(push).view(np.uint32)[0, k * 256: k * 256 + nwk], o_push[k * area: k * area + nwk])
+
+
 def test_sparse_steps_check_their_arguments():
     L = qa.Layout.make(100000, 2, 1024)
     t = torch.zeros(8, dtype=torch.int32, device=DEV)
