@@ -11,6 +11,12 @@
  *              q = SynQ, or q = Q(SynQ) (second quantization)             } fused into
  *   workers  : G += q^2, H = delta + sqrt(G), QCMD or QRDA update of x    } qa_step_qcmd / qa_step_qrda
  *
+ * The same roles as separate calls, for a deployment in which server and workers are different
+ * processes: qa_aggregate_quantize (server: messages in, q_t out as a message) and a step with
+ * M = 1 on that message (worker).  With the indicator of Section 3.2 only the selected components
+ * travel: qa_indicator, qa_quantize_pack_selected (worker), qa_indicator_or,
+ * qa_aggregate_quantize_selected, qa_select_codes (server), qa_step_*_selected (worker).
+ *
  * Conventions common to every call
  *   - Every data pointer is a DEVICE pointer owned by the caller; the library never
  *     allocates, frees or keeps device memory, and keeps no state between calls
