@@ -230,6 +230,58 @@ def test_pull_direction_through_the_sparse_message_equals_the_fused_step(method)
     assert np.count_nonzero(host(xa)) > 0
 
 
+@pytest.mark.parametrize("method", ["qcmd", "qrda"])
+def test_server_and_worker_roles_as_separate_calls_equal_the_fused_step(method):
+    """Algorithm 1 with only sparse messages between the roles: workers send (I_m, Q(S(g, I_m))),
+    the server answers with (I_syn, S(q_t, I_syn)) from qa_aggregate_quantize_selected +
+    qa_select_codes, a worker updates with qa_step_*_selected on that one message.  Must equal the
+    fused step with the per-bucket second quantization on the decoded codes, bit for bit."""
+    rng = np.random.default_rng(17)
+    d, M, b = 50001, 5, 4096
+    eta, lam, delta, t = 0.1, 1e-3, 1e-8, 4
+    L, L1 = qa.Layout.make(d, M, b), qa.Layout.make(d, 1, b)
+    nb, NW, gs = L.n_buckets, (d + 31) // 32, ((d + 3) // 4) * 4
+    x0, G0, z0 = rand_state(rng, d, nz=0.05)
+    g = np.zeros((M, gs), np.float32)
+    g[:, :d] = rng.standard_normal((M, d)) * rng.choice([1e-4, 0.05], (M, d), p=[0.9, 0.1])
+    gd, xd, Gd, zd = dev(g), dev(x0), dev(G0), dev(z0)
+    mth = 0 if method == "qcmd" else 1
+    # workers
+    ind = torch.zeros((M, NW), dtype=torch.int32, device=DEV)
+    sel = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((M, nb), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((M, nb), dtype=torch.float32, device=DEV)
+    qa.qa_indicator(L, mth, gd, gs, xd, Gd, zd, t, eta, lam, delta, ind, NW)
+    qa.qa_quantize_pack_selected(L, gd, gs, ind, NW, sel, cnt, sc, None)
+    # server
+    syn = torch.zeros(NW, dtype=torch.int32, device=DEV)
+    qc = torch.zeros((1, L1.code_stride), dtype=torch.int32, device=DEV)
+    qs = torch.zeros((1, nb), dtype=torch.float32, device=DEV)
+    push = torch.zeros((1, L1.code_stride), dtype=torch.int32, device=DEV)
+    push_cnt = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
+    qa.qa_indicator_or(L, ind, NW, syn)
+    qa.qa_aggregate_quantize_selected(L, ind, NW, sel, sc, qa.QA_REQUANT_BUCKET, qc, qs, None, None)
+    qa.qa_select_codes(L1, qc, syn, 0, push, push_cnt)
+    # a worker
+    xb, Gb, zb = xd.clone(), Gd.clone(), zd.clone()
+    if method == "qcmd":
+        qa.qa_step_qcmd_selected(L1, syn, 0, push, qs, xb, Gb, zb, eta, lam, delta, 0, None)
+    else:
+        qa.qa_step_qrda_selected(L1, syn, 0, push, qs, xb, Gb, zb, t, eta, lam, delta, 0, None)
+    # everything in one place: decode, fused step with the second quantization
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    qa.qa_decode_selected(L, ind, NW, sel, codes)
+    xa, Ga, za = xd.clone(), Gd.clone(), zd.clone()
+    if method == "qcmd":
+        qa.qa_step_qcmd(L, codes, sc, xa, Ga, za, eta, lam, delta, qa.QA_REQUANT_BUCKET, None)
+    else:
+        qa.qa_step_qrda(L, codes, sc, xa, Ga, za, t, eta, lam, delta, qa.QA_REQUANT_BUCKET, None)
+    torch.cuda.synchronize()
+    for u, v in ((xa, xb), (Ga, Gb), (za, zb)):
+        assert np.array_equal(host(u).view(np.uint32), host(v).view(np.uint32))
+    assert 0 < int(host(push_cnt).sum()) < d and np.count_nonzero(host(xa)) > 0
+
+
 def test_unsupported_bucket_sizes_are_refused():
     L = qa.Layout.make(100000, 2, 1024)
     t = torch.zeros(8, dtype=torch.int32, device=DEV)
