@@ -307,15 +307,19 @@ def test_local_grad_csr_matches_oracle():
     assert (gg == og).mean() > 0.999
 
 
-@pytest.mark.parametrize("csr", [False, True])
-def test_local_grad_batched_equals_per_worker_calls_and_oracle(csr):
+@pytest.mark.parametrize("csr,shape", [(False, (400, 3000, 30, 48, 5)), (True, (400, 3000, 30, 48, 5)),
+                                       # large batches, heavy collisions on a few columns, a ragged last row group
+                                       (True, (600, 5000, 30, 301, 7)), (True, (600, 1500, 20, 256, 8))])
+def test_local_grad_batched_equals_per_worker_calls_and_oracle(csr, shape):
     rng = np.random.default_rng(8)
-    n, d, k, B, M = 400, 3000, 30, 48, 5
+    n, d, k, B, M = shape
     y = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
     x = (rng.standard_normal(d) * 0.1).astype(np.float32)
     rows = rng.integers(0, n, (M, B)).astype(np.int32)
     if csr:
         vals, indptr, idx = _random_csr(rng, n, d, k)
+        if B > 100:
+            idx = np.where(rng.random(idx.size) < 0.6, idx % 37, idx).astype(np.int32)   # hot columns
         A_d, ip_d, ix_d = dev(vals), dev(indptr), dev(idx)
         ref = [oracle.local_grad_csr(vals, indptr, idx, d, y, rows[m], x) for m in range(M)]
         fmt, op = qa.QA_CSR, qa.QA_OP_GRAD_CSR
