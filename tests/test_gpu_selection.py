@@ -24,7 +24,7 @@ def rand_state(rng, d, nz=0.3):
 
 
 @pytest.mark.parametrize("method", [0, 1])
-@pytest.mark.parametrize("d,M", [(1, 1), (33, 2), (1000, 3), (4096, 2), (70001, 4)])
+@pytest.mark.parametrize("d,M", [(1, 1), (33, 2), (1000, 3), (4096, 2), (70001, 4), (70004, 3)])
 def test_indicator_matches_oracle(method, d, M):
     rng = np.random.default_rng(d + M + method)
     x, G, z = rand_state(rng, d)
