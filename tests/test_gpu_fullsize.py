@@ -88,6 +88,18 @@ def test_sampled_buckets_at_full_size(name):
         assert nonzero_codes > 0
     # a property that holds at any size: coordinates never touched by any worker keep G == 0
     assert float(G.min().item()) >= 0.0
+    # the server's call on the last step's messages, same sampled buckets
+    qc = torch.zeros((1, L.code_stride), dtype=torch.int32, device=DEV)
+    qs = torch.zeros((1, L.scale_stride), dtype=torch.float32, device=DEV)
+    qa.qa_aggregate_quantize(L, codes, scales, qa.QA_REQUANT_BUCKET, qc, qs, None, None)
+    torch.cuda.synchronize()
+    for j, (k, n) in enumerate(zip(sample, lens)):
+        lo, hi = int(offs[j]), int(offs[j + 1])
+        oc, osc, _ = oracle.quantize_pack(g_s[:, lo:hi], bucket=b)
+        qc_ref, qs_ref, _ = oracle.quantize_pack(oracle.aggregate(oc, osc, n, b)[None, :], bucket=b)
+        w0, w1 = k * (b // 16), k * (b // 16) + (n + 15) // 16
+        assert np.array_equal(host(qc[0, w0:w1]).view(np.uint32), qc_ref[0]), f"q_t codes, bucket {k}"
+        assert host(qs[0, k]) == qs_ref[0, 0], f"q_t scale, bucket {k}"
 
 
 def test_sparse_encoding_beyond_2_32_coordinates():
