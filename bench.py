@@ -435,6 +435,19 @@ def main():
         bpc = algorithmic_bytes_per_coord("qcmd", M)
         also["qcmd"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
                         "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+        # row a4 alone: the average written out as fp32 (M/4 B of codes in, 4 B out per coordinate)
+        gbar = torch.empty(d, dtype=torch.float32, device=dev)
+        qa.qa_aggregate_unpack(L, codes, scales, gbar)
+        e0.record()
+        for _ in range(3):
+            qa.qa_aggregate_unpack(L, codes, scales, gbar)
+        e1.record()
+        torch.cuda.synchronize()
+        avg = e0.elapsed_time(e1) / 3
+        bpc = M / 4 + 4
+        also["aggregate_unpack"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
+                                    "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+        del gbar          # stays in torch's cache (see the note on the gradient buffer above)
         # the paper's double quantization at bucket granularity, formed inside the same kernel
         if 0 < bucket <= 4096:
             rq = qa.QA_REQUANT_BUCKET
