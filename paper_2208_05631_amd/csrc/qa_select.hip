@@ -9,6 +9,8 @@
 //                               the per-thread popcounts, LDS bit stream).
 //   decode_selected_kernel    : S^{-1}: spreads the compact codes back to the dense 2-bit layout
 //                               that the fused steps read.
+//   select_codes_kernel       : S applied to a coded message (the server's push): the inverse.
+// (The steps that read sparse messages directly live with the step kernel.)
 #include "qa_common.h"
 #include "qa_sparse.h"
 

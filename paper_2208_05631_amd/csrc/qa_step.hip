@@ -7,6 +7,8 @@
 // Per coordinate the kernel forms  acc = sum_m s_m * c_m  in binary64 (each product is exact),
 // gbar = (float)(acc / M), optionally re-quantizes gbar per bucket inside the tile, and applies
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
+// The same kernel also takes its code words from sparse-encoded messages (expanded on the fly)
+// and, in aggregate mode with the second quantization, emits q_t as a coded message.
 #include "qa_segments.h"
 #include "qa_sparse.h"
 
