@@ -1,8 +1,9 @@
 """Seeded random shapes through the C ABI against the oracle: quantize+pack, the three fused steps
 with every second-quantization mode, the server's call, and (where the sparse encoding applies)
-the selected quantizer and the step on sparse messages.  Everything is compared bit for bit; the
-shapes mix tiny, ragged and multi-tile vectors, worker counts on both sides of the chunk sizes,
-every bucket size, ties, sparse, and scales spread over 80 binades."""
+the selected quantizer and the step on sparse messages; in a second test tensor lists, the exact
+and the stochastic quantizer, the indicator and code selection.  Everything is compared bit for
+bit; the shapes mix tiny, ragged and multi-tile vectors, worker counts on both sides of the chunk
+sizes, every bucket size, ties, sparse, and scales spread over 80 binades."""
 import numpy as np
 import pytest
 import torch
@@ -133,3 +134,123 @@ def test_random_shapes_match_oracle_bit_for_bit(seed):
                                      dev(sc), xd, Gd, zd, t, eta, lam, delta, requant, ws)
             torch.cuda.synchronize()
             assert same_bits(host(xd), ox) and same_bits(host(Gd), oG) and same_bits(host(zd), oz), (what, "sparse")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_shapes_of_the_other_calls_match_oracle_bit_for_bit(seed):
+    rng = np.random.default_rng(2000 + seed)
+    for case in range(40):
+        M = int(rng.choice([1, 2, 3, 5, 8, 13, 16]))
+        # ---- a list of tensors in one flat vector ----
+        nseg = int(rng.integers(1, 30))
+        lengths = [int(rng.choice([0, rng.integers(1, 20), rng.integers(20, 600), rng.integers(600, 9000)]))
+                   for _ in range(nseg)]
+        begin, pos = [], int(rng.integers(0, 3)) * 16
+        for n in lengths:
+            begin.append(pos)
+            pos = (pos + n + 15) // 16 * 16 + 16 * int(rng.integers(0, 3))
+        d = pos + int(rng.integers(1, 40))
+        begin, length = np.array(begin, np.int64), np.array(lengths, np.int64)
+        what = f"seed {seed} case {case}: tensors {lengths} d={d} M={M}"
+        L = qa.Layout.make(d, M, 0, 0.75, None, nseg)
+        table = torch.zeros(qa.qa_segment_plan_bytes(d, nseg), dtype=torch.uint8, device=DEV)
+        plan = qa.qa_segment_plan_init(d, begin, length, table)
+        g = (rng.standard_normal((M, d)) * 10.0 ** rng.integers(-4, 1) * (rng.random((M, d)) < 0.7)).astype(np.float32)
+        gs = (d + 3) // 4 * 4
+        gp = np.zeros((M, gs), np.float32)
+        gp[:, :d] = g
+        c_ref, s_ref, th_ref = oracle.quantize_pack_segments(g, begin, length)
+        codes = torch.full((M, L.code_stride), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+        scales = torch.full((M, nseg), -7.0, dtype=torch.float32, device=DEV)
+        th = torch.full((M, nseg), -7.0, dtype=torch.float32, device=DEV)
+        qa.qa_quantize_pack_segments(L, plan, dev(gp), gs, codes, scales, th,
+                                     workspace(qa.qa_segment_workspace_bytes(plan, M, qa.QA_OP_QUANTIZE)))
+        torch.cuda.synchronize()
+        touched = np.zeros(L.words, bool)
+        for b_, n_ in zip(begin, length):
+            touched[b_ // 16:(b_ + n_ + 15) // 16] = True
+        c = host(codes).view(np.uint32)
+        assert np.array_equal(c[:, touched], c_ref[:, touched]) and (c[:, ~touched] == 0x5A5A5A5A).all(), what
+        assert same_bits(host(scales), s_ref) and same_bits(host(th), th_ref), what
+        x0 = (rng.standard_normal(d) * 0.05).astype(np.float32)
+        G0 = (rng.random(d) * 1e-3).astype(np.float32)
+        z0 = (rng.standard_normal(d) * 0.01).astype(np.float32)
+        requant = bool(rng.random() < 0.5)
+        rq = qa.QA_REQUANT_BUCKET if requant else qa.QA_REQUANT_NONE
+        ws = workspace(qa.qa_segment_workspace_bytes(plan, M, qa.QA_OP_STEP))
+        for method in ("qcmd", "qrda"):
+            xr, Gr, zr = x0.copy(), G0.copy(), z0.copy()
+            xd, Gd, zd = dev(x0), dev(G0), dev(z0)
+            if method == "qrda":
+                oracle.step_segments(oracle.QRDA, c_ref, s_ref, d, begin, length, xr, Gr, zr, 3, 0.1, 1e-3, 1e-8, requant)
+                qa.qa_step_qrda_segments(L, plan, codes, scales, xd, Gd, zd, 3, 0.1, 1e-3, 1e-8, rq, ws)
+            else:
+                oracle.step_segments(oracle.QCMD, c_ref, s_ref, d, begin, length, xr, Gr, zr, 3, 0.1, 1e-3, 1e-8, requant)
+                qa.qa_step_qcmd_segments(L, plan, codes, scales, xd, Gd, zd, 0.1, 1e-3, 1e-8, rq, ws)
+            torch.cuda.synchronize()
+            assert same_bits(host(xd), xr) and same_bits(host(Gd), Gr) and same_bits(host(zd), zr), (what, method, requant)
+        # ---- exact ranking threshold, stochastic quantizer ----
+        d2 = int(rng.choice([rng.integers(1, 300), rng.integers(300, 30000)]))
+        bucket = int(rng.choice([64, 128, 256, 512, 1024, 2048, 4096] + ([0] if d2 <= 4096 else [])))
+        kind = str(rng.choice(["gauss", "sparse", "ties"]))
+        g2 = random_gradients(rng, kind, M, d2)
+        what = f"seed {seed} case {case}: d={d2} M={M} bucket={bucket} {kind}"
+        L2 = qa.Layout.make(d2, M, bucket)
+        gs2 = (d2 + 3) // 4 * 4
+        gp2 = np.zeros((M, gs2), np.float32)
+        gp2[:, :d2] = g2
+        th_ref = np.stack([oracle.exact_thresholds(g2[m], bucket) for m in range(M)])
+        c_ref, s_ref, _ = oracle.quantize_pack(g2, bucket, thresholds=th_ref)
+        codes = torch.full((M, L2.code_stride), -1, dtype=torch.int32, device=DEV)
+        scales = torch.full((M, L2.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+        th = torch.full((M, L2.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+        qa.qa_quantize_pack(L2, dev(gp2), gs2, codes, scales, th, qa.QA_THRESH_EXACT, None)
+        torch.cuda.synchronize()
+        assert same_bits(host(th)[:, :L2.n_buckets], th_ref), (what, "exact threshold")
+        assert np.array_equal(host(codes).view(np.uint32)[:, :L2.words], c_ref), (what, "exact codes")
+        assert same_bits(host(scales)[:, :L2.n_buckets], s_ref), (what, "exact scales")
+        rseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 1000))
+        bs = int(rng.choice([0, 4096, 8192]))
+        Ls = qa.Layout.make(d2, M, bs)
+        oc, osc = oracle.quantize_pack_stochastic(g2, bucket=bs, seed=rseed, step=step)
+        codes = torch.full((M, Ls.code_stride), -1, dtype=torch.int32, device=DEV)
+        scales = torch.full((M, Ls.scale_stride), -7.0, dtype=torch.float32, device=DEV)
+        qa.qa_quantize_pack_stochastic(Ls, dev(gp2), gs2, codes, scales, rseed, step)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(codes).view(np.uint32)[:, :Ls.words], oc), (what, "stochastic", bs)
+        assert same_bits(host(scales)[:, :Ls.n_buckets], osc), (what, "stochastic", bs)
+        # ---- indicator, code selection, decode ----
+        d3 = int(rng.choice([rng.integers(1, 5000), rng.integers(5000, 40000)]))
+        b3 = 4096 if d3 > 4096 else int(rng.choice([0, 4096]))
+        method, lam, t = int(rng.integers(0, 2)), float(rng.choice([0.0, 1e-3, 0.05])), int(rng.integers(1, 9))
+        x3 = (rng.standard_normal(d3) * 0.1 * (rng.random(d3) < 0.3)).astype(np.float32)
+        G3 = (rng.random(d3) * 10.0 ** rng.integers(-6, 1)).astype(np.float32)
+        z3 = (rng.standard_normal(d3) * 0.05).astype(np.float32)
+        g3 = (rng.standard_normal((M, d3)) * rng.choice([1e-3, 0.05], (M, d3))).astype(np.float32)
+        what = f"seed {seed} case {case}: indicator d={d3} M={M} method={method} lam={lam} t={t}"
+        L3, NW = qa.Layout.make(d3, M, b3), (d3 + 31) // 32
+        stride = d3 + int(rng.integers(0, 5))
+        gp3 = np.zeros((M, stride), np.float32)
+        gp3[:, :d3] = g3
+        ind = torch.full((M, NW), -1, dtype=torch.int32, device=DEV)
+        qa.qa_indicator(L3, method, dev(gp3), stride, dev(x3), dev(G3), dev(z3), t, 0.1, lam, 1e-8, ind, NW)
+        torch.cuda.synchronize()
+        ref = np.stack([oracle.indicator(method, g3[m], x3, G3, z3, t, 0.1, lam, 1e-8) for m in range(M)])
+        assert np.array_equal(host(ind).view(np.uint32), ref), what
+        dense_ref, _, _ = oracle.quantize_pack(g3, bucket=b3)
+        sel = torch.full((M, L3.code_stride), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+        cnt = torch.zeros((M, L3.n_buckets), dtype=torch.int32, device=DEV)
+        qa.qa_select_codes(L3, dev(dense_ref.view(np.int32)), ind, NW, sel, cnt)
+        back = torch.full((M, L3.code_stride), -1, dtype=torch.int32, device=DEV)
+        qa.qa_decode_selected(L3, ind, NW, sel, back)
+        torch.cuda.synchronize()
+        area = 256 if b3 else (d3 + 15) // 16
+        for m in range(M):
+            o_sel, o_cnt = oracle.select_codes(dense_ref[m], ref[m], d3, b3)
+            assert np.array_equal(host(cnt).view(np.uint32)[m], o_cnt), what
+            for k in range(L3.n_buckets):
+                nwk = (int(o_cnt[k]) + 15) // 16
+                assert np.array_equal(host(sel).view(np.uint32)[m, k * 256:k * 256 + nwk],
+                                      o_sel[k * area:k * area + nwk]), what
+            assert np.array_equal(host(back).view(np.uint32)[m, :L3.words],
+                                  oracle.decode_selected(ref[m], o_sel, d3, bucket=b3)), what
