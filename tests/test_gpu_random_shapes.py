@@ -254,3 +254,48 @@ def test_random_shapes_of_the_other_calls_match_oracle_bit_for_bit(seed):
                                       o_sel[k * area:k * area + nwk]), what
             assert np.array_equal(host(back).view(np.uint32)[m, :L3.words],
                                   oracle.decode_selected(ref[m], o_sel, d3, bucket=b3)), what
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_random_gradient_shapes_match_oracle(seed):
+    """Dense and CSR minibatch gradients: zero pattern exact, values within 1e-6 (binary64 sums in
+    another order, exp/log from another library); repeated rows, duplicate and clustered columns."""
+    rng = np.random.default_rng(3000 + seed)
+    exact = []
+    for case in range(80):
+        csr = bool(rng.random() < 0.5)
+        n, M = int(rng.integers(1, 400)), int(rng.choice([1, 2, 5, 8, 16]))
+        B = int(rng.choice([1, 3, 16, 64, 130, 300]))
+        d = int(rng.choice([rng.integers(1, 50), rng.integers(50, 3000), 4 * rng.integers(1, 2000)]))
+        y = np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+        x = (rng.standard_normal(d) * 10.0 ** rng.integers(-3, 1)).astype(np.float32)
+        rows = rng.integers(0, n, (M, B)).astype(np.int32)
+        what = f"seed {seed} case {case}: csr={csr} n={n} d={d} B={B} M={M}"
+        if csr:
+            k = int(rng.integers(1, min(d, 60) + 1))
+            idx = rng.integers(0, d, (n, k)).astype(np.int32)
+            if rng.random() < 0.5:
+                idx = (idx % max(1, d // 50 + 1)).astype(np.int32)
+            vals = rng.standard_normal((n, k)).astype(np.float32)
+            indptr = (np.arange(n + 1) * k).astype(np.int64)
+            ref = [oracle.local_grad_csr(vals.reshape(-1), indptr, idx.reshape(-1), d, y, rows[m], x) for m in range(M)]
+            A_d, ip_d, ix_d = dev(vals.reshape(-1)), dev(indptr), dev(idx.reshape(-1))
+            fmt, op = qa.QA_CSR, qa.QA_OP_GRAD_CSR
+        else:
+            A = rng.standard_normal((n, d)).astype(np.float32)
+            ref = [oracle.local_grad_dense(A, y, rows[m], x) for m in range(M)]
+            A_d, ip_d, ix_d, fmt, op = dev(A), None, None, qa.QA_DENSE, qa.QA_OP_GRAD_DENSE
+        gs = (d + 3) // 4 * 4 + 4 * int(rng.integers(0, 3))
+        ws = workspace(qa.qa_workspace_bytes(qa.Layout.make(d, M, 0), op))
+        g = torch.full((M, gs), 5.0, dtype=torch.float32, device=DEV)
+        loss = torch.zeros(M, dtype=torch.float32, device=DEV)
+        qa.qa_local_grad_batched(fmt, A_d, ip_d, ix_d, n, d, dev(y), dev(rows), B, M, dev(x), g, gs, loss, ws)
+        torch.cuda.synchronize()
+        gg, ll = host(g), host(loss)
+        R = np.stack([r[0] for r in ref])
+        assert np.all(gg[:, d:] == 5.0), what
+        assert np.array_equal(gg[:, :d] != 0, R != 0), what
+        assert np.allclose(gg[:, :d], R, rtol=1e-6, atol=1e-30), what
+        assert np.allclose(ll, [r[1] for r in ref], rtol=1e-6), what
+        exact.append((gg[:, :d] == R).mean())
+    assert np.mean(exact) > 0.999
