@@ -369,6 +369,22 @@ def main():
         q_ms.append(ev0.elapsed_time(ev1))
     del gbuf          # stays in torch's cache: returning 4 GiB to the driver here stalls the queue
     quant_ms = float(np.median(q_ms[1:] if M > 1 else q_ms))
+    # all M gradients in one call, when they fit beside everything else (same codes and scales come out)
+    quant_all_ms = None
+    if M > 1 and M * d * 4 <= (16 << 30) and d % 4 == 0:
+        gall = torch.empty((M, d), dtype=torch.float32, device=dev)
+        for m in range(M):
+            gen(d, m, 1, device=dev, out=gall[m])
+        nqa = qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE)
+        wsa = torch.empty(nqa, dtype=torch.uint8, device=dev) if nqa else None
+        qa.qa_quantize_pack(L, gall, d, codes, scales, None, 0, wsa)
+        ev0.record()
+        for _ in range(3):
+            qa.qa_quantize_pack(L, gall, d, codes, scales, None, 0, wsa)
+        ev1.record()
+        torch.cuda.synchronize()
+        quant_all_ms = ev0.elapsed_time(ev1) / 3
+        del gall, wsa
     qbytes = 4.25 if 0 < bucket <= 4096 else 8.25      # larger buckets read the gradient twice
 
     def kind_of(t):
@@ -497,7 +513,10 @@ def main():
         "kernels_outside_timed_steps": also,
         "quantize_pack": {"ms_per_worker": quant_ms, "worker_coords_per_s": d / (quant_ms * 1e-3),
                           "achieved_GBps": qbytes * d / (quant_ms * 1e-3) / 1e9,
-                          "frac": qbytes * d / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+                          "frac": qbytes * d / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          "all_workers_one_call_ms": quant_all_ms,
+                          "all_workers_one_call_GBps": (qbytes * d * M / (quant_all_ms * 1e-3) / 1e9
+                                                        if quant_all_ms else None)},
         # rows a2-a8 together for this configuration: M quantize+pack launches (measured above, one
         # worker's fp32 gradient at a time: M of them do not fit beside the state) + the fused step
         "quantize_plus_step": {"ms_per_step": M * quant_ms + wall * 1e3 / args.steps,

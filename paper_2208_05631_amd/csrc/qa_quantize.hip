@@ -586,8 +586,20 @@ __global__ __launch_bounds__(kThreads) void quantize_abs_partial_kernel(QuantArg
   __shared__ double lds_d[kWaves];
   const int64_t tile = blockIdx.x;
   const int m = blockIdx.y;
+  const float* g = a.g + (int64_t)m * a.g_stride;
   float v[4][4];
-  load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+  if ((tile + 1) * kTile <= a.d) {
+    // streaming loads: the second pass over the gradient comes after all of it has gone by
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const floatx4 q = __builtin_nontemporal_load(
+          reinterpret_cast<const floatx4*>(g + tile * kTile + (j * kThreads + (int)threadIdx.x) * 4));
+      v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    }
+  } else {
+    load_tile(g, a.d, tile, v);
+  }
   double s = 0.0;
 #pragma unroll
   for (int j = 0; j < 4; ++j)
