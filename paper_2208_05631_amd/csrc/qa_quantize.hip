@@ -52,6 +52,23 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ g, int64_t d
   }
 }
 
+// The same with streaming (non-temporal) loads for tiles that lie wholly below d: for passes after
+// which the element is not needed again soon.
+__device__ __forceinline__ void load_tile_stream(const float* __restrict__ g, int64_t d, int64_t tile,
+                                                 float v[4][4]) {
+  if ((tile + 1) * kTile <= d) {
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const floatx4 q = __builtin_nontemporal_load(
+          reinterpret_cast<const floatx4*>(g + tile * kTile + (j * kThreads + (int)threadIdx.x) * 4));
+      v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    }
+  } else {
+    load_tile(g, d, tile, v);
+  }
+}
+
 // Ternary fields of the thread's 16 elements -> the four code words of its quad (group j of
 // lanes 4q..4q+3 is code word j*64 + t/4 of the tile); lane (t & 3) == j stores word j.
 __device__ __forceinline__ void pack_and_store(const float v[4][4], const float Delta[4],
@@ -586,20 +603,9 @@ __global__ __launch_bounds__(kThreads) void quantize_abs_partial_kernel(QuantArg
   __shared__ double lds_d[kWaves];
   const int64_t tile = blockIdx.x;
   const int m = blockIdx.y;
-  const float* g = a.g + (int64_t)m * a.g_stride;
   float v[4][4];
-  if ((tile + 1) * kTile <= a.d) {
-    // streaming loads: the second pass over the gradient comes after all of it has gone by
-    typedef float floatx4 __attribute__((ext_vector_type(4)));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const floatx4 q = __builtin_nontemporal_load(
-          reinterpret_cast<const floatx4*>(g + tile * kTile + (j * kThreads + (int)threadIdx.x) * 4));
-      v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
-    }
-  } else {
-    load_tile(g, a.d, tile, v);
-  }
+  // streaming: the second pass over the gradient comes after all of it has gone by
+  load_tile_stream(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
   double s = 0.0;
 #pragma unroll
   for (int j = 0; j < 4; ++j)
@@ -637,7 +643,7 @@ __global__ __launch_bounds__(kThreads) void quantize_codes_partial_kernel(QuantA
   const float D = a.thresh_given ? a.thresholds[(int64_t)m * a.scale_stride + k]
                                  : a.thr_ws[(int64_t)m * a.nb + k];
   float v[4][4];
-  load_tile(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
+  load_tile_stream(a.g + (int64_t)m * a.g_stride, a.d, tile, v);
   double s = 0.0;
   uint32_t c = 0;
 #pragma unroll
