@@ -36,7 +36,10 @@ __device__ __forceinline__ void load_piece_values(const float* __restrict__ g, c
   for (int j = 0; j < 4; ++j) {
     const int64_t i = base + (int64_t)(j * kThreads + (int)threadIdx.x) * 4;
     if (i >= pc.lo && i + 3 < pc.hi) {
-      const float4 q = *reinterpret_cast<const float4*>(g + i);
+      // streaming: each of the two passes over the gradients reads an element once, a whole
+      // pass apart
+      typedef float floatx4 __attribute__((ext_vector_type(4)));
+      const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + i));
       v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
     } else {
 #pragma unroll
