@@ -777,7 +777,7 @@ __global__ __launch_bounds__(kThreads) void quantize_stochastic_tile_kernel(Stoc
   const int64_t tile = blockIdx.x;
   const int m = blockIdx.y;
   float v[4][4];
-  load_tile(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
+  load_tile_stream(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
   float s = wave_max_f32(tile_abs_max(v));
   if ((threadIdx.x % kWave) == 0) lds_m[threadIdx.x / kWave] = s;
   __syncthreads();
@@ -795,7 +795,7 @@ __global__ __launch_bounds__(kThreads) void quantize_stochastic_twopass_kernel(S
   const int m = blockIdx.y;
   const int64_t k = tile / a.q.tiles_per_bucket;
   float v[4][4];
-  load_tile(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
+  load_tile_stream(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
   float* sc = a.q.scales + (int64_t)m * a.q.scale_stride + k;
   if (a.pass == 0) {
     const float s = wave_max_f32(tile_abs_max(v));
