@@ -283,14 +283,16 @@ int qa_step_qrda_selected(const qa_layout* layout, const uint32_t* ind, int64_t 
                           float* z, int64_t t, float eta, float lambda, float delta, int requant,
                           void* ws, size_t ws_bytes, void* stream);
 
-/* qa_aggregate_quantize on sparse-encoded messages (Algorithm 1, server: "Decode", "Average",
- * "Quantize the aggregated gradient" in one call); ind / ind_stride / sel_codes as for
- * qa_decode_selected.  qa_select_codes with the synchronous indicator then turns q_codes into
- * the message S(q_t, I^Syn) that is pushed to the workers. */
+/* qa_aggregate_quantize on sparse-encoded messages (Algorithm 1, server: "Decode", "Compute the
+ * synchronous indicator", "Average", "Quantize the aggregated gradient" in one call); ind /
+ * ind_stride / sel_codes as for qa_decode_selected.  If ind_syn_out is not NULL it receives the
+ * synchronous indicator, ceil(d/32) words, exactly as qa_indicator_or writes it.  qa_select_codes
+ * with that indicator then turns q_codes into the message S(q_t, I^Syn) that is pushed to the
+ * workers. */
 int qa_aggregate_quantize_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
                                    const uint32_t* sel_codes, const float* scales, int requant,
-                                   uint32_t* q_codes, float* q_scales, float* q_thresholds, void* ws,
-                                   size_t ws_bytes, void* stream);
+                                   uint32_t* q_codes, float* q_scales, float* q_thresholds,
+                                   uint32_t* ind_syn_out, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- a list of parameter tensors in one flat vector --------------------------------------------
  *

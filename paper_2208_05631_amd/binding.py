@@ -278,12 +278,13 @@ def qa_aggregate_quantize(layout, codes, scales, requant, q_codes, q_scales, q_t
 
 
 def qa_aggregate_quantize_selected(layout, ind, ind_stride, sel_codes, scales, requant, q_codes, q_scales,
-                                   q_thresholds, ws, stream=None):
+                                   q_thresholds, ind_syn_out, ws, stream=None):
     _lib.qa_aggregate_quantize_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, C.c_int,
-                                                    _vp, _vp, _vp, _vp, _sz, _vp]
+                                                    _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     _check(_lib.qa_aggregate_quantize_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes),
                                                _p(scales), requant, _p(q_codes), _p(q_scales),
-                                               _p(q_thresholds), _p(ws), _nbytes(ws), _stream(stream)),
+                                               _p(q_thresholds), _p(ind_syn_out), _p(ws), _nbytes(ws),
+                                               _stream(stream)),
            "qa_aggregate_quantize_selected")
 
 

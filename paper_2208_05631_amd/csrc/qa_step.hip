@@ -39,6 +39,7 @@ struct StepArgs {
   uint32_t* q_codes;
   float* q_scales;
   float* q_thresholds;   // optional
+  uint32_t* ind_syn;     // optional, sparse messages: OR of the workers' indicators
 };
 
 // 10 -> 00 so that the reserved pattern reads as zero; 01 and 11 are unchanged.
@@ -307,6 +308,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     const uint32_t ind_off = (uint32_t)(t >> 1) * 4u;
     const int64_t live = a.d - (tile_base + 16 * (int64_t)t);
     const uint32_t live_mask = live >= 16 ? 0xFFFFu : (live > 0 ? (1u << live) - 1u : 0u);
+    uint32_t syn = 0;                                    // the synchronous indicator of the thread's 16
     for (int m0 = 0; m0 < a.M; m0 += kChunk) {
       const int left = a.M - m0;
       uint32_t mk[kChunk];
@@ -315,6 +317,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
         const uint32_t iv =
             i < left ? stream_load(itile + (int64_t)(m0 + i) * a.ind_stride, ind_off, ind_bytes) : 0u;
         mk[i] = (iv >> (16 * (t & 1))) & live_mask;
+        syn |= mk[i];
       }
       // marked components before this thread's, per worker (two 16-bit counts per scan; a tile
       // holds at most 4096)
@@ -373,6 +376,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
             }
           }
       }
+    }
+    if (a.ind_syn) {                                     // uniform; word t/2 = the halves of threads t, t^1
+      const uint32_t other = (uint32_t)dpp_i32<kDppQuadXor1>((int)syn);
+      const int64_t iw = tile * (kTile / 32) + (t >> 1);
+      if ((t & 1) == 0 && iw < NW) a.ind_syn[iw] = syn | (other << 16);
     }
   } else if (reorder_ok) {
     for (int m0 = 0; m0 < a.M; m0 += kChunk) {
@@ -713,10 +721,11 @@ static int aggregate_quantize_common(const qa_layout* L, const uint32_t* codes, 
                                      int requant, uint32_t* q_codes, float* q_scales,
                                      float* q_thresholds, void* ws, size_t ws_bytes,
                                      hipStream_t stream, bool sparse, const uint32_t* ind,
-                                     int64_t ind_stride) {
+                                     int64_t ind_stride, uint32_t* ind_syn) {
   int rc = check_layout(L);
   if (rc != QA_OK) return rc;
   if (!codes || !scales || !q_codes || !q_scales) return QA_ERR_INVALID_ARG;
+  if (!aligned(ind_syn, 4)) return QA_ERR_ALIGNMENT;
   if (requant != QA_REQUANT_BUCKET && requant != QA_REQUANT_GLOBAL) return QA_ERR_INVALID_ARG;
   if (requant == QA_REQUANT_BUCKET && L->bucket == 0) return QA_ERR_INVALID_ARG;
   if (sparse) {
@@ -731,7 +740,7 @@ static int aggregate_quantize_common(const qa_layout* L, const uint32_t* codes, 
   if (tiles_of(L->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
 
   StepArgs ag = make_args(L, codes, scales);
-  if (sparse) { ag.ind = ind; ag.ind_stride = ind_stride; }
+  if (sparse) { ag.ind = ind; ag.ind_stride = ind_stride; ag.ind_syn = ind_syn; }
   if (requant_in_tile(L, requant)) {
     ag.q_codes = q_codes; ag.q_scales = q_scales; ag.q_thresholds = q_thresholds;
     launch_mode<kAggregate>(ag, false, true, stream);
@@ -894,15 +903,16 @@ extern "C" int qa_aggregate_quantize(const qa_layout* layout, const uint32_t* co
                                      void* stream) {
   return qa::aggregate_quantize_common(layout, codes, scales, requant, q_codes, q_scales,
                                        q_thresholds, ws, ws_bytes, static_cast<hipStream_t>(stream),
-                                       false, nullptr, 0);
+                                       false, nullptr, 0, nullptr);
 }
 
 extern "C" int qa_aggregate_quantize_selected(const qa_layout* layout, const uint32_t* ind,
                                               int64_t ind_stride, const uint32_t* sel_codes,
                                               const float* scales, int requant, uint32_t* q_codes,
-                                              float* q_scales, float* q_thresholds, void* ws,
-                                              size_t ws_bytes, void* stream) {
+                                              float* q_scales, float* q_thresholds,
+                                              uint32_t* ind_syn_out, void* ws, size_t ws_bytes,
+                                              void* stream) {
   return qa::aggregate_quantize_common(layout, sel_codes, scales, requant, q_codes, q_scales,
                                        q_thresholds, ws, ws_bytes, static_cast<hipStream_t>(stream),
-                                       true, ind, ind_stride);
+                                       true, ind, ind_stride, ind_syn_out);
 }

@@ -259,8 +259,7 @@ def test_server_and_worker_roles_as_separate_calls_equal_the_fused_step(method):
     qs = torch.zeros((1, nb), dtype=torch.float32, device=DEV)
     push = torch.zeros((1, L1.code_stride), dtype=torch.int32, device=DEV)
     push_cnt = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
-    qa.qa_indicator_or(L, ind, NW, syn)
-    qa.qa_aggregate_quantize_selected(L, ind, NW, sel, sc, qa.QA_REQUANT_BUCKET, qc, qs, None, None)
+    qa.qa_aggregate_quantize_selected(L, ind, NW, sel, sc, qa.QA_REQUANT_BUCKET, qc, qs, None, syn, None)
     qa.qa_select_codes(L1, qc, syn, 0, push, push_cnt)
     # a worker
     xb, Gb, zb = xd.clone(), Gd.clone(), zd.clone()
@@ -386,11 +385,15 @@ def test_server_call_on_sparse_messages_matches_oracle(d, M, bucket, p, requant,
     qs = torch.full((1, L1.scale_stride), -7.0, dtype=torch.float32, device=DEV)
     ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
     ind_d = dev(ind.view(np.int32))
+    syn_k = torch.full((NW + 2,), -1, dtype=torch.int32, device=DEV)
     qa.qa_aggregate_quantize_selected(L, ind_d, 0 if shared else NW, dev(sel.view(np.int32)), dev(sc),
-                                      requant, qc, qs, None, ws)
+                                      requant, qc, qs, None, syn_k, ws)
     torch.cuda.synchronize()
     assert np.array_equal(host(qc).view(np.uint32)[:, :W], qc_ref)
     assert np.array_equal(host(qs)[:, :L1.n_buckets].view(np.uint32), qs_ref.view(np.uint32))
+    # the synchronous indicator comes out of the same pass
+    assert np.array_equal(host(syn_k).view(np.uint32)[:NW], oracle.indicator_or(ind, d))
+    assert np.all(host(syn_k)[NW:] == -1)
     if bq == bucket:                                     # the pushed message S(q_t, I_syn)
         syn = torch.zeros(NW, dtype=torch.int32, device=DEV)
         ind_all = ind_d if not shared else ind_d.repeat(M, 1)
