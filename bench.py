@@ -538,7 +538,7 @@ def main():
         c_s = codes[:, :Ws].cpu().numpy().view(np.uint32).copy()
         s_s = scales[:, :nbs].cpu().numpy().copy()
         ox, oG, oz = (np.zeros(ds, np.float32) for _ in range(3))
-        n_cpu = 10
+        n_cpu = 30                                # about 15 s of one host core
         oracle.lib()
         c0 = time.perf_counter()
         for tt in range(1, n_cpu + 1):
