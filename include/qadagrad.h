@@ -55,6 +55,7 @@ extern "C" {
 #define QA_ERR_WORKSPACE (-3)   /* workspace NULL or smaller than qa_workspace_bytes says    */
 #define QA_ERR_LAUNCH (-4)      /* the HIP runtime refused a launch (hipGetLastError != 0)   */
 #define QA_ERR_UNSUPPORTED (-5) /* valid request this build does not implement               */
+#define QA_ERR_TOO_LARGE (-6)   /* qa_quantize_pack_static: needs more than the static scratch */
 
 /* second-quantization mode of the fused steps ("q_t = Q(SynQ_t)", Section 3.2, equation Qt;
  * the methods marked with a dagger in Section 5.1 skip it) */
@@ -154,6 +155,27 @@ int qa_local_grad_batched(int format, const float* A_or_vals, const int64_t* ind
 int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, uint32_t* codes,
                      float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
                      void* stream);
+
+/* qa_quantize_pack for callers that cannot allocate or pass device scratch: code recorded into a
+ * HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * results as qa_quantize_pack, bit for bit, without the workspace: the per-tile partial sums,
+ * counts and thresholds that the multi-pass layouts need (one scale per vector, or buckets above
+ * 4096) live in a 4 MiB array in the library's own device image instead.  The call allocates
+ * nothing and frees nothing.
+ *   - Limit: qa_workspace_bytes(layout, QA_OP_QUANTIZE) <= 4 MiB (QA_STATIC_SCRATCH_BYTES), about
+ *     12 bytes per worker and 4096 coordinates: e.g. M * ceil(d/4096) <= 349 000.  Larger
+ *     problems return QA_ERR_TOO_LARGE and launch nothing.  Layouts that need no workspace
+ *     (bucket <= 4096, or a vector of at most 4096 coordinates) have no limit.
+ *   - Each GPU holds one such array for the life of the process.  The first call on a device
+ *     looks its address up (the device of the calling thread must be the one `stream` belongs
+ *     to); make that first call outside stream capture.
+ *   - All calls on one GPU share the array: two calls whose kernels may overlap (different
+ *     streams, or several host threads) race on it.  Calls on one stream are ordered and safe.
+ *     Nothing in the array needs clearing between calls. */
+#define QA_STATIC_SCRATCH_BYTES (4u << 20)
+int qa_quantize_pack_static(const qa_layout* layout, const float* g, int64_t g_stride,
+                            uint32_t* codes, float* scales, float* thresholds, uint32_t flags,
+                            void* stream);
 
 /* Stochastic ternary quantizer, the "ternary" comparison of Section 5.1 (TernGrad, cited in
  * Section 2; the paper does not restate it): per bucket s = max|v_i|, component i is kept with

@@ -13,4 +13,5 @@ from .binding import (  # noqa: F401
     SegmentPlan, qa_segment_plan_bytes, qa_segment_plan_init, qa_segment_workspace_bytes,
     qa_quantize_pack_segments, qa_step_qcmd_segments, qa_step_qrda_segments, qa_select_codes, qa_segment_plan_host,
     qa_step_qcmd_selected, qa_step_qrda_selected, qa_aggregate_quantize, qa_aggregate_quantize_selected,
+    qa_quantize_pack_static,
 )

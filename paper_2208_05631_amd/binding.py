@@ -148,6 +148,14 @@ def qa_quantize_pack(layout, g, g_stride, codes, scales, thresholds, flags, ws, 
            "qa_quantize_pack")
 
 
+def qa_quantize_pack_static(layout, g, g_stride, codes, scales, thresholds, flags, stream=None):
+    _lib.qa_quantize_pack_static.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp,
+                                             C.c_uint32, _vp]
+    _check(_lib.qa_quantize_pack_static(C.byref(layout), _p(g), g_stride, _p(codes), _p(scales),
+                                        _p(thresholds), flags, _stream(stream)),
+           "qa_quantize_pack_static")
+
+
 def qa_aggregate_unpack(layout, codes, scales, gbar_out, stream=None):
     _check(_lib.qa_aggregate_unpack(C.byref(layout), _p(codes), _p(scales), _p(gbar_out),
                                     _stream(stream)), "qa_aggregate_unpack")

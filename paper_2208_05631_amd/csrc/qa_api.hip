@@ -17,6 +17,7 @@ extern "C" const char* qa_strerror(int code) {
     case QA_ERR_WORKSPACE: return "workspace missing or too small (see qa_workspace_bytes)";
     case QA_ERR_LAUNCH: return "HIP kernel launch failed";
     case QA_ERR_UNSUPPORTED: return "request not supported by this build";
+    case QA_ERR_TOO_LARGE: return "problem needs more scratch than the library's static array holds";
     default: return "unknown error code";
   }
 }

@@ -8,6 +8,8 @@
 //                    formed in registers/LDS; the gradient is read once (4 B/elem + 0.25 B out).
 //   bucket  > 4096 or 0 (whole vector): tile partial sums -> finalize threshold -> codes and
 //                    tile partial (count, sum) -> finalize scale; the gradient is read twice.
+#include <mutex>
+
 #include "qa_common.h"
 
 namespace qa {
@@ -897,7 +899,67 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   return launch_status();
 }
 
+// ---- scratch that the library owns, for callers that cannot hand over a workspace -------------
+//
+// The multi-pass quantizer keeps per-tile partial sums, counts and the thresholds between its
+// launches.  qa_quantize_pack_static keeps them in this array instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy until the process ends; its device address
+// is looked up once per device and that address (never the symbol itself) is what host code
+// hands to the kernels.
+constexpr size_t kScratchBytes = size_t(4) << 20;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void* scratch_ptr[kMaxDevices];    // device address of `scratch` on each GPU, 0 = not yet asked
+
+// Address of the current device's copy of `scratch`.
+static int scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return QA_ERR_LAUNCH;
+  }
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return QA_ERR_LAUNCH;
+    }
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return QA_OK;
+}
+
 }  // namespace qa
+
+extern "C" int qa_quantize_pack_static(const qa_layout* layout, const float* g, int64_t g_stride,
+                                       uint32_t* codes, float* scales, float* thresholds,
+                                       uint32_t flags, void* stream) {
+  using namespace qa;
+  int rc = check_layout(layout);
+  if (rc != QA_OK) return rc;
+  if (!g || !codes || !scales) return QA_ERR_INVALID_ARG;
+  if (flags & ~(QA_THRESH_GIVEN | QA_THRESH_EXACT)) return QA_ERR_INVALID_ARG;
+  if ((flags & QA_THRESH_GIVEN) && (flags & QA_THRESH_EXACT)) return QA_ERR_INVALID_ARG;
+  if ((flags & (QA_THRESH_GIVEN | QA_THRESH_EXACT)) && !thresholds) return QA_ERR_INVALID_ARG;
+  if (g_stride < layout->d || (g_stride % 4) != 0) return QA_ERR_INVALID_ARG;
+  if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(thresholds, 4))
+    return QA_ERR_ALIGNMENT;
+  const size_t need = quantize_workspace_bytes(layout);
+  if (need > kScratchBytes) return QA_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  if (need) {
+    rc = scratch_address(&ws);
+    if (rc != QA_OK) return rc;
+  }
+  // every partial that a later launch reads is written by an earlier launch of the same call:
+  // nothing in the array has to start at zero
+  return quantize_launch(layout, g, g_stride, codes, scales, thresholds, flags, ws,
+                         need ? kScratchBytes : 0, static_cast<hipStream_t>(stream));
+}
 
 extern "C" int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride,
                                 uint32_t* codes, float* scales, float* thresholds, uint32_t flags,

@@ -3,6 +3,7 @@ through the binding, bring results back.  No arithmetic of the method lives here
 import numpy as np
 import torch
 
+import oracle
 import paper_2208_05631_amd as qa
 
 DEV = torch.device("cuda:0")
@@ -68,3 +69,38 @@ class GpuState:
     def get(self):
         torch.cuda.synchronize()
         return host(self.x), host(self.G), host(self.z)
+
+
+def ulp_distance(a, b):
+    """Distance in units in the last place between two float32 arrays (finite values)."""
+    def ordered(v):
+        i = np.ascontiguousarray(v, np.float32).view(np.int32).astype(np.int64)
+        return np.where(i < 0, -(i & 0x7FFFFFFF), i)
+    return np.abs(ordered(a) - ordered(b))
+
+
+def quantizer_parity(g, bucket, codes, scales, thresholds, what="", thr_coef=0.75):
+    """The GPU quantizer's message (codes u32 [M, >=W], scales / thresholds f32 [M, >=nb]) for the
+    gradient g (f32 [M, d]) against the oracle's for the same g.
+
+    What the arithmetic guarantees: a bucket's sums are formed in binary64 in a different order on
+    the two sides and rounded once, so a threshold or a scale may differ by one binary32 ulp (about
+    once in 2^29 sums); codes are exact given the threshold.  Bit-identical messages return 0.
+    Otherwise every threshold and scale must lie within 1 ulp, and the codes must equal, bit for
+    bit, the oracle's codes for the GPU's own thresholds; the number of (worker, bucket) pairs
+    that were not bit-identical is returned so that the caller can report it."""
+    M, d = g.shape
+    W, nb = oracle.n_words(d), oracle.n_buckets(d, bucket)
+    oc, osc, oth = oracle.quantize_pack(g, bucket=bucket, thr_coef=thr_coef)
+    gt = np.ascontiguousarray(thresholds[:, :nb], np.float32)
+    gs = np.ascontiguousarray(scales[:, :nb], np.float32)
+    same = (gt.view(np.uint32) == oth[:, :nb].view(np.uint32)) & \
+           (gs.view(np.uint32) == osc[:, :nb].view(np.uint32))
+    if same.all():
+        assert np.array_equal(codes[:, :W], oc[:, :W]), f"codes differ with identical thresholds {what}"
+        return 0
+    assert int(ulp_distance(gt, oth[:, :nb]).max()) <= 1, f"threshold off by more than 1 ulp {what}"
+    oc2, osc2, _ = oracle.quantize_pack(g, bucket=bucket, thr_coef=thr_coef, thresholds=gt)
+    assert np.array_equal(codes[:, :W], oc2[:, :W]), f"codes differ for the same thresholds {what}"
+    assert int(ulp_distance(gs, osc2[:, :nb]).max()) <= 1, f"scale off by more than 1 ulp {what}"
+    return int((~same).sum())

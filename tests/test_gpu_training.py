@@ -4,7 +4,15 @@ for the paper's sparse linear-model experiments.
 
 Per step: packed codes and the zero set of x must be identical; x, G, z within 1e-5 max
 relative error; the objective curve (mean logistic loss on an evaluation set + lambda*|x|_1)
-within 1e-4.  Each side computes its own gradients from its own parameters."""
+within 1e-4.  Each side computes its own gradients from its own parameters.
+
+Both sides form every long sum in binary64 and round once, in different orders, so a margin, a
+gradient component, a threshold or a scale can differ in its last binary32 bit about once in 2^29
+sums.  When a step's messages are not bit-identical the test does not fail on that alone: it
+requires the gradients to agree to 1e-6, the GPU's thresholds and scales to lie within one ulp of
+the oracle's for the GPU's own gradient, and the GPU's codes to be bit-exact for the GPU's own
+thresholds ("bit-exact given the same scale"); the oracle then continues from the GPU's message,
+and the number of such steps is reported and bounded."""
 import os
 
 import numpy as np
@@ -18,7 +26,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_05631_amd as qa
-    from gpu_util import DEV, dev, host, workspace
+    from gpu_util import DEV, dev, host, quantizer_parity, workspace
 
 RTOL_STATE = 1e-5
 TOL_LOSS = 1e-4
@@ -47,6 +55,7 @@ class GpuTrainer:
         self.g = torch.zeros((M, self.gs), dtype=torch.float32, device=DEV)
         self.codes = torch.zeros((M, self.L.code_stride), dtype=torch.int32, device=DEV)
         self.scales = torch.zeros((M, self.L.scale_stride), dtype=torch.float32, device=DEV)
+        self.th = torch.zeros((M, self.L.scale_stride), dtype=torch.float32, device=DEV)
         self.loss = torch.zeros(1, dtype=torch.float32, device=DEV)
         op = qa.QA_OP_GRAD_CSR if csr else qa.QA_OP_GRAD_DENSE
         self.ws_g = workspace(qa.qa_workspace_bytes(self.L, op))
@@ -64,7 +73,7 @@ class GpuTrainer:
         qa.qa_local_grad_batched(fmt, self.A, self.indptr, self.indices, self.n, self.d, self.y,
                                  dev(rows), rows.shape[1], self.M, self.x, self.g, self.gs, None,
                                  self.ws_g)
-        qa.qa_quantize_pack(self.L, self.g, self.gs, self.codes, self.scales, None, 0, self.ws_q)
+        qa.qa_quantize_pack(self.L, self.g, self.gs, self.codes, self.scales, self.th, 0, self.ws_q)
         if method == "qcmd":
             qa.qa_step_qcmd(self.L, self.codes, self.scales, self.x, self.G, self.z, eta, lam, delta,
                             requant, self.ws_s)
@@ -90,10 +99,11 @@ class OracleTrainer:
             return oracle.local_grad_csr(p.vals, p.indptr, p.indices, self.d, p.y, rows, self.x)
         return oracle.local_grad_dense(p.A, p.y, rows, self.x)
 
-    def step(self, rows, method, t, eta, lam, delta, requant):
-        g = np.stack([self.grad(rows[m])[0] for m in range(self.M)])
-        self.g = g
-        self.codes, self.scales, _ = oracle.quantize_pack(g, bucket=self.b)
+    def make_messages(self, rows):
+        self.g = np.stack([self.grad(rows[m])[0] for m in range(self.M)])
+        self.codes, self.scales, _ = oracle.quantize_pack(self.g, bucket=self.b)
+
+    def apply(self, method, t, eta, lam, delta, requant):
         if method == "qcmd":
             oracle.step_qcmd(self.codes, self.scales, self.d, self.b, self.x, self.G, self.z, eta, lam,
                              delta, requant)
@@ -106,37 +116,76 @@ class OracleTrainer:
         return float(loss) + lam * float(np.abs(self.x.astype(np.float64)).sum())
 
 
+class ParityRun:
+    """GPU and oracle side by side; advance(n) takes the next n steps of Algorithm 1 on both and
+    compares after every step, finish() checks what holds for the whole run."""
+
+    def __init__(self, prob, d, M, B, bucket, csr, method, T, eta, lam, delta, requant, seed,
+                 eval_rows):
+        self.gt = GpuTrainer(prob, d, M, bucket, csr)
+        self.ot = OracleTrainer(prob, d, M, bucket, csr)
+        self.n = prob.n if csr else prob.A.shape[0]
+        self.d, self.M, self.B, self.bucket, self.method, self.T = d, M, B, bucket, method, T
+        self.eta, self.lam, self.delta, self.requant, self.seed = eta, lam, delta, requant, seed
+        self.eval_rows, self.er_dev = eval_rows, dev(eval_rows)
+        self.t = 0
+        self.worst, self.exact_steps, self.last_bit_steps = 0.0, 0, []
+        self.curve_g, self.curve_o = [], []
+
+    def advance(self, n_steps):
+        gt, ot, d, bucket, method = self.gt, self.ot, self.d, self.bucket, self.method
+        eta, lam, delta, requant = self.eta, self.lam, self.delta, self.requant
+        W, nb = gt.L.words, gt.L.n_buckets
+        for t in range(self.t + 1, min(self.t + n_steps, self.T) + 1):
+            rows = synth.minibatch_rows(self.n, self.M, self.B, t, self.seed)
+            gt.step(rows, method, t, eta, lam, delta, requant)
+            ot.make_messages(rows)
+            torch.cuda.synchronize()
+            codes = host(gt.codes).view(np.uint32)
+            scales = host(gt.scales)
+            gg = host(gt.g)[:, :d]
+            assert np.array_equal(gg != 0, ot.g != 0), f"gradient sparsity pattern differs, step {t}"
+            if not (np.array_equal(codes[:, :W], ot.codes[:, :W]) and
+                    np.array_equal(scales[:, :nb].view(np.uint32), ot.scales[:, :nb].view(np.uint32))):
+                # a last-bit difference somewhere before the codes: check what the arithmetic
+                # guarantees and let the oracle continue from the GPU's (verified) messages
+                ge = max_rel(gg, ot.g)
+                assert ge <= 1e-6, f"gradients differ by {ge} at step {t}"
+                quantizer_parity(gg, bucket, codes, scales, host(gt.th), what=f"(step {t})")
+                ot.codes = np.ascontiguousarray(codes[:, :W])
+                ot.scales = np.ascontiguousarray(scales[:, :nb])
+                self.last_bit_steps.append(t)
+            ot.apply(method, t, eta, lam, delta, requant)
+            x, G, z = host(gt.x), host(gt.G), host(gt.z)
+            assert np.array_equal(x == 0, ot.x == 0), f"zero set of x differs, step {t}"
+            e = max(max_rel(x, ot.x), max_rel(G, ot.G), max_rel(z, ot.z))
+            assert e <= RTOL_STATE, f"state rel err {e} at step {t}"
+            self.worst = max(self.worst, e)
+            self.exact_steps += int(e == 0.0)
+            if t % 5 == 0 or t == self.T:
+                self.curve_g.append(gt.objective(self.er_dev, lam))
+                self.curve_o.append(ot.objective(self.eval_rows, lam))
+                assert abs(self.curve_g[-1] - self.curve_o[-1]) <= TOL_LOSS, f"objective differs at step {t}"
+            self.t = t
+
+    def finish(self):
+        T, ot = self.T, self.ot
+        assert self.t == T, f"only {self.t} of {T} steps were taken"
+        assert self.curve_o[-1] < self.curve_o[0] or T < 10, "the oracle run does not descend"
+        assert len(self.last_bit_steps) <= 2 + T // 100, \
+            f"messages not bit-identical at steps {self.last_bit_steps}"
+        print(f"{self.method}: T = {T}; worst state rel err {self.worst:.2e}; "
+              f"{self.exact_steps}/{T} steps bit-identical; "
+              f"steps with a last-bit difference in the messages: {self.last_bit_steps}; "
+              f"objective {self.curve_o[0]:.4f} -> {self.curve_o[-1]:.4f}; "
+              f"nnz(x) = {(ot.x != 0).sum()} of {self.d}")
+        return ot
+
+
 def run_parity(prob, d, M, B, bucket, csr, method, T, eta, lam, delta, requant, seed, eval_rows):
-    gt = GpuTrainer(prob, d, M, bucket, csr)
-    ot = OracleTrainer(prob, d, M, bucket, csr)
-    n = prob.n if csr else prob.A.shape[0]
-    er_dev = dev(eval_rows)
-    worst = 0.0
-    exact_steps = 0
-    curve_g, curve_o = [], []
-    for t in range(1, T + 1):
-        rows = synth.minibatch_rows(n, M, B, t, seed)
-        gt.step(rows, method, t, eta, lam, delta, requant)
-        ot.step(rows, method, t, eta, lam, delta, requant)
-        torch.cuda.synchronize()
-        codes = host(gt.codes).view(np.uint32)
-        assert np.array_equal(codes[:, :gt.L.words], ot.codes[:, :gt.L.words]), f"codes differ, step {t}"
-        gg = host(gt.g)[:, :d]
-        assert np.array_equal(gg != 0, ot.g != 0), f"gradient sparsity pattern differs, step {t}"
-        x, G, z = host(gt.x), host(gt.G), host(gt.z)
-        assert np.array_equal(x == 0, ot.x == 0), f"zero set of x differs, step {t}"
-        e = max(max_rel(x, ot.x), max_rel(G, ot.G), max_rel(z, ot.z))
-        assert e <= RTOL_STATE, f"state rel err {e} at step {t}"
-        worst = max(worst, e)
-        exact_steps += int(e == 0.0 and np.array_equal(host(gt.scales), ot.scales))
-        if t % 5 == 0 or t == T:
-            curve_g.append(gt.objective(er_dev, lam))
-            curve_o.append(ot.objective(eval_rows, lam))
-            assert abs(curve_g[-1] - curve_o[-1]) <= TOL_LOSS, f"objective differs at step {t}"
-    assert curve_o[-1] < curve_o[0] or T < 10, "the oracle run does not descend"
-    print(f"{method}: worst state rel err {worst:.2e}; {exact_steps}/{T} steps bit-identical; "
-          f"objective {curve_o[0]:.4f} -> {curve_o[-1]:.4f}; nnz(x) = {(ot.x != 0).sum()} of {d}")
-    return ot
+    run = ParityRun(prob, d, M, B, bucket, csr, method, T, eta, lam, delta, requant, seed, eval_rows)
+    run.advance(T)
+    return run.finish()
 
 
 @pytest.fixture(scope="module")
@@ -157,22 +206,33 @@ def test_tiny_dense_logistic_regression(tiny_problem, method, requant):
 
 @pytest.fixture(scope="module")
 def sparse_problem():
-    full = os.environ.get("QA_FULL_CONFIG2", "0") == "1"
-    return synth.csr_problem(n=(1 << 18) if full else (1 << 15), d=1 << 20, nnz_per_row=100,
-                             zipf_s=1.1, M=16, seed=1)
+    return synth.csr_problem(n=1 << 18, d=1 << 20, nnz_per_row=100, zipf_s=1.1, M=16, seed=1)
 
 
+CONFIG2_T = int(os.environ.get("QA_CONFIG2_STEPS", "500"))    # shortens the run while developing
+CONFIG2_PART = 50                                             # steps per test: a sign of life per part
+_config2_runs = {}
+
+
+@pytest.mark.parametrize("part", range((CONFIG2_T + CONFIG2_PART - 1) // CONFIG2_PART))
 @pytest.mark.parametrize("method", ["qcmd", "qrda"])
-def test_sparse_highdim_logistic_regression(sparse_problem, method):
-    """d=2^20, CSR rows with 100 Zipf(1.1) columns, M=16 workers x batch 256, lambda=1e-4,
-    bucket 4096.  T=500 and n=2^18 with QA_FULL_CONFIG2=1, otherwise T=40 and n=2^15 (same
-    kernel shapes: the row count only changes which rows a batch can draw)."""
+def test_sparse_highdim_logistic_regression(sparse_problem, method, part):
+    """d=2^20, n=2^18 CSR rows with 100 Zipf(1.1) columns, M=16 workers x batch 256, lambda=1e-4,
+    bucket 4096, T=500 steps of each method.  One run per method, cut into parts of 50 steps
+    that share its state (they run in order; a part whose predecessor did not run fails in
+    finish()), every step compared as in ParityRun."""
     p = sparse_problem
-    T = 500 if os.environ.get("QA_FULL_CONFIG2", "0") == "1" else 40
-    rng = np.random.default_rng(99)
-    eval_rows = rng.integers(0, p.n, 4096).astype(np.int32)
-    run_parity(p, p.d, 16, 256, 4096, True, method, T, 0.1, 1e-4, 1e-8, 0, seed=1,
-               eval_rows=eval_rows)
+    if part == 0:
+        rng = np.random.default_rng(99)
+        eval_rows = rng.integers(0, p.n, 4096).astype(np.int32)
+        _config2_runs[method] = ParityRun(p, p.d, 16, 256, 4096, True, method, CONFIG2_T, 0.1, 1e-4,
+                                          1e-8, 0, seed=1, eval_rows=eval_rows)
+    run = _config2_runs[method]
+    assert run.t == part * CONFIG2_PART, "parts must run in order"
+    run.advance(CONFIG2_PART)
+    if run.t == CONFIG2_T:
+        run.finish()
+        del _config2_runs[method]
 
 
 @pytest.mark.parametrize("method,requant,bucket", [("qcmd", 0, 0), ("qrda", 2, 0), ("qcmd", 1, 256)])
