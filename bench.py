@@ -21,11 +21,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see
-# profiles/step_kernel_largest_traffic.txt for the runs and the calibration against a plain
-# elementwise kernel of known size: FETCH_SIZE reads half the true KiB on this chip, WRITE_SIZE
-# reads true KiB).  Keyed by (workload, kernel kind); null for workloads not profiled.
-MEASURED_TRAFFIC_BYTES = {
+# HBM bytes per launch from rocprofv3 --pmc runs of this same command (FETCH_SIZE, WRITE_SIZE,
+# each scaled by what the counter reads for a plain elementwise kernel of known size: FETCH_SIZE
+# reads half the true KiB on this chip, WRITE_SIZE the true KiB).  NOT measured in this run: the
+# figures are copied from the profile summary named beside them and are reported together with
+# that file's name; null for workloads that were not profiled.
+TRAFFIC_SOURCE = "profiles/step_kernel_largest_traffic.txt"
+PROFILED_TRAFFIC_BYTES = {
     ("largest", "qcmd_z"): 30.60e9 + 12.885e9,
     ("largest", "qrda"): 26.31e9 + 12.885e9,
 }
@@ -435,65 +437,63 @@ def main():
             bpc = (M / 4 + 4) + 4.25 + (bpc - M / 4 + 0.25)
         kernels[k] = {"avg_ms": avg, "median_ms": float(np.median(ms)), "min_ms": float(np.min(ms)),
                       "max_ms": float(np.max(ms)), "launches": len(ms), "bytes_per_coord": bpc,
-                      "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+                      "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9,
+                      "frac": bpc * d / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"])
     dk = kernels[dominant]
     nnz_x = int((x != 0).sum().item())
 
-    # plain QCMD (z not tracked, 16 + M/4 B/coordinate): after the K timed steps, not part of them
-    also = {}
-    if wl["schedule"] == "alternate":
-        qa.qa_step_qcmd(L, codes, scales, x, G, None, eta, lam, delta, qa.QA_REQUANT_NONE, None)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
-            qa.qa_step_qcmd(L, codes, scales, x, G, None, eta, lam, delta, qa.QA_REQUANT_NONE, None)
-        e1.record()
+    def timed_launches(fn, n):
+        fn()                                                  # one untimed launch first
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        for _ in range(n):
+            fn()
+        a1.record()
         torch.cuda.synchronize()
-        avg = e0.elapsed_time(e1) / 3
-        bpc = algorithmic_bytes_per_coord("qcmd", M)
-        also["qcmd"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
-                        "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+        return a0.elapsed_time(a1) / n
+
+    def entry(avg, n, bpc):
+        gbps = bpc * d / (avg * 1e-3) / 1e9
+        return {"avg_ms": avg, "launches": n, "bytes_per_coord": bpc, "achieved_GBps": gbps,
+                "frac": gbps / HBM_PEAK_GBPS}
+
+    # Other calls on the same resident messages, after the K timed steps and not part of them,
+    # each with as many launches as a kernel of the timed schedule got.
+    also = {}
+    n_also = max(3, args.steps // 2)
+    if wl["schedule"] == "alternate":
+        # plain QCMD: z not tracked, 16 + M/4 B per coordinate (equation QCMD as printed)
+        avg = timed_launches(lambda: qa.qa_step_qcmd(L, codes, scales, x, G, None, eta, lam, delta,
+                                                     qa.QA_REQUANT_NONE, None), n_also)
+        also["qcmd"] = entry(avg, n_also, algorithmic_bytes_per_coord("qcmd", M))
         # row a4 alone: the average written out as fp32 (M/4 B of codes in, 4 B out per coordinate)
         gbar = torch.empty(d, dtype=torch.float32, device=dev)
-        qa.qa_aggregate_unpack(L, codes, scales, gbar)
-        e0.record()
-        for _ in range(3):
-            qa.qa_aggregate_unpack(L, codes, scales, gbar)
-        e1.record()
-        torch.cuda.synchronize()
-        avg = e0.elapsed_time(e1) / 3
-        bpc = M / 4 + 4
-        also["aggregate_unpack"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
-                                    "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+        avg = timed_launches(lambda: qa.qa_aggregate_unpack(L, codes, scales, gbar), n_also)
+        also["aggregate_unpack"] = entry(avg, n_also, M / 4 + 4)
         del gbar          # stays in torch's cache (see the note on the gradient buffer above)
         # the paper's double quantization at bucket granularity, formed inside the same kernel
         if 0 < bucket <= 4096:
             rq = qa.QA_REQUANT_BUCKET
-            qa.qa_step_qcmd(L, codes, scales, x, G, z, eta, lam, delta, rq, None)
-            e0.record()
-            for _ in range(3):
-                qa.qa_step_qcmd(L, codes, scales, x, G, z, eta, lam, delta, rq, None)
-            e1.record()
-            torch.cuda.synchronize()
-            avg = e0.elapsed_time(e1) / 3
-            bpc = algorithmic_bytes_per_coord("qcmd_z", M)
-            also["qcmd_z_requant_bucket"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
-                                             "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+            avg = timed_launches(lambda: qa.qa_step_qcmd(L, codes, scales, x, G, z, eta, lam, delta, rq,
+                                                         None), n_also)
+            also["qcmd_z_requant_bucket"] = entry(avg, n_also, algorithmic_bytes_per_coord("qcmd_z", M))
             # the server's call alone: messages in, q_t = Q(SynQ_t) out as a one-worker message
             qc = torch.zeros((1, L.code_stride), dtype=torch.int32, device=dev)
             qs = torch.zeros((1, L.scale_stride), dtype=torch.float32, device=dev)
-            qa.qa_aggregate_quantize(L, codes, scales, rq, qc, qs, None, None)
-            e0.record()
-            for _ in range(3):
-                qa.qa_aggregate_quantize(L, codes, scales, rq, qc, qs, None, None)
-            e1.record()
-            torch.cuda.synchronize()
-            avg = e0.elapsed_time(e1) / 3
-            bpc = M / 4 + 0.25
-            also["aggregate_quantize_bucket"] = {"avg_ms": avg, "launches": 3, "bytes_per_coord": bpc,
-                                                 "achieved_GBps": bpc * d / (avg * 1e-3) / 1e9}
+            avg = timed_launches(lambda: qa.qa_aggregate_quantize(L, codes, scales, rq, qc, qs, None, None),
+                                 n_also)
+            also["aggregate_quantize_bucket"] = entry(avg, n_also, M / 4 + 0.25)
             del qc, qs
+
+    # ---- what this machine's memory system gives a plain copy: fp32 elementwise kernel with 128-bit
+    # accesses (torch's), min(d, 2^30) elements, 8 B moved per element ----
+    n_copy = min(d, 1 << 30)
+    src = torch.empty(n_copy, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    copy_ms = timed_launches(lambda: torch.mul(src, 1.0, out=dst), 10)
+    copy_gbps = 8.0 * n_copy / (copy_ms * 1e-3) / 1e9
+    del src, dst
 
     out = {
         "metric": "fused QCMD/QRDA step: coordinates/s and achieved HBM GB/s (% peak), 1 MI355X",
@@ -506,12 +506,21 @@ def main():
         "config": {"workload": f"{args.workload}: d={d}, M={M}, bucket={bucket}, "
                                f"{wl['gen']} gradients as packed 2-bit codes, schedule={wl['schedule']}, "
                                f"requant={wl.get('requant', 'none')}", "d": d, "M": M, "bucket": bucket,
-                   "code_pad_words": args.code_pad_words},
+                   "code_pad_words": args.code_pad_words,
+                   "messages": "one set of M quantized gradients, generated and quantized before the "
+                               "timed region, is re-used by every step (the step time depends on "
+                               "the values by about 2 %)"},
         "roofline": {"bound": "hbm", "kernel": f"step_lut_kernel[{dominant}]",
                      "achieved": dk["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dk["achieved_GBps"] / HBM_PEAK_GBPS,
                      "algorithmic_bytes": dk["bytes_per_coord"] * d,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dominant))},
+                     "traffic": PROFILED_TRAFFIC_BYTES.get((args.workload, dominant)),
+                     "traffic_source": (TRAFFIC_SOURCE + " (rocprofv3 --pmc runs of this command; "
+                                        "not measured in this run)"
+                                        if (args.workload, dominant) in PROFILED_TRAFFIC_BYTES else None),
+                     "copy_GBps": copy_gbps, "frac_of_copy": dk["achieved_GBps"] / copy_gbps,
+                     "copy_kernel": f"torch.mul(src, 1.0, out=dst), {n_copy} fp32, 8 B per element, "
+                                    f"{copy_ms:.3f} ms"},
         "kernels": kernels,
         "kernels_outside_timed_steps": also,
         "quantize_pack": {"ms_per_worker": quant_ms, "worker_coords_per_s": d / (quant_ms * 1e-3),
@@ -530,28 +539,45 @@ def main():
         "device": torch.cuda.get_device_name(0),
     }
 
-    # ---- CPU baseline: the oracle as it stands, one host thread, on a bounded sample ----
+    # ---- CPU baseline: the oracle as it stands, one host thread pinned to one core, on a
+    # bounded sample: the first ds coordinates of the same messages ----
     if not args.no_cpu_baseline:
         import oracle
-        ds = min(d, 1 << 22)                      # sampled coordinates: the first ds
+        ds = min(d, 1 << 22)
         Ws, nbs = ds // 16, (ds // bucket if bucket else 1)
         c_s = codes[:, :Ws].cpu().numpy().view(np.uint32).copy()
         s_s = scales[:, :nbs].cpu().numpy().copy()
         ox, oG, oz = (np.zeros(ds, np.float32) for _ in range(3))
         n_cpu = 30                                # about 15 s of one host core
         oracle.lib()
-        c0 = time.perf_counter()
-        for tt in range(1, n_cpu + 1):
-            if kind_of(tt) == "qrda":
-                oracle.step_qrda(c_s, s_s, ds, bucket, ox, oG, oz, tt, eta, lam, delta)
-            else:
-                oracle.step_qcmd(c_s, s_s, ds, bucket, ox, oG, oz if kind_of(tt) == "qcmd_z" else None,
-                                 eta, lam, delta, requant)
-        cpu_s = time.perf_counter() - c0
+        allowed = sorted(os.sched_getaffinity(0))
+        core = allowed[len(allowed) // 2]
+        os.sched_setaffinity(0, {core})
+        try:
+            c0 = time.perf_counter()
+            for tt in range(1, n_cpu + 1):
+                if kind_of(tt) == "qrda":
+                    oracle.step_qrda(c_s, s_s, ds, bucket, ox, oG, oz, tt, eta, lam, delta)
+                else:
+                    oracle.step_qcmd(c_s, s_s, ds, bucket, ox, oG, oz if kind_of(tt) == "qcmd_z" else None,
+                                     eta, lam, delta, requant)
+            cpu_s = time.perf_counter() - c0
+        finally:
+            os.sched_setaffinity(0, set(allowed))
+        model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                for line in f:
+                    if line.startswith("model name"):
+                        model = line.split(":", 1)[1].strip()
+                        break
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": ds * n_cpu / cpu_s, "unit": "coordinates/s", "cores": 1,
-                               "kind": "oracle",
-                               "sample": f"first {ds} coordinates (all {M} workers), {n_cpu} steps, "
-                                         f"{cpu_s:.1f} s"}
+                               "kind": "oracle", "cpu_model": model, "nproc": os.cpu_count(),
+                               "cpus_allowed": len(allowed), "pinned_to_core": core,
+                               "sample": f"first {ds} coordinates (all {M} workers), {n_cpu} steps of "
+                                         f"the timed schedule, {cpu_s:.1f} s"}
     print(json.dumps(out))
 
 

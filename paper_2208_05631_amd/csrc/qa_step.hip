@@ -9,6 +9,9 @@
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
 // The same kernel also takes its code words from sparse-encoded messages (expanded on the fly)
 // and, in aggregate mode with the second quantization, emits q_t as a coded message.
+#include <cmath>
+#include <cstring>
+
 #include "qa_segments.h"
 #include "qa_sparse.h"
 
@@ -30,6 +33,11 @@ struct StepArgs {
   float* x; float* G; float* z; float* gbar;
   double* abs_partials;   // aggregate mode, optional: sum of |gbar| of each tile (first pass of a quantizer)
   float eta, lam_eta, delta, t_lam, thr_coef;
+  // Tiles whose scales all have biased exponents in [fast_emin, fast_emax] (and pass the span
+  // test) may take the short forms of sqrt and division in the update: every numerator and
+  // denominator then lies where the full forms do no rescaling (set by set_fast_limits)
+  int fast_emin, fast_emax;
+  uint32_t fast_r_lo, fast_r_span;   // QRDA: bit patterns bounding the positive r = |z| - t*lambda
   SegTable seg;       // tensor-list launches: work-group = piece, one scale column per tensor
   // sparse-encoded messages (kernels with SPARSE): `codes` holds the compact per-bucket streams,
   // worker m's indicator words start at ind + m*ind_stride (stride 0: one indicator for all)
@@ -49,25 +57,98 @@ __device__ __forceinline__ uint32_t sanitize(uint32_t w) {
 }
 
 // Accumulator and closed-form update of one coordinate (equations Hq, QCMD, QRDA): binary32,
-// one rounding per operation, in this order.
+// one rounding per operation, in this order.  accumulate() forms the new G (and z), solve_x()
+// the new parameter from them.
 template <int MODE, bool TRACK_Z>
-__device__ __forceinline__ void update_coordinate(const StepArgs& a, float q, float& x, float& G,
-                                                  float& z) {
+__device__ __forceinline__ void accumulate(float q, float& G, float& z) {
   const float q2 = q * q;
   G = G + q2;
+  if (MODE == kQrda || TRACK_Z) z = z + q;
+}
+// G, z: the values after accumulate(); x: the parameter before the step (QCMD)
+template <int MODE>
+__device__ __forceinline__ float solve_x(const StepArgs& a, float q, float x, float G, float z) {
   const float H = a.delta + sqrtf(G);
   if (MODE == kQcmd) {
     const float step = (a.eta * q) / H;
     const float u = x - step;
     const float tau = a.lam_eta / H;
     const float r = fabsf(u) - tau;
-    x = r > 0.0f ? copysignf(r, u) : 0.0f;
-    if (TRACK_Z) z = z + q;
+    return r > 0.0f ? copysignf(r, u) : 0.0f;
   } else {
-    z = z + q;
     const float r = fabsf(z) - a.t_lam;
     const float mag = (a.eta * r) / H;
-    x = r > 0.0f ? -copysignf(mag, z) : 0.0f;
+    return r > 0.0f ? -copysignf(mag, z) : 0.0f;
+  }
+}
+template <int MODE, bool TRACK_Z>
+__device__ __forceinline__ void update_coordinate(const StepArgs& a, float q, float& x, float& G,
+                                                  float& z) {
+  accumulate<MODE, TRACK_Z>(q, G, z);
+  x = solve_x<MODE>(a, q, x, G, z);
+}
+
+// ---- short forms of the correctly rounded sqrt and division ----------------------------------
+//
+// The compiler expands binary32 sqrt and division into: rescale the operands if they lie near
+// the ends of the exponent range, a hardware estimate, fused corrections, undo the rescaling,
+// special values.  For operands well inside the range the rescaling steps do nothing, so the
+// same estimate and the same corrections alone give the same, correctly rounded, bits.  The
+// functions below are those cores; callers establish the ranges (per tile from the exponents
+// of the scales, per lane for what comes from the caller's state) and fall back to the full
+// forms otherwise.
+//
+//   sqrt_core(G)      : G == 0 or 2^-96 <= G < 2^126
+//   div_core(a, H, r) : r = recip_core(H), 2^-64 <= H < 2^64, a == 0 or 2^-62 <= |a| < 2^59 with
+//                       |a| / H < 2^95 (quotient and reciprocal normal, exponents < 96 apart)
+__device__ __forceinline__ float sqrt_core(float G) {
+  const float s = __builtin_amdgcn_sqrtf(G);            // within one ulp
+  const float down = __int_as_float(__float_as_int(s) - 1);
+  const float up = __int_as_float(__float_as_int(s) + 1);
+  const float r_down = __builtin_fmaf(-down, s, G);
+  const float r_up = __builtin_fmaf(-up, s, G);
+  float out = r_down <= 0.0f ? down : s;
+  out = r_up > 0.0f ? up : out;
+  return out;
+}
+__device__ __forceinline__ float recip_core(float H) {
+  const float r = __builtin_amdgcn_rcpf(H);
+  const float e = __builtin_fmaf(-H, r, 1.0f);
+  return __builtin_fmaf(e, r, r);
+}
+__device__ __forceinline__ float div_core(float a, float H, float r) {
+  const float q0 = a * r;
+  const float e0 = __builtin_fmaf(-H, q0, a);
+  const float q1 = __builtin_fmaf(e0, r, q0);
+  const float e1 = __builtin_fmaf(-H, q1, a);
+  return __builtin_fmaf(e1, r, q1);
+}
+
+constexpr uint32_t kBitsTwoToMinus96 = 0x0F800000u;
+constexpr uint32_t kBitsTwoTo126 = 0x7E800000u;
+
+// solve_x with the short forms.  `bad` is set when this lane's G (or, for QRDA, its positive r)
+// lies outside the ranges above: the caller then discards the result of the whole wave's group
+// and takes solve_x instead.
+template <int MODE>
+__device__ __forceinline__ float solve_x_core(const StepArgs& a, float q, float x, float G, float z,
+                                              bool& bad) {
+  const uint32_t gb = __float_as_uint(G);
+  bad |= (gb - 1u) < (kBitsTwoToMinus96 - 1u);           // 0 < G < 2^-96
+  bad |= gb >= kBitsTwoTo126;                           // huge, Inf, NaN, negative
+  const float H = a.delta + sqrt_core(G);
+  const float rcp = recip_core(H);
+  if (MODE == kQcmd) {
+    const float step = div_core(a.eta * q, H, rcp);
+    const float u = x - step;
+    const float tau = div_core(a.lam_eta, H, rcp);
+    const float r = fabsf(u) - tau;
+    return r > 0.0f ? copysignf(r, u) : 0.0f;
+  } else {
+    const float r = fabsf(z) - a.t_lam;
+    bad |= r > 0.0f && !((__float_as_uint(r) - a.fast_r_lo) < a.fast_r_span);
+    const float mag = div_core(a.eta * r, H, rcp);
+    return r > 0.0f ? -copysignf(mag, z) : 0.0f;
   }
 }
 
@@ -151,23 +232,50 @@ __device__ __forceinline__ void store_state(float* __restrict__ p, int64_t tile_
   }
 }
 
+// 8 * (byte R of v): the byte offset of a table entry, in one instruction (shift with a byte
+// select on its source).  `three` holds the shift count in a vector register.
+template <int R>
+__device__ __forceinline__ uint32_t byte_times_8(uint32_t v, uint32_t three) {
+  uint32_t out;
+  if constexpr (R == 0)
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0"
+        : "=v"(out) : "v"(three), "v"(v));
+  else if constexpr (R == 1)
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
+        : "=v"(out) : "v"(three), "v"(v));
+  else if constexpr (R == 2)
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2"
+        : "=v"(out) : "v"(three), "v"(v));
+  else
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3"
+        : "=v"(out) : "v"(three), "v"(v));
+  return out;
+}
+
 // One group of four workers: gather their codes per coordinate into bytes, look the partial
-// sums up, add.  Coordinate 4r+c of the thread's 16 sits in byte r of zq[c].
+// sums up, add.  Coordinate 4r+c of the thread's 16 sits in byte r of zq[c].  16 bit-field
+// merges for the gather (each a shift and a bit-field insert), then per coordinate one address
+// instruction, one LDS read and one binary64 addition.
 __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t wc, uint32_t wd,
                                              const double* __restrict__ T, double acc[16]) {
-  const uint32_t xe = (wa & 0x33333333u) | ((wb & 0x33333333u) << 2);
+  const uint32_t xe = (wa & 0x33333333u) | ((wb << 2) & 0xCCCCCCCCu);
   const uint32_t xo = ((wa >> 2) & 0x33333333u) | (wb & 0xCCCCCCCCu);
-  const uint32_t ye = (wc & 0x33333333u) | ((wd & 0x33333333u) << 2);
+  const uint32_t ye = (wc & 0x33333333u) | ((wd << 2) & 0xCCCCCCCCu);
   const uint32_t yo = ((wc >> 2) & 0x33333333u) | (wd & 0xCCCCCCCCu);
   uint32_t zq[4];
-  zq[0] = (xe & 0x0F0F0F0Fu) | ((ye & 0x0F0F0F0Fu) << 4);
-  zq[1] = (xo & 0x0F0F0F0Fu) | ((yo & 0x0F0F0F0Fu) << 4);
+  zq[0] = (xe & 0x0F0F0F0Fu) | ((ye << 4) & 0xF0F0F0F0u);
+  zq[1] = (xo & 0x0F0F0F0Fu) | ((yo << 4) & 0xF0F0F0F0u);
   zq[2] = ((xe >> 4) & 0x0F0F0F0Fu) | (ye & 0xF0F0F0F0u);
   zq[3] = ((xo >> 4) & 0x0F0F0F0Fu) | (yo & 0xF0F0F0F0u);
+  const uint32_t three = 3u;
+  const char* Tb = reinterpret_cast<const char*>(T);
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[4 * r + c] += T[(zq[c] >> (8 * r)) & 0xFFu];
+  for (int c = 0; c < 4; ++c) {
+    acc[c] += *reinterpret_cast<const double*>(Tb + byte_times_8<0>(zq[c], three));
+    acc[4 + c] += *reinterpret_cast<const double*>(Tb + byte_times_8<1>(zq[c], three));
+    acc[8 + c] += *reinterpret_cast<const double*>(Tb + byte_times_8<2>(zq[c], three));
+    acc[12 + c] += *reinterpret_cast<const double*>(Tb + byte_times_8<3>(zq[c], three));
+  }
 }
 
 // Workers are taken in chunks of 4*G (G groups of four, one table per group).
@@ -265,6 +373,8 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     bad |= lds_e[2 * kWaves + v];
   }
   const bool reorder_ok = !bad && (emax - emin) <= a.span_limit;
+  // may the update use the short sqrt / division? (decided here so that emin, emax die early)
+  const bool try_core = reorder_ok && emin >= a.fast_emin && emax <= a.fast_emax;
 
   double acc[16];
 #pragma unroll
@@ -423,7 +533,9 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   if (MODE != kAggregate) {
     load_state(a.G, tile_base, lo, hi, full_tile, sG);
     if (MODE == kQcmd) load_state(a.x, tile_base, lo, hi, full_tile, sx);
-    if (MODE == kQrda || TRACK_Z) load_state(a.z, tile_base, lo, hi, full_tile, sz);
+    // with the second quantization still to come, z (needed last) is requested after it
+    if ((MODE == kQrda || TRACK_Z) && !(REQUANT && MODE == kQcmd))
+      load_state(a.z, tile_base, lo, hi, full_tile, sz);
   }
 
   float q[16];
@@ -494,6 +606,8 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
   }
 
+  if (REQUANT && MODE == kQcmd && TRACK_Z) load_state(a.z, tile_base, lo, hi, full_tile, sz);
+
   // ---- hand q over through LDS to the float4 mapping of the state loads ----
   float* qt = reinterpret_cast<float*>(tab);
   __syncthreads();
@@ -503,17 +617,30 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
         make_float4(q[4 * v], q[4 * v + 1], q[4 * v + 2], q[4 * v + 3]);
   __syncthreads();
   if (full_tile && MODE != kAggregate) {
-    // whole tile: each float4 group is updated and stored as soon as its q is read back
+    // whole tile: each float4 group is updated and stored as soon as its q is read back.
+    // Tiles whose scales lie in the safe exponent range try the short sqrt / division first;
+    // a group in which any lane of the wave leaves the safe range is redone in full.
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float4 qv = *reinterpret_cast<const float4*>(qt + 4 * (j * kThreads + t));
       const float qq[4] = {qv.x, qv.y, qv.z, qv.w};
       float G[4] = {sG.v[j].x, sG.v[j].y, sG.v[j].z, sG.v[j].w};
-      float x[4] = {0.f, 0.f, 0.f, 0.f}, z[4] = {0.f, 0.f, 0.f, 0.f};
-      if (MODE == kQcmd) { x[0] = sx.v[j].x; x[1] = sx.v[j].y; x[2] = sx.v[j].z; x[3] = sx.v[j].w; }
+      float x0[4] = {0.f, 0.f, 0.f, 0.f}, z[4] = {0.f, 0.f, 0.f, 0.f}, x[4];
+      if (MODE == kQcmd) { x0[0] = sx.v[j].x; x0[1] = sx.v[j].y; x0[2] = sx.v[j].z; x0[3] = sx.v[j].w; }
       if (MODE == kQrda || TRACK_Z) { z[0] = sz.v[j].x; z[1] = sz.v[j].y; z[2] = sz.v[j].z; z[3] = sz.v[j].w; }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) update_coordinate<MODE, TRACK_Z>(a, qq[e], x[e], G[e], z[e]);
+      for (int e = 0; e < 4; ++e) accumulate<MODE, TRACK_Z>(qq[e], G[e], z[e]);
+      bool done = false;
+      if (try_core) {
+        bool bad = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = solve_x_core<MODE>(a, qq[e], x0[e], G[e], z[e], bad);
+        done = !__any(bad);                               // uniform over the wave
+      }
+      if (!done) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = solve_x<MODE>(a, qq[e], x0[e], G[e], z[e]);
+      }
       const int64_t i = tile_base + (int64_t)(j * kThreads + t) * 4;
       stream_store4(a.G + i, make_float4(G[0], G[1], G[2], G[3]));
       stream_store4(a.x + i, make_float4(x[0], x[1], x[2], x[3]));
@@ -606,6 +733,26 @@ static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float
   a.span_limit = 29 - ilog2(L->M);
   a.tile_uniform = (L->bucket == 0 || L->bucket >= kTile) ? 1 : 0;
   return a;
+}
+
+// Which tiles may use the short sqrt / division of the update (see sqrt_core / div_core): the
+// numerators eta*q and lambda*eta (QCMD) or eta*r (QRDA) and the denominator H = delta + sqrt(G)
+// must lie where the full division does no rescaling.  With |q| between 2^(emin-150)/M and
+// 2^(emax-126) for a tile whose non-zero scales have biased exponents emin..emax, that becomes a
+// window on (emin, emax), and for QRDA a window on the positive r, checked per lane.
+static void set_fast_limits(StepArgs& a, int mode, float eta, float lam_eta, float delta) {
+  a.fast_emin = 1 << 20; a.fast_emax = -1;               // no tile qualifies
+  if (!(delta >= 0x1p-64f && delta <= 0x1p63f)) return;
+  if (!(eta >= 0x1p-40f && eta <= 0x1p40f)) return;
+  const int le = ilogbf(eta), ld = ilogbf(delta);
+  const int hi = 93 + ld < 59 ? 93 + ld : 59;            // numerators stay below 2^hi
+  if (mode == kQcmd && lam_eta != 0.0f && !(lam_eta >= 0x1p-61f && lam_eta < ldexpf(1.0f, hi))) return;
+  a.fast_emin = -61 - le + 150 + ilog2(a.M);
+  a.fast_emax = hi - le - 2 + 126;
+  const float r_lo = ldexpf(1.0f, -61 - le), r_hi = ldexpf(1.0f, hi - le - 1);
+  uint32_t lo_bits, hi_bits;
+  memcpy(&lo_bits, &r_lo, 4); memcpy(&hi_bits, &r_hi, 4);
+  a.fast_r_lo = lo_bits; a.fast_r_span = hi_bits - lo_bits;
 }
 
 template <int MODE, bool TRACK_Z, bool REQUANT, int NGT, bool SPARSE = false>
@@ -709,6 +856,7 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
   a.x = x; a.G = G; a.z = z;
   a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta;
   a.t_lam = (float)t * lambda;
+  set_fast_limits(a, mode, eta, a.lam_eta, delta);
   if (mode == kQcmd) launch_mode<kQcmd>(a, track_z, fused_requant, stream);
   else launch_mode<kQrda>(a, false, fused_requant, stream);
   return launch_status();
@@ -816,6 +964,7 @@ static int step_segments_common(int mode, const qa_layout* L, const qa_segment_p
   a.x = x; a.G = G; a.z = z;
   a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta;
   a.t_lam = (float)t * lambda;
+  set_fast_limits(a, mode, eta, a.lam_eta, delta);
   if (mode == kQcmd) launch_mode<kQcmd>(a, track_z, false, stream);
   else launch_mode<kQrda>(a, false, false, stream);
   return launch_status();

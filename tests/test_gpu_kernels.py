@@ -257,6 +257,51 @@ def test_fused_steps_match_oracle_over_several_steps(d, M, bucket, requant):
         "within tolerance but not bit-identical"
 
 
+@pytest.mark.parametrize("method", ["qcmd", "qcmd_z", "qrda"])
+@pytest.mark.parametrize("requant", [0, 1])
+def test_update_with_state_and_scalars_at_the_ends_of_the_exponent_range(method, requant):
+    """For tiles whose scales lie in a safe exponent window the kernel takes short forms of the
+    correctly rounded sqrt and division, and falls back to the full forms for any group of lanes
+    whose accumulator (or, for QRDA, |z| - t*lambda) leaves the window.  State planted with tiny,
+    huge, zero, negative-zero and non-finite values next to ordinary ones, and hyper-parameters
+    inside and outside the window, must all give the oracle's bits."""
+    d, M, bucket = 5 * 4096, 16, 4096
+    rng = np.random.default_rng(404)
+    g = make_grad("laplace_sparse", M, d, seed=5)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
+    L = qa.Layout.make(d, M, bucket)
+    pool = np.array([0.0, -0.0, 1e-45, 1e-40, 3e-39, 1e-35, 1e-30, 1.2e-29, 1.3e-29, 1e-20, 1e-6, 1.0,
+                     1e20, 8e37, 9e37, 3e38, np.inf, np.nan], np.float32)
+    for case, (eta, lam, delta, t) in enumerate([(0.1, 2e-4, 1e-8, 3), (0.1, 0.0, 1e-8, 1),
+                                                 (1e-20, 1e-3, 1e-8, 2), (0.1, 2e-4, 1e-30, 5),
+                                                 (3e3, 1e-38, 1e10, 7), (0.1, 1e30, 1e-8, 4)]):
+        x0 = (rng.standard_normal(d) * 1e-2 * (rng.random(d) < 0.5)).astype(np.float32)
+        G0 = (rng.random(d) * 1e-5).astype(np.float32)
+        z0 = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+        where = rng.random(d) < 0.02                       # a few lanes per wave
+        G0[where] = np.abs(rng.choice(pool, int(where.sum())))
+        where = rng.random(d) < 0.02
+        z0[where] = rng.choice(pool, int(where.sum())) * rng.choice([-1, 1], int(where.sum()))
+        tl = np.float32(t) * np.float32(lam)
+        where = rng.random(d) < 0.02                       # |z| - t*lambda just above / below zero
+        z0[where] = (tl * (1 + rng.integers(-3, 4, int(where.sum())) * 2.0 ** -23)).astype(np.float32)
+        where = rng.random(d) < 0.01
+        x0[where] = rng.choice(pool, int(where.sum())) * rng.choice([-1, 1], int(where.sum()))
+        ox, oG, oz = x0.copy(), G0.copy(), z0.copy()
+        st = GpuState(L, oc, osc, x0, G0, z0)
+        if method == "qrda":
+            oracle.step_qrda(oc, osc, d, bucket, ox, oG, oz, t, eta, lam, delta, requant)
+            st.qrda(t, eta, lam, delta, requant)
+        else:
+            tz = method == "qcmd_z"
+            oracle.step_qcmd(oc, osc, d, bucket, ox, oG, oz if tz else None, eta, lam, delta, requant)
+            st.qcmd(eta, lam, delta, requant, track_z=tz)
+        x, G, z = st.get()
+        for name, a, o in (("x", x, ox), ("G", G, oG), ("z", z, oz)):
+            same = (a.view(np.uint32) == o.view(np.uint32)) | (np.isnan(a) & np.isnan(o))
+            assert same.all(), (case, name, int((~same).sum()), a[~same][:4], o[~same][:4])
+
+
 def test_qcmd_without_z_leaves_z_alone():
     d, M, b = 9000, 4, 4096
     g = make_grad("gauss", M, d, 77)
