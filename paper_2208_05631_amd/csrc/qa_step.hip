@@ -252,16 +252,29 @@ __device__ __forceinline__ uint32_t byte_times_8(uint32_t v, uint32_t three) {
   return out;
 }
 
-// One group of four workers: gather their codes per coordinate into bytes, look the partial
-// sums up, add.  Coordinate 4r+c of the thread's 16 sits in byte r of zq[c].  16 bit-field
-// merges for the gather (each a shift and a bit-field insert), then per coordinate one address
-// instruction, one LDS read and one binary64 addition.
+// One group of four workers a, b, c, d: gather their codes per coordinate into bytes, look the
+// partial sums up, add.  Coordinate 4r+c of the thread's 16 sits in byte r of zq[c].
+//
+// Index byte of a coordinate: bits 0..3 = "non-zero" bits (low code bits) of a, b, c, d,
+// bits 4..7 = their "negative" bits (high code bits).  With 8-byte entries the LDS bank of an
+// entry is chosen by the low five index bits, so the all-zero entry and the eight entries with a
+// single non-zero worker (the bulk of the look-ups when codes are sparse) lie in different banks,
+// except +c/-c and +d/-d which pair up.  With the four 2-bit codes side by side instead, every
+// entry of worker d alone would share its bank with the all-zero entry that most lanes read.
+// Cost: 8 merges that split the words into low-bit and high-bit pairs, then the 16 merges of a
+// 4 x 2-bit gather; then per coordinate one address instruction, one LDS read and one binary64
+// addition.
 __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t wc, uint32_t wd,
                                              const double* __restrict__ T, double acc[16]) {
-  const uint32_t xe = (wa & 0x33333333u) | ((wb << 2) & 0xCCCCCCCCu);
-  const uint32_t xo = ((wa >> 2) & 0x33333333u) | (wb & 0xCCCCCCCCu);
-  const uint32_t ye = (wc & 0x33333333u) | ((wd << 2) & 0xCCCCCCCCu);
-  const uint32_t yo = ((wc >> 2) & 0x33333333u) | (wd & 0xCCCCCCCCu);
+  // field i (bits 2i, 2i+1) of p0 = low bits of (a, b) for coordinate i; p1: (c, d); p2, p3: high bits
+  const uint32_t p0 = (wa & 0x55555555u) | ((wb << 1) & 0xAAAAAAAAu);
+  const uint32_t p1 = (wc & 0x55555555u) | ((wd << 1) & 0xAAAAAAAAu);
+  const uint32_t p2 = ((wa >> 1) & 0x55555555u) | (wb & 0xAAAAAAAAu);
+  const uint32_t p3 = ((wc >> 1) & 0x55555555u) | (wd & 0xAAAAAAAAu);
+  const uint32_t xe = (p0 & 0x33333333u) | ((p1 << 2) & 0xCCCCCCCCu);
+  const uint32_t xo = ((p0 >> 2) & 0x33333333u) | (p1 & 0xCCCCCCCCu);
+  const uint32_t ye = (p2 & 0x33333333u) | ((p3 << 2) & 0xCCCCCCCCu);
+  const uint32_t yo = ((p2 >> 2) & 0x33333333u) | (p3 & 0xCCCCCCCCu);
   uint32_t zq[4];
   zq[0] = (xe & 0x0F0F0F0Fu) | ((ye << 4) & 0xF0F0F0F0u);
   zq[1] = (xo & 0x0F0F0F0Fu) | ((yo << 4) & 0xF0F0F0F0u);
@@ -380,13 +393,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 #pragma unroll
   for (int j = 0; j < 16; ++j) acc[j] = 0.0;
 
-  // decoded values of the four 2-bit fields of byte t (reserved pattern 10 -> 0)
+  // decoded codes of the four workers for index byte t (see lookup_group): bit j = non-zero,
+  // bit 4+j = negative; the reserved pattern (negative without non-zero) reads as 0
   double dj[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int f = (t >> (2 * j)) & 3;
-    dj[j] = f == 1 ? 1.0 : (f == 3 ? -1.0 : 0.0);
-  }
+  for (int j = 0; j < 4; ++j) dj[j] = ((t >> j) & 1) ? (((t >> (4 + j)) & 1) ? -1.0 : 1.0) : 0.0;
   // tables of the chunk that starts at worker m0, then the look-ups of its code words wc
   auto chunk = [&](const uint32_t (&wc)[kChunk], int m0) {
     const int left = a.M - m0;
