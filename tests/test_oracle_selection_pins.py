@@ -52,7 +52,10 @@ def test_indicator_follows_its_definition_through_the_pinned_updates(method):
     assert int(ind[-1]) >> (d % 32) == 0                          # unused bits stay zero
 
 
-@pytest.mark.parametrize("d,bucket", [(1000, 0), (1000, 256), (9000, 4096), (4096, 4096)])
+@pytest.mark.parametrize("d,bucket", [(1000, 0), (1000, 256), (9000, 4096), (4096, 4096),
+                                      # one scale for a message of many tiles; buckets below and
+                                      # above a 4096-tile on a ragged length
+                                      (70001, 0), (70001, 64), (70001, 2048), (70001, 16384)])
 def test_quantize_selected_is_the_quantizer_on_the_compacted_vector(d, bucket):
     rng = np.random.default_rng(d + bucket)
     g = rng.standard_normal(d).astype(np.float32)
@@ -100,7 +103,8 @@ def test_indicator_or():
     assert np.array_equal(oracle.indicator_or(ind, 320), np.bitwise_or.reduce(ind, axis=0))
 
 
-@pytest.mark.parametrize("d,bucket", [(37, 0), (1000, 256), (9000, 4096)])
+@pytest.mark.parametrize("d,bucket", [(37, 0), (1000, 256), (9000, 4096), (70001, 0), (70001, 512),
+                                      (70001, 8192)])
 def test_select_codes_is_numpy_compaction_and_inverts_under_decode(d, bucket):
     """S(q, I) on a coded message: the marked components' codes in index order (numpy boolean
     indexing is the definition), per bucket; decode puts them back, zeros elsewhere."""
@@ -132,3 +136,33 @@ def test_select_codes_is_numpy_compaction_and_inverts_under_decode(d, bucket):
     ind2[0] |= np.uint32(1)
     sel2, _ = oracle.select_codes(dense2, ind2, d, bucket=bucket)
     assert oracle.unpack(sel2, 1)[0] == 0
+
+
+def test_one_scale_message_of_a_long_vector_has_32_plus_d_plus_2k_bits():
+    """Encode paragraph of Section 3.5 for a sparse model: one float, d indicator bits and two
+    bits for each of the k selected components, for a vector much longer than any tile.  The
+    selected codes form ONE stream of 2k bits from bit 0 of the message's code area; nothing
+    beyond it is written; the threshold's length is k."""
+    rng = np.random.default_rng(12)
+    d = 50000
+    g = (rng.standard_normal(d) * 1e-2).astype(np.float32)
+    mask = rng.random(d) < 0.07
+    ind = np.zeros(oracle.n_ind_words(d), np.uint32)
+    for i in np.nonzero(mask)[0]:
+        ind[i // 32] |= np.uint32(1 << (i % 32))
+    k = int(mask.sum())
+    sel, cnt, sc, th = oracle.quantize_selected(g, ind, bucket=0)
+    assert cnt.shape == (1,) and sc.shape == (1,) and int(cnt[0]) == k
+    nw = (k + 15) // 16
+    assert not sel[nw:].any()                                     # 2k bits and nothing else
+    assert (int(sel[nw - 1]) >> (2 * (k % 16))) == 0 or k % 16 == 0   # unused bits of the last word
+    v = g[mask]
+    assert th[0] == np.float32(0.75 * np.abs(v.astype(np.float64)).sum() / k)
+    kept = np.abs(v) > th[0]
+    assert sc[0] == np.float32(np.abs(v[kept].astype(np.float64)).sum() / kept.sum())
+    want = np.where(v > th[0], 1, np.where(v < -th[0], -1, 0)).astype(np.int8)
+    assert np.array_equal(oracle.unpack(sel, k), want)
+    bits = 32 + d + 2 * k
+    assert bits == 32 * sc.size + 32 * ind.size - (32 * ind.size - d) + 2 * int(cnt.sum())
+    # the dense message of the same vector costs 32 + 2d bits: the sparse one is smaller iff k < d/2
+    assert bits < 32 + 2 * d
