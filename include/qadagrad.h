@@ -75,6 +75,8 @@ extern "C" {
 #define QA_OP_STEP 2
 #define QA_OP_GRAD_CSR 3
 #define QA_OP_GRAD_DENSE 4
+#define QA_OP_SELECT 5        /* qa_quantize_pack_selected, qa_decode_selected, qa_select_codes   */
+#define QA_OP_STEP_SELECTED 6 /* qa_step_*_selected, qa_aggregate_quantize_selected               */
 
 /* data formats of qa_local_grad */
 #define QA_DENSE 0
@@ -241,7 +243,23 @@ int qa_step_qrda(const qa_layout* layout, const uint32_t* codes, const float* sc
  * A worker sends only the components of its gradient whose parameter is, or would become,
  * non-zero, plus one bit per coordinate saying which ones.  The indicator of worker m is
  * ind[m*ind_stride + i/32], bit i%32; unused bits of the last word are 0.
- * These calls require bucket == 4096, or bucket == 0 with d <= 4096 (QA_ERR_UNSUPPORTED otherwise).
+ *
+ * Sparse message of worker m, for every bucket size the layout allows: bucket k (coordinates
+ * [k*b, min((k+1)*b, d)), b = bucket, or the whole vector for bucket == 0) owns the area of
+ * ceil(b/16) words that starts at sel_codes[m*code_stride + k*ceil(b/16)]; the codes of its
+ * marked components, in index order, are packed from bit 0 of that area; counts[m*scale_stride + k]
+ * says how many there are, scales[m*scale_stride + k] is their scale.  Only the first
+ * ceil(count/16) words of an area are meaningful (and written).  With bucket == 0 this is the
+ * paper's message: one float, d indicator bits and 2k code bits in one stream.
+ *
+ * Buckets of 4096 (and a vector of at most 4096 coordinates with one scale) are served by
+ * kernels that work tile by tile and need no workspace; the steps read such messages directly.
+ * Buckets of 64 .. 2048 need none either.  Buckets above 4096 and one scale for a longer vector
+ * span several tiles: every call first counts the marked components of each tile and scans the
+ * counts (qa_workspace_bytes(layout, QA_OP_SELECT) bytes of workspace), and a bucket may hold
+ * fewer than 2^32 coordinates (QA_ERR_UNSUPPORTED otherwise).  For all sizes other than 4096 the
+ * steps on sparse messages decode into the workspace first and then take the dense path
+ * (qa_workspace_bytes(layout, QA_OP_STEP_SELECTED) bytes).
  */
 #define QA_METHOD_QCMD 0
 #define QA_METHOD_QRDA 1
@@ -261,32 +279,38 @@ int qa_indicator_or(const qa_layout* layout, const uint32_t* ind, int64_t ind_st
 
 /* Q(S(g, I)) for M workers: in every bucket k the marked components, in index order, form a
  * vector of length counts[m*scale_stride + k]; threshold (with that length as n), scale and
- * ternary codes as in qa_quantize_pack; its codes are packed from bit 0 of word
- * sel_codes[m*code_stride + k*256].  Only the first ceil(count/16) words of a bucket's 256-word
- * area are written (unused bits of the last one are 0), the rest is left untouched: the message
- * of a bucket is 32 + 4096 + 2*count bits.  count == 0 gives scale 0, threshold 0, no codes.
- * thresholds may be NULL. */
+ * ternary codes as in qa_quantize_pack; its codes are packed from bit 0 of the bucket's area.
+ * Only the first ceil(count/16) words of an area are written (unused bits of the last one
+ * are 0), the rest is left untouched: the message
+ * of a bucket is 32 + b + 2*count bits.  count == 0 gives scale 0, threshold 0, no codes.
+ * thresholds may be NULL.  ws: qa_workspace_bytes(layout, QA_OP_SELECT) (0 bytes, ws may be NULL,
+ * unless buckets span several tiles). */
 int qa_quantize_pack_selected(const qa_layout* layout, const float* g, int64_t g_stride,
                               const uint32_t* ind, int64_t ind_stride, uint32_t* sel_codes,
-                              uint32_t* counts, float* scales, float* thresholds, void* stream);
+                              uint32_t* counts, float* scales, float* thresholds, void* ws,
+                              size_t ws_bytes, void* stream);
 
 /* S^{-1} (Algorithm 1, server: "Decode ... to get Q(g^(m))"): writes the dense 2-bit codes of
  * qa_layout for all M workers, codes_out[m*code_stride + w], w < ceil(d/16): the j-th marked
  * component of a bucket gets the j-th code of its area, unmarked components get 0.  With the
- * scales from qa_quantize_pack_selected the result feeds qa_aggregate_unpack / qa_step_*. */
+ * scales from qa_quantize_pack_selected the result feeds qa_aggregate_unpack / qa_step_*.
+ * ind_stride = 0 applies one indicator to all M messages.  ws as for qa_quantize_pack_selected. */
 int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
-                       const uint32_t* sel_codes, uint32_t* codes_out, void* stream);
+                       const uint32_t* sel_codes, uint32_t* codes_out, void* ws, size_t ws_bytes,
+                       void* stream);
 
 /* S applied to coded messages (Algorithm 1, server: "Push S(q_t, I^Syn) and I^Syn to every
  * worker"): for each of the M messages codes[m*code_stride + w] (dense 2-bit layout, e.g. the
  * one-worker message that qa_aggregate_unpack followed by qa_quantize_pack produces for q_t), the
  * codes of the marked components, in index order, are packed per bucket exactly like the output of
- * qa_quantize_pack_selected: from bit 0 of word sel_codes[m*code_stride + k*256], only the first
- * ceil(count/16) words of an area are written; counts[m*scale_stride + k] = marked components of
- * bucket k.  ind_stride = 0 applies the same indicator (the synchronous one) to every message.
- * qa_decode_selected is the inverse on the marked components.  Not in place. */
+ * qa_quantize_pack_selected: from bit 0 of the bucket's area, only the first ceil(count/16) words
+ * of an area are written; counts[m*scale_stride + k] = marked components of bucket k.
+ * ind_stride = 0 applies the same indicator (the synchronous one) to every message.
+ * qa_decode_selected is the inverse on the marked components.  Not in place.  ws as for
+ * qa_quantize_pack_selected. */
 int qa_select_codes(const qa_layout* layout, const uint32_t* codes, const uint32_t* ind,
-                    int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts, void* stream);
+                    int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts, void* ws,
+                    size_t ws_bytes, void* stream);
 
 /* The fused steps on sparse-encoded messages (Algorithm 1: the server's "Decode" followed by
  * SynQ_t and the update; on a worker, the update from the pushed S(q_t, I^Syn) with M = 1):
@@ -294,8 +318,10 @@ int qa_select_codes(const qa_layout* layout, const uint32_t* codes, const uint32
  * it, without that buffer.  ind / ind_stride / sel_codes as for qa_decode_selected, scales as
  * written by qa_quantize_pack_selected; ind_stride = 0 applies one indicator to all M messages.
  * Only the first ceil(count/16) words of a bucket's area are read, count = marked components of
- * the bucket.  Everything else (arguments, requant, workspace of QA_OP_STEP, errors) as for
- * the dense steps; bucket restrictions as for the other calls of this group. */
+ * the bucket.  Everything else (arguments, requant, errors) as for the dense steps.
+ * ws: qa_workspace_bytes(layout, QA_OP_STEP_SELECTED); with buckets of 4096 that is the dense
+ * steps' workspace (the kernel expands the messages itself), otherwise it also holds the decoded
+ * code words of all M messages. */
 int qa_step_qcmd_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
                           const uint32_t* sel_codes, const float* scales, float* x, float* G,
                           float* z_or_null, float eta, float lambda, float delta, int requant,

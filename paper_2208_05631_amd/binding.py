@@ -17,6 +17,7 @@ QA_REQUANT_NONE, QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL = 0, 1, 2
 QA_THRESH_GIVEN = 1
 QA_THRESH_EXACT = 2
 QA_OP_QUANTIZE, QA_OP_STEP, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE = 1, 2, 3, 4
+QA_OP_SELECT, QA_OP_STEP_SELECTED = 5, 6
 QA_DENSE, QA_CSR = 0, 1
 QA_METHOD_QCMD, QA_METHOD_QRDA = 0, 1
 
@@ -86,8 +87,8 @@ _lib.qa_indicator.argtypes = [C.POINTER(Layout), C.c_int, _vp, C.c_int64, _vp, _
                               C.c_float, C.c_float, C.c_float, _vp, C.c_int64, _vp]
 _lib.qa_indicator_or.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp]
 _lib.qa_quantize_pack_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, C.c_int64, _vp, _vp,
-                                           _vp, _vp, _vp]
-_lib.qa_decode_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp]
+                                           _vp, _vp, _vp, _sz, _vp]
+_lib.qa_decode_selected.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, _vp, _sz, _vp]
 _lib.qa_quantize_pack_stochastic.argtypes = [C.POINTER(Layout), _vp, C.c_int64, _vp, _vp, C.c_uint64,
                                              C.c_uint32, _vp]
 _lib.qa_segment_plan_bytes.restype = _sz
@@ -185,15 +186,16 @@ def qa_indicator_or(layout, ind, ind_stride, ind_syn_out, stream=None):
 
 
 def qa_quantize_pack_selected(layout, g, g_stride, ind, ind_stride, sel_codes, counts, scales,
-                              thresholds, stream=None):
+                              thresholds, ws=None, stream=None):
     _check(_lib.qa_quantize_pack_selected(C.byref(layout), _p(g), g_stride, _p(ind), ind_stride,
                                           _p(sel_codes), _p(counts), _p(scales), _p(thresholds),
-                                          _stream(stream)), "qa_quantize_pack_selected")
+                                          _p(ws), _nbytes(ws), _stream(stream)),
+           "qa_quantize_pack_selected")
 
 
-def qa_decode_selected(layout, ind, ind_stride, sel_codes, codes_out, stream=None):
+def qa_decode_selected(layout, ind, ind_stride, sel_codes, codes_out, ws=None, stream=None):
     _check(_lib.qa_decode_selected(C.byref(layout), _p(ind), ind_stride, _p(sel_codes), _p(codes_out),
-                                   _stream(stream)), "qa_decode_selected")
+                                   _p(ws), _nbytes(ws), _stream(stream)), "qa_decode_selected")
 
 
 def qa_quantize_pack_stochastic(layout, g, g_stride, codes, scales, seed, step, stream=None):
@@ -253,10 +255,10 @@ def qa_step_qrda_segments(layout, plan, codes, scales, x, G, z, t, eta, lam, del
                                       _stream(stream)), "qa_step_qrda_segments")
 
 
-def qa_select_codes(layout, codes, ind, ind_stride, sel_codes, counts, stream=None):
-    _lib.qa_select_codes.argtypes = [C.POINTER(Layout), _vp, _vp, C.c_int64, _vp, _vp, _vp]
+def qa_select_codes(layout, codes, ind, ind_stride, sel_codes, counts, ws=None, stream=None):
+    _lib.qa_select_codes.argtypes = [C.POINTER(Layout), _vp, _vp, C.c_int64, _vp, _vp, _vp, _sz, _vp]
     _check(_lib.qa_select_codes(C.byref(layout), _p(codes), _p(ind), ind_stride, _p(sel_codes),
-                                _p(counts), _stream(stream)), "qa_select_codes")
+                                _p(counts), _p(ws), _nbytes(ws), _stream(stream)), "qa_select_codes")
 
 
 def qa_step_qcmd_selected(layout, ind, ind_stride, sel_codes, scales, x, G, z_or_null, eta, lam, delta,

@@ -4,6 +4,8 @@
 namespace qa {
 size_t quantize_workspace_bytes(const qa_layout* L);
 size_t step_workspace_bytes(const qa_layout* L);
+size_t select_workspace_bytes(const qa_layout* L);
+size_t step_selected_workspace_bytes(const qa_layout* L);
 size_t grad_workspace_bytes(int64_t d, bool csr);
 }  // namespace qa
 
@@ -32,5 +34,7 @@ extern "C" size_t qa_workspace_bytes(const qa_layout* layout, int op) {
   if (check_layout(layout) != QA_OK) return 0;
   if (op == QA_OP_QUANTIZE) return quantize_workspace_bytes(layout);
   if (op == QA_OP_STEP) return step_workspace_bytes(layout);
+  if (op == QA_OP_SELECT) return select_workspace_bytes(layout);
+  if (op == QA_OP_STEP_SELECTED) return step_selected_workspace_bytes(layout);
   return 0;
 }

@@ -21,10 +21,15 @@ struct SelArgs {
   const float* x; const float* G; const float* z;
   uint32_t* ind; const uint32_t* ind_in; int64_t ind_stride;
   uint32_t* sel_codes; const uint32_t* sel_in; uint32_t* dense; int64_t code_stride;
+  int64_t dense_stride;        // words between workers in `dense` (the decoder's output)
   uint32_t* counts; float* scales; float* thresholds; int64_t scale_stride;
   int64_t d, W, NW;            // coordinates, dense code words, indicator words
   int M, method;
   float eta, lam_eta, delta, t_lam, thr_coef;
+  // buckets other than one 4096-tile (the general kernels below)
+  int seg;                     // threads per bucket inside a tile: bucket/16 for 64 <= bucket <= 4096
+  int64_t nb, ntiles, tiles_per_bucket, area_words;   // buckets spanning several tiles
+  uint32_t* ws_count; double* ws_s1; double* ws_s2; uint32_t* ws_c2; int64_t* ws_start; float* ws_thr;
 };
 
 // The worker's own would-be parameter from gradient component g (same operation order as the
@@ -338,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void decode_selected_kernel(SelArgs a) {
         win >>= 2 * __popc(nib);
       }
       const int64_t w = (tile0 + u) * kTileWords + j * 64 + lane;
-      if (w < a.W) (a.dense + (int64_t)m * a.code_stride)[w] = out;
+      if (w < a.W) (a.dense + (int64_t)m * a.dense_stride)[w] = out;
     }
 }
 
@@ -423,12 +428,366 @@ __global__ __launch_bounds__(kThreads) void select_codes_kernel(SelArgs a) {
   }
 }
 
+// ---- any bucket size -------------------------------------------------------------------------
+//
+// The kernels above are specialised for one threshold/scale per 4096-tile.  The general ones
+// below take every other granularity of the layout, in the plain mapping "thread t = code word t
+// of the tile" (16 coordinates), and are not tuned:
+//   * buckets of 64 .. 2048 coordinates lie inside a tile: bucket j of a tile is the segment of
+//     seg = bucket/16 consecutive threads, its compact stream starts at word j*seg of the tile's
+//     256 words, and a thread's codes start at (selected components of its bucket before it);
+//   * buckets above 4096, and one scale for a vector of several tiles (the 32 + d + 2k bit
+//     message of the Encode paragraph), span tiles: a first pass counts every tile's selected
+//     components, a scan per bucket turns the counts into each tile's first position in the
+//     bucket's stream (kept in the workspace), and the tiles then place or fetch their codes
+//     there.  Neighbouring tiles share stream words, so producers OR their part into words that
+//     a small kernel has zeroed first.
+
+// the 16 indicator bits of the thread's coordinates, without those at or beyond d
+__device__ __forceinline__ uint32_t live_mask16(const SelArgs& a, const uint32_t* ind, int64_t tile, int t) {
+  const int64_t left = a.d - (tile * kTile + 16 * (int64_t)t);
+  const uint32_t m = mask16_of(ind, a.NW, tile, t);
+  return left >= 16 ? m : (left > 0 ? (m & ((1u << left) - 1u)) : 0u);
+}
+
+// Where the thread's selected codes sit: `pos` counts 2-bit codes from bit 0 of word `base[0]`.
+struct StreamPos {
+  int64_t base;        // word offset into the worker's sel_codes row (the same for the whole tile)
+  uint32_t pos;        // this thread's first selected code
+  uint32_t in_bucket;  // selected components of the thread's bucket (tile-local buckets only)
+  uint32_t in_tile;    // selected components of the tile
+  uint32_t first;      // position of the tile's first selected code (multi-tile: start % 16)
+};
+
+// n = number of selected components of this thread.  Contains barriers.
+template <bool MULTI>
+__device__ __forceinline__ StreamPos stream_position(const SelArgs& a, int64_t tile, int m, uint32_t n,
+                                                     uint32_t* lds_w, uint32_t* lds_ex) {
+  StreamPos p;
+  const int t = threadIdx.x;
+  const uint32_t ex = block_exclusive_scan(n, lds_w, &p.in_tile);
+  if (MULTI) {
+    const int64_t start = a.ws_start[(int64_t)m * a.ntiles + tile];
+    const int64_t k = tile / a.tiles_per_bucket;
+    p.base = k * a.area_words + (start >> 4);
+    p.first = (uint32_t)(start & 15);
+    p.pos = p.first + ex;
+    p.in_bucket = 0;
+  } else {
+    lds_ex[t] = ex;
+    if (t == 0) lds_ex[kThreads] = p.in_tile;
+    __syncthreads();
+    const int s0 = t & ~(a.seg - 1);
+    p.in_bucket = lds_ex[s0 + a.seg] - lds_ex[s0];
+    p.base = tile * kTileWords;
+    p.first = 0;
+    p.pos = 16u * (uint32_t)s0 + (ex - lds_ex[s0]);
+  }
+  return p;
+}
+
+// OR `bits` (2*n bits) into the LDS stream at code position pos.
+__device__ __forceinline__ void stream_append(uint32_t* stream, uint32_t pos, uint32_t n, uint32_t bits) {
+  if (n == 0) return;
+  const uint32_t word = pos / 16, sh = 2 * (pos % 16);
+  atomicOr(&stream[word], bits << sh);
+  if (sh && (2 * n + sh > 32)) atomicOr(&stream[word + 1], bits >> (32 - sh));
+}
+
+// Write the tile's part of the stream from LDS.  Tile-local buckets: the first ceil(K/16) words
+// of each bucket's area, nothing else.  Multi-tile buckets: the words the tile's codes touch;
+// a word that other tiles may also touch is OR-ed into (it was zeroed before), the others stored.
+template <bool MULTI>
+__device__ __forceinline__ void stream_flush(const SelArgs& a, const StreamPos& p, const uint32_t* stream,
+                                             uint32_t* row) {
+  const int t = threadIdx.x;
+  if (MULTI) {
+    const uint32_t end = p.first + p.in_tile;              // one past the tile's last code
+    const uint32_t words = (end + 15) / 16;
+    if (p.in_tile == 0) return;
+    for (uint32_t w = t; w < words; w += kThreads) {       // at most 257 words
+      const bool shared = (w == 0 && p.first != 0) || (w == words - 1 && (end % 16) != 0);
+      if (shared) atomicOr(&row[p.base + w], stream[w]);
+      else row[p.base + w] = stream[w];
+    }
+  } else {
+    const int s0 = t & ~(a.seg - 1);
+    if ((uint32_t)(t - s0) < (p.in_bucket + 15) / 16) row[p.base + t] = stream[t];
+  }
+}
+
+// pass 1 of the multi-tile path: selected components of every tile and, with a gradient, the sum
+// of their magnitudes
+template <bool HAS_G>
+__global__ __launch_bounds__(kThreads) void gsel_count_kernel(SelArgs a) {
+  __shared__ uint32_t lds_w[kWaves];
+  __shared__ double lds_d[kWaves];
+  const int t = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
+  uint32_t K;
+  block_exclusive_scan((uint32_t)__popc(mask), lds_w, &K);
+  if (HAS_G) {
+    const float* g = a.g + (int64_t)m * a.g_stride;
+    const int64_t i0 = tile * kTile + 16 * (int64_t)t;
+    double s1 = 0.0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if ((mask >> j) & 1u) s1 += (double)fabsf(g[i0 + j]);     // marked bits lie below d
+    const double S1 = block_sum_f64(s1, lds_d);
+    if (t == 0) a.ws_s1[(int64_t)m * a.ntiles + tile] = S1;
+  }
+  if (t == 0) a.ws_count[(int64_t)m * a.ntiles + tile] = K;
+}
+
+// pass 2: per (bucket, worker), in tile order: each tile's first position in the bucket's stream,
+// the bucket's count and (with a gradient) its threshold.  One work-group per bucket; the tiles
+// are taken 256 at a time with a running offset, so the order of the binary64 additions is fixed.
+template <bool HAS_G>
+__global__ __launch_bounds__(kThreads) void gsel_scan_kernel(SelArgs a) {
+  __shared__ uint32_t lds_w[kWaves];
+  __shared__ double lds_d[kWaves];
+  const int t = threadIdx.x;
+  const int64_t k = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t t0 = k * a.tiles_per_bucket;
+  const int64_t t1 = t0 + a.tiles_per_bucket < a.ntiles ? t0 + a.tiles_per_bucket : a.ntiles;
+  const uint32_t* cnt = a.ws_count + (int64_t)m * a.ntiles;
+  int64_t running = 0;
+  double s1 = 0.0;
+  for (int64_t i = t0; i < t1; i += kThreads) {
+    const int64_t j = i + t;
+    const uint32_t c = j < t1 ? cnt[j] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan(c, lds_w, &total);
+    if (j < t1) {
+      a.ws_start[(int64_t)m * a.ntiles + j] = running + ex;
+      if (HAS_G) s1 += a.ws_s1[(int64_t)m * a.ntiles + j];
+    }
+    running += total;
+    __syncthreads();                                     // lds_w is reused by the next round
+  }
+  if (HAS_G) s1 = block_sum_f64(s1, lds_d);
+  if (t == 0) {
+    a.counts[(int64_t)m * a.scale_stride + k] = (uint32_t)running;   // a bucket holds < 2^32 here
+    if (HAS_G) {
+      const float Delta = running ? threshold_from_sum(s1, a.thr_coef, running) : 0.0f;
+      a.ws_thr[(int64_t)m * a.nb + k] = Delta;
+      if (a.thresholds) a.thresholds[(int64_t)m * a.scale_stride + k] = Delta;
+    }
+  }
+}
+
+// zero the first ceil(K/16) words of every bucket's area (tile `blockIdx.x` covers 256 of them)
+__global__ __launch_bounds__(kThreads) void gsel_zero_kernel(SelArgs a) {
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t k = tile / a.tiles_per_bucket;
+  const int64_t w = (tile - k * a.tiles_per_bucket) * kTileWords + threadIdx.x;   // word of the area
+  const int64_t K = a.counts[(int64_t)m * a.scale_stride + k];
+  if (w < (K + 15) / 16) a.sel_codes[(int64_t)m * a.code_stride + k * a.area_words + w] = 0u;
+}
+
+// Q(S(g, I)) for any bucket size.  MULTI: thresholds come from pass 2, the kept sums of the tile
+// go to the workspace for gsel_scale_kernel.
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads) void gsel_quantize_kernel(SelArgs a) {
+  __shared__ uint32_t stream[kTileWords + 2];
+  __shared__ uint32_t lds_w[kWaves];
+  __shared__ uint32_t lds_ex[kThreads + 1];
+  __shared__ double lds_d[kWaves];
+  __shared__ uint32_t lds_u[kWaves];
+  const int t = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const float* g = a.g + (int64_t)m * a.g_stride;
+  const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
+  const int64_t i0 = tile * kTile + 16 * (int64_t)t;
+  float v[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) v[j] = (i0 + j < a.d) ? g[i0 + j] : 0.0f;
+  stream[t] = 0u;
+  if (t < 2) stream[kTileWords + t] = 0u;
+  const uint32_t n = (uint32_t)__popc(mask);
+  const StreamPos p = stream_position<MULTI>(a, tile, m, n, lds_w, lds_ex);   // barriers: stream is zero
+
+  float Delta;
+  if (MULTI) {
+    Delta = a.ws_thr[(int64_t)m * a.nb + tile / a.tiles_per_bucket];
+  } else {
+    double s1 = 0.0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
+    const double S1 = segment_sum(s1, a.seg, lds_d);
+    Delta = p.in_bucket ? threshold_from_sum(S1, a.thr_coef, (int64_t)p.in_bucket) : 0.0f;
+  }
+  double s2 = 0.0;
+  uint32_t c2 = 0, bits = 0, k = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    if ((mask >> j) & 1u) {
+      const float av = fabsf(v[j]);
+      if (av > Delta) { s2 += (double)av; ++c2; }
+      bits |= ternary_field(v[j], Delta) << (2 * k);
+      ++k;
+    }
+  }
+  stream_append(stream, p.pos, n, bits);
+  const int seg = MULTI ? kThreads : a.seg;
+  __syncthreads();                                       // lds_d of the first sum has been read
+  const double S2 = segment_sum(s2, seg, lds_d);
+  const uint32_t C2 = segment_sum_u32(c2, seg, lds_u);
+  __syncthreads();                                       // the stream is complete
+  stream_flush<MULTI>(a, p, stream, a.sel_codes + (int64_t)m * a.code_stride);
+  if (MULTI) {
+    if (t == 0) {
+      a.ws_s2[(int64_t)m * a.ntiles + tile] = S2;
+      a.ws_c2[(int64_t)m * a.ntiles + tile] = C2;
+    }
+  } else if ((t & (a.seg - 1)) == 0) {
+    const int64_t kb = (tile * kTile + 16 * (int64_t)t) / (16 * (int64_t)a.seg);
+    if (kb < a.nb) {
+      a.counts[(int64_t)m * a.scale_stride + kb] = p.in_bucket;
+      a.scales[(int64_t)m * a.scale_stride + kb] = scale_from_sum(S2, C2);
+      if (a.thresholds) a.thresholds[(int64_t)m * a.scale_stride + kb] = Delta;
+    }
+  }
+}
+
+// last pass of the multi-tile quantizer: scale of each (bucket, worker)
+__global__ __launch_bounds__(kThreads) void gsel_scale_kernel(SelArgs a) {
+  __shared__ double lds_d[kWaves];
+  __shared__ double lds_c[kWaves];
+  const int64_t k = blockIdx.x;
+  const int m = blockIdx.y;
+  const int64_t t0 = k * a.tiles_per_bucket;
+  const int64_t t1 = t0 + a.tiles_per_bucket < a.ntiles ? t0 + a.tiles_per_bucket : a.ntiles;
+  double s = strided_partial_sum(a.ws_s2 + (int64_t)m * a.ntiles, t0, t1);
+  double c = strided_partial_sum(a.ws_c2 + (int64_t)m * a.ntiles, t0, t1);
+  s = segment_sum(s, kThreads, lds_d);
+  c = segment_sum(c, kThreads, lds_c);
+  if (threadIdx.x == 0) a.scales[(int64_t)m * a.scale_stride + k] = scale_from_sum(s, (uint64_t)c);
+}
+
+// S^{-1} for any bucket size: thread t writes dense code word t of the tile.
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads) void gsel_decode_kernel(SelArgs a) {
+  __shared__ uint8_t lut[16 * 256];
+  __shared__ uint32_t lds_w[kWaves];
+  __shared__ uint32_t lds_ex[kThreads + 1];
+  const int t = threadIdx.x;
+  reinterpret_cast<uint4*>(lut)[t] = reinterpret_cast<const uint4*>(kDepositLut.v)[t];
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
+  const uint32_t n = (uint32_t)__popc(mask);
+  const StreamPos p = stream_position<MULTI>(a, tile, m, n, lds_w, lds_ex);   // barriers: lut is in LDS
+  const uint32_t* row = a.sel_in + (int64_t)m * a.code_stride + p.base;
+  // the thread's n codes are codes pos .. pos+n-1 counted from row[0]; they exist (n > 0), so
+  // the words read lie inside what the producer wrote
+  const uint32_t w0 = p.pos / 16, sh = 2 * (p.pos % 16);
+  const uint32_t lo = n ? row[w0] : 0u;
+  const uint32_t hi = (p.pos % 16) + n > 16u ? row[w0 + 1] : 0u;
+  uint32_t win = lo >> sh;
+  if (sh) win |= hi << (32 - sh);
+  uint32_t out = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t nib = (mask >> (4 * q)) & 15u;
+    out |= (uint32_t)lut[nib * 256 + (win & 0xFFu)] << (8 * q);
+    win >>= 2 * __popc(nib);
+  }
+  const int64_t w = tile * kTileWords + t;
+  if (w < a.W) (a.dense + (int64_t)m * a.dense_stride)[w] = out;
+}
+
+// S applied to a coded message for any bucket size.
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads) void gsel_select_codes_kernel(SelArgs a) {
+  __shared__ uint8_t lut[16 * 256];
+  __shared__ uint32_t stream[kTileWords + 2];
+  __shared__ uint32_t lds_w[kWaves];
+  __shared__ uint32_t lds_ex[kThreads + 1];
+  const int t = threadIdx.x;
+  reinterpret_cast<uint4*>(lut)[t] = reinterpret_cast<const uint4*>(kExtractLut.v)[t];
+  stream[t] = 0u;
+  if (t < 2) stream[kTileWords + t] = 0u;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
+  const uint32_t n = (uint32_t)__popc(mask);
+  const int64_t w = tile * kTileWords + t;
+  const uint32_t raw = w < a.W ? (a.sel_in + (int64_t)m * a.code_stride)[w] : 0u;
+  const uint32_t low = raw & 0x55555555u;
+  const uint32_t word = low | (raw & (low << 1));        // reserved pattern 10 reads as 0
+  const StreamPos p = stream_position<MULTI>(a, tile, m, n, lds_w, lds_ex);   // barriers: lut, stream ready
+  uint32_t bits = 0, filled = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t nib = (mask >> (4 * q)) & 15u;
+    bits |= (uint32_t)lut[nib * 256 + ((word >> (8 * q)) & 0xFFu)] << filled;
+    filled += 2 * __popc(nib);
+  }
+  stream_append(stream, p.pos, n, bits);
+  __syncthreads();
+  stream_flush<MULTI>(a, p, stream, a.sel_codes + (int64_t)m * a.code_stride);
+  if (!MULTI && (t & (a.seg - 1)) == 0) {
+    const int64_t kb = (tile * kTile + 16 * (int64_t)t) / (16 * (int64_t)a.seg);
+    if (kb < a.nb) a.counts[(int64_t)m * a.scale_stride + kb] = p.in_bucket;
+  }
+}
+
+// Which kernels serve a layout's sparse messages.
+enum SelKind { kSelTile, kSelLocal, kSelMulti };
+static SelKind sel_kind(const qa_layout* L) {
+  if (L->bucket == kTile || (L->bucket == 0 && L->d <= kTile)) return kSelTile;   // the tuned kernels
+  if (L->bucket != 0 && L->bucket < kTile) return kSelLocal;                        // buckets inside a tile
+  return kSelMulti;                                                                 // buckets over several tiles
+}
+
+static inline size_t sel_align(size_t v) { return (v + 255) & ~size_t(255); }
+
+// Workspace of the multi-tile path: per (worker, tile) a count, two binary64 sums, a kept count and
+// the tile's first position in its bucket's stream; per (worker, bucket) a threshold.
+size_t select_workspace_bytes(const qa_layout* L) {
+  if (sel_kind(L) != kSelMulti) return 0;
+  const size_t mt = (size_t)L->M * (size_t)tiles_of(L->d);
+  return sel_align(mt * 4) + 2 * sel_align(mt * 8) + sel_align(mt * 4) + sel_align(mt * 8) +
+         sel_align((size_t)L->M * (size_t)buckets_of(L->d, L->bucket) * 4);
+}
+
 static int check_select_layout(const qa_layout* L) {
   int rc = check_layout(L);
   if (rc != QA_OK) return rc;
-  // thresholds/scales per 4096-tile, or one per vector when the vector is a single tile
-  if (L->bucket == kTile || (L->bucket == 0 && L->d <= kTile)) return QA_OK;
-  return QA_ERR_UNSUPPORTED;
+  // a bucket's selected count is kept in 32 bits
+  const int64_t blen = L->bucket ? L->bucket : L->d;
+  if (blen >= (int64_t(1) << 32)) return QA_ERR_UNSUPPORTED;
+  return QA_OK;
+}
+
+// Geometry of the general kernels and, for multi-tile buckets, the workspace pointers.
+static int general_args(const qa_layout* L, SelArgs& a, void* ws, size_t ws_bytes) {
+  const SelKind kind = sel_kind(L);
+  a.nb = buckets_of(L->d, L->bucket);
+  a.ntiles = tiles_of(L->d);
+  a.seg = kind == kSelLocal ? L->bucket / 16 : kThreads;
+  if (kind != kSelMulti) return QA_OK;
+  const size_t need = select_workspace_bytes(L);
+  if (!ws || ws_bytes < need) return QA_ERR_WORKSPACE;
+  if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+  a.tiles_per_bucket = L->bucket ? L->bucket / kTile : a.ntiles;
+  a.area_words = L->bucket ? L->bucket / 16 : words_of(L->d);
+  const size_t mt = (size_t)L->M * (size_t)a.ntiles;
+  char* p = static_cast<char*>(ws);
+  a.ws_count = reinterpret_cast<uint32_t*>(p); p += sel_align(mt * 4);
+  a.ws_s1 = reinterpret_cast<double*>(p);      p += sel_align(mt * 8);
+  a.ws_s2 = reinterpret_cast<double*>(p);      p += sel_align(mt * 8);
+  a.ws_c2 = reinterpret_cast<uint32_t*>(p);    p += sel_align(mt * 4);
+  a.ws_start = reinterpret_cast<int64_t*>(p);  p += sel_align(mt * 8);
+  a.ws_thr = reinterpret_cast<float*>(p);
+  return QA_OK;
 }
 
 static SelArgs base_args(const qa_layout* L) {
@@ -464,6 +823,20 @@ extern "C" int qa_indicator(const qa_layout* layout, int method, const float* g,
   return launch_status();
 }
 
+namespace qa {
+// does the fused step read this layout's sparse messages itself (one threshold/scale per tile)?
+bool sparse_messages_fused(const qa_layout* L) { return sel_kind(L) == kSelTile; }
+int check_sparse_layout(const qa_layout* L) { return check_select_layout(L); }
+
+void indicator_or_launch(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                         uint32_t* ind_syn_out, hipStream_t stream) {
+  SelArgs a = base_args(layout);
+  a.ind_in = ind; a.ind_stride = ind_stride; a.ind = ind_syn_out;
+  hipLaunchKernelGGL(indicator_or_kernel, dim3((unsigned)((a.NW + kThreads - 1) / kThreads)),
+                     dim3(kThreads), 0, stream, a);
+}
+}  // namespace qa
+
 extern "C" int qa_indicator_or(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
                                uint32_t* ind_syn_out, void* stream) {
   using namespace qa;
@@ -471,17 +844,14 @@ extern "C" int qa_indicator_or(const qa_layout* layout, const uint32_t* ind, int
   if (rc != QA_OK) return rc;
   if (!ind || !ind_syn_out || ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
   if (!aligned(ind, 4) || !aligned(ind_syn_out, 4)) return QA_ERR_ALIGNMENT;
-  SelArgs a = base_args(layout);
-  a.ind_in = ind; a.ind_stride = ind_stride; a.ind = ind_syn_out;
-  hipLaunchKernelGGL(indicator_or_kernel, dim3((unsigned)((a.NW + kThreads - 1) / kThreads)),
-                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  indicator_or_launch(layout, ind, ind_stride, ind_syn_out, static_cast<hipStream_t>(stream));
   return launch_status();
 }
 
 extern "C" int qa_quantize_pack_selected(const qa_layout* layout, const float* g, int64_t g_stride,
                                          const uint32_t* ind, int64_t ind_stride, uint32_t* sel_codes,
                                          uint32_t* counts, float* scales, float* thresholds,
-                                         void* stream) {
+                                         void* ws, size_t ws_bytes, void* stream_) {
   using namespace qa;
   int rc = check_select_layout(layout);
   if (rc != QA_OK) return rc;
@@ -491,33 +861,84 @@ extern "C" int qa_quantize_pack_selected(const qa_layout* layout, const float* g
   if (!aligned(g, 16) || !aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(counts, 4) ||
       !aligned(scales, 4) || !aligned(thresholds, 4))
     return QA_ERR_ALIGNMENT;
+  if (tiles_of(layout->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
   SelArgs a = base_args(layout);
   a.g = g; a.g_stride = g_stride; a.ind_in = ind; a.ind_stride = ind_stride;
   a.sel_codes = sel_codes; a.counts = counts; a.scales = scales; a.thresholds = thresholds;
-  hipLaunchKernelGGL(quantize_selected_kernel, dim3((unsigned)tiles_of(layout->d), (unsigned)layout->M),
-                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  const dim3 block(kThreads), tiles((unsigned)tiles_of(layout->d), (unsigned)layout->M);
+  const SelKind kind = sel_kind(layout);
+  if (kind == kSelTile) {
+    hipLaunchKernelGGL(quantize_selected_kernel, tiles, block, 0, stream, a);
+    return launch_status();
+  }
+  rc = general_args(layout, a, ws, ws_bytes);
+  if (rc != QA_OK) return rc;
+  if (kind == kSelLocal) {
+    hipLaunchKernelGGL(gsel_quantize_kernel<false>, tiles, block, 0, stream, a);
+    return launch_status();
+  }
+  const dim3 buckets((unsigned)a.nb, (unsigned)layout->M);
+  hipLaunchKernelGGL(gsel_count_kernel<true>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_scan_kernel<true>, buckets, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_zero_kernel, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_quantize_kernel<true>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_scale_kernel, buckets, block, 0, stream, a);
   return launch_status();
 }
 
+namespace qa {
+// S^{-1} for all M messages into dense code words; shared with the steps that take sparse
+// messages of other bucket sizes than 4096.  `counts_scratch` (multi-tile buckets only) receives
+// the per-bucket counts that the scan produces on the way; it may be the workspace's own.
+int decode_selected_launch(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                           const uint32_t* sel_codes, uint32_t* codes_out, int64_t out_stride,
+                           void* ws, size_t ws_bytes, hipStream_t stream) {
+  SelArgs a = base_args(layout);
+  a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = sel_codes; a.dense = codes_out;
+  a.dense_stride = out_stride;
+  const dim3 block(kThreads), tiles((unsigned)tiles_of(layout->d), (unsigned)layout->M);
+  const SelKind kind = sel_kind(layout);
+  if (kind == kSelTile) {
+    hipLaunchKernelGGL(decode_selected_kernel,
+                       dim3((unsigned)((tiles_of(layout->d) + kWaves * kDecodeTiles - 1) / (kWaves * kDecodeTiles)),
+                            (unsigned)layout->M),
+                       block, 0, stream, a);
+    return launch_status();
+  }
+  int rc = general_args(layout, a, ws, ws_bytes);
+  if (rc != QA_OK) return rc;
+  if (kind == kSelLocal) {
+    hipLaunchKernelGGL(gsel_decode_kernel<false>, tiles, block, 0, stream, a);
+    return launch_status();
+  }
+  // the scan also leaves each bucket's count; nobody asked for it here: the kept-count slots of
+  // the workspace (unused by a decode) take it, M*nb <= M*ntiles words
+  a.counts = a.ws_c2; a.scale_stride = a.nb;
+  hipLaunchKernelGGL(gsel_count_kernel<false>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_scan_kernel<false>, dim3((unsigned)a.nb, (unsigned)layout->M), block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_decode_kernel<true>, tiles, block, 0, stream, a);
+  return launch_status();
+}
+}  // namespace qa
+
 extern "C" int qa_decode_selected(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
-                                  const uint32_t* sel_codes, uint32_t* codes_out, void* stream) {
+                                  const uint32_t* sel_codes, uint32_t* codes_out, void* ws,
+                                  size_t ws_bytes, void* stream) {
   using namespace qa;
   int rc = check_select_layout(layout);
   if (rc != QA_OK) return rc;
-  if (!ind || !sel_codes || !codes_out || ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
+  if (!ind || !sel_codes || !codes_out) return QA_ERR_INVALID_ARG;
+  if (ind_stride != 0 && ind_stride < (layout->d + 31) / 32) return QA_ERR_INVALID_ARG;
   if (!aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(codes_out, 4)) return QA_ERR_ALIGNMENT;
-  SelArgs a = base_args(layout);
-  a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = sel_codes; a.dense = codes_out;
-  hipLaunchKernelGGL(decode_selected_kernel,
-                     dim3((unsigned)((tiles_of(layout->d) + kWaves * kDecodeTiles - 1) / (kWaves * kDecodeTiles)),
-                          (unsigned)layout->M),
-                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
-  return launch_status();
+  if (tiles_of(layout->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+  return decode_selected_launch(layout, ind, ind_stride, sel_codes, codes_out, layout->code_stride, ws,
+                                ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int qa_select_codes(const qa_layout* layout, const uint32_t* codes, const uint32_t* ind,
-                               int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts,
-                               void* stream) {
+                               int64_t ind_stride, uint32_t* sel_codes, uint32_t* counts, void* ws,
+                               size_t ws_bytes, void* stream_) {
   using namespace qa;
   int rc = check_select_layout(layout);
   if (rc != QA_OK) return rc;
@@ -526,10 +947,27 @@ extern "C" int qa_select_codes(const qa_layout* layout, const uint32_t* codes, c
   if (!aligned(codes, 4) || !aligned(ind, 4) || !aligned(sel_codes, 4) || !aligned(counts, 4))
     return QA_ERR_ALIGNMENT;
   if (codes == sel_codes) return QA_ERR_INVALID_ARG;       // not in place
+  if (tiles_of(layout->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
   SelArgs a = base_args(layout);
   a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = codes; a.sel_codes = sel_codes; a.counts = counts;
-  hipLaunchKernelGGL(select_codes_kernel,
-                     dim3((unsigned)((tiles_of(layout->d) + kWaves - 1) / kWaves), (unsigned)layout->M),
-                     dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+  const dim3 block(kThreads), tiles((unsigned)tiles_of(layout->d), (unsigned)layout->M);
+  const SelKind kind = sel_kind(layout);
+  if (kind == kSelTile) {
+    hipLaunchKernelGGL(select_codes_kernel,
+                       dim3((unsigned)((tiles_of(layout->d) + kWaves - 1) / kWaves), (unsigned)layout->M),
+                       block, 0, stream, a);
+    return launch_status();
+  }
+  rc = general_args(layout, a, ws, ws_bytes);
+  if (rc != QA_OK) return rc;
+  if (kind == kSelLocal) {
+    hipLaunchKernelGGL(gsel_select_codes_kernel<false>, tiles, block, 0, stream, a);
+    return launch_status();
+  }
+  hipLaunchKernelGGL(gsel_count_kernel<false>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_scan_kernel<false>, dim3((unsigned)a.nb, (unsigned)layout->M), block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_zero_kernel, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_select_codes_kernel<true>, tiles, block, 0, stream, a);
   return launch_status();
 }

@@ -689,6 +689,14 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 
 static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
+size_t select_workspace_bytes(const qa_layout* L);
+bool sparse_messages_fused(const qa_layout* L);
+int check_sparse_layout(const qa_layout* L);
+int decode_selected_launch(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                           const uint32_t* sel_codes, uint32_t* codes_out, int64_t out_stride,
+                           void* ws, size_t ws_bytes, hipStream_t stream);
+void indicator_or_launch(const qa_layout* layout, const uint32_t* ind, int64_t ind_stride,
+                         uint32_t* ind_syn_out, hipStream_t stream);
 size_t quantize_workspace_bytes(const qa_layout* L);
 int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32_t* codes,
                     float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
@@ -728,6 +736,38 @@ size_t step_workspace_bytes(const qa_layout* L) {
     if (nb > need) need = nb;
   }
   return need;
+}
+
+// Sparse messages whose buckets are not one tile each are first decoded into dense code words
+// (in the workspace) and then take the dense path: the definition of the steps on sparse messages.
+// Workspace: [dense codes, M rows of a 256-byte multiple][decoder's workspace][step's workspace].
+static int64_t decoded_stride(const qa_layout* L) { return (words_of(L->d) + 63) & ~int64_t(63); }
+size_t step_selected_workspace_bytes(const qa_layout* L) {
+  if (sparse_messages_fused(L)) return step_workspace_bytes(L);
+  return align256((size_t)L->M * (size_t)decoded_stride(L) * 4) + align256(select_workspace_bytes(L)) +
+         step_workspace_bytes(L);
+}
+// Decodes into the workspace; on return *dense / *D describe the dense messages and *ws / *ws_bytes
+// what is left of the workspace.
+static int decode_into_workspace(const qa_layout* L, const uint32_t* ind, int64_t ind_stride,
+                                 const uint32_t* sel_codes, qa_layout* D, const uint32_t** dense,
+                                 void** ws, size_t* ws_bytes, hipStream_t stream) {
+  const size_t codes_bytes = align256((size_t)L->M * (size_t)decoded_stride(L) * 4);
+  const size_t sel_bytes = align256(select_workspace_bytes(L));
+  if (!*ws || *ws_bytes < codes_bytes + sel_bytes) return QA_ERR_WORKSPACE;
+  if (!aligned(*ws, 256)) return QA_ERR_ALIGNMENT;
+  char* p = static_cast<char*>(*ws);
+  *D = *L;
+  D->code_stride = decoded_stride(L);
+  uint32_t* out = reinterpret_cast<uint32_t*>(p);
+  int rc = decode_selected_launch(L, ind, ind_stride, sel_codes, out, D->code_stride,
+                                  sel_bytes ? p + codes_bytes : nullptr, sel_bytes, stream);
+  if (rc != QA_OK) return rc;
+  *dense = out;
+  *ws = p + codes_bytes + sel_bytes;
+  *ws_bytes -= codes_bytes + sel_bytes;
+  if (*ws_bytes == 0) *ws = nullptr;
+  return QA_OK;
 }
 
 static StepArgs make_args(const qa_layout* L, const uint32_t* codes, const float* scales) {
@@ -813,7 +853,8 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
     if (!ind) return QA_ERR_INVALID_ARG;
     if (ind_stride != 0 && ind_stride < (L->d + 31) / 32) return QA_ERR_INVALID_ARG;
     if (!aligned(ind, 4)) return QA_ERR_ALIGNMENT;
-    if (!(L->bucket == kTile || (L->bucket == 0 && L->d <= kTile))) return QA_ERR_UNSUPPORTED;
+    rc = check_sparse_layout(L);
+    if (rc != QA_OK) return rc;
   }
   if (mode == kQrda && !z) return QA_ERR_INVALID_ARG;
   if (!(eta > 0.0f) || !(lambda >= 0.0f) || !(delta > 0.0f)) return QA_ERR_INVALID_ARG;
@@ -825,6 +866,15 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
       !aligned(scales, 4))
     return QA_ERR_ALIGNMENT;
   if (tiles_of(L->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+
+  qa_layout D;
+  if (sparse && !sparse_messages_fused(L)) {
+    // decode first, then the dense step on what the decoder wrote
+    rc = decode_into_workspace(L, ind, ind_stride, codes, &D, &codes, &ws, &ws_bytes, stream);
+    if (rc != QA_OK) return rc;
+    L = &D;
+    sparse = false;
+  }
 
   qa_layout R;
   const qa_layout* use = L;
@@ -891,12 +941,23 @@ static int aggregate_quantize_common(const qa_layout* L, const uint32_t* codes, 
     if (!ind) return QA_ERR_INVALID_ARG;
     if (ind_stride != 0 && ind_stride < (L->d + 31) / 32) return QA_ERR_INVALID_ARG;
     if (!aligned(ind, 4)) return QA_ERR_ALIGNMENT;
-    if (!(L->bucket == kTile || (L->bucket == 0 && L->d <= kTile))) return QA_ERR_UNSUPPORTED;
+    rc = check_sparse_layout(L);
+    if (rc != QA_OK) return rc;
   }
   if (!aligned(codes, 4) || !aligned(scales, 4) || !aligned(q_codes, 4) || !aligned(q_scales, 4) ||
       !aligned(q_thresholds, 4))
     return QA_ERR_ALIGNMENT;
   if (tiles_of(L->d) > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
+
+  qa_layout D;
+  if (sparse && !sparse_messages_fused(L)) {
+    // decode first (and OR the indicators), then the dense call on what the decoder wrote
+    rc = decode_into_workspace(L, ind, ind_stride, codes, &D, &codes, &ws, &ws_bytes, stream);
+    if (rc != QA_OK) return rc;
+    if (ind_syn) indicator_or_launch(L, ind, ind_stride, ind_syn, stream);
+    L = &D;
+    sparse = false;
+  }
 
   StepArgs ag = make_args(L, codes, scales);
   if (sparse) { ag.ind = ind; ag.ind_stride = ind_stride; ag.ind_syn = ind_syn; }

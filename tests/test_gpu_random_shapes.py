@@ -101,8 +101,8 @@ def test_random_shapes_match_oracle_bit_for_bit(seed):
             torch.cuda.synchronize()
             assert np.array_equal(host(qc).view(np.uint32)[:, :L1.words], qc_ref), what
             assert same_bits(host(qs)[:, :L1.n_buckets], qs_ref), what
-        # sparse messages, where that encoding applies
-        if bucket == 4096 or (bucket == 0 and d <= 4096):
+        # sparse messages (every bucket size)
+        if True:
             p = float(rng.choice([0.0, 0.05, 0.5, 1.0]))
             shared = bool(rng.random() < 0.3)
             ind = random_indicator(rng, 1 if shared else M, d, p)
@@ -115,15 +115,16 @@ def test_random_shapes_match_oracle_bit_for_bit(seed):
                 o_sel, o_cnt, o_sc, _ = oracle.quantize_selected(g[m], im, bucket=bucket)
                 for k in range(nb):
                     nwk = (int(o_cnt[k]) + 15) // 16
-                    lo = k * (256 if bucket else (d + 15) // 16)
-                    sel[m, k * 256: k * 256 + nwk] = o_sel[lo: lo + nwk]
+                    lo = k * (((bucket or d) + 15) // 16)
+                    sel[m, lo: lo + nwk] = o_sel[lo: lo + nwk]
                 sc[m] = o_sc
                 dense[m] = oracle.decode_selected(im, o_sel, d, bucket=bucket)
             ind_rows = ind if not shared else np.repeat(ind, M, 0)
             sel_g = torch.full((M, L.code_stride), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
             cnt_g = torch.zeros((M, nb), dtype=torch.int32, device=DEV)
             sc_g = torch.zeros((M, nb), dtype=torch.float32, device=DEV)
-            qa.qa_quantize_pack_selected(L, dev(gp), gs, dev(ind_rows.view(np.int32)), NW, sel_g, cnt_g, sc_g, None)
+            qa.qa_quantize_pack_selected(L, dev(gp), gs, dev(ind_rows.view(np.int32)), NW, sel_g, cnt_g, sc_g, None,
+                                         workspace(qa.qa_workspace_bytes(L, qa.QA_OP_SELECT)))
             torch.cuda.synchronize()
             assert np.array_equal(host(sel_g).view(np.uint32), sel) and same_bits(host(sc_g), sc), what
             ox, oG, oz = x0.copy(), G0.copy(), z0.copy()
@@ -131,7 +132,8 @@ def test_random_shapes_match_oracle_bit_for_bit(seed):
             with np.errstate(all="ignore"):
                 oracle.step_qrda(dense, sc, d, bucket, ox, oG, oz, t, eta, lam, delta, requant)
             qa.qa_step_qrda_selected(L, dev(ind.view(np.int32)), 0 if shared else NW, dev(sel.view(np.int32)),
-                                     dev(sc), xd, Gd, zd, t, eta, lam, delta, requant, ws)
+                                     dev(sc), xd, Gd, zd, t, eta, lam, delta, requant,
+                                     workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP_SELECTED)))
             torch.cuda.synchronize()
             assert same_bits(host(xd), ox) and same_bits(host(Gd), oG) and same_bits(host(zd), oz), (what, "sparse")
 
@@ -221,7 +223,7 @@ def test_random_shapes_of_the_other_calls_match_oracle_bit_for_bit(seed):
         assert same_bits(host(scales)[:, :Ls.n_buckets], osc), (what, "stochastic", bs)
         # ---- indicator, code selection, decode ----
         d3 = int(rng.choice([rng.integers(1, 5000), rng.integers(5000, 40000)]))
-        b3 = 4096 if d3 > 4096 else int(rng.choice([0, 4096]))
+        b3 = int(rng.choice([0, 64, 512, 2048, 4096, 8192]))
         method, lam, t = int(rng.integers(0, 2)), float(rng.choice([0.0, 1e-3, 0.05])), int(rng.integers(1, 9))
         x3 = (rng.standard_normal(d3) * 0.1 * (rng.random(d3) < 0.3)).astype(np.float32)
         G3 = (rng.random(d3) * 10.0 ** rng.integers(-6, 1)).astype(np.float32)
@@ -240,17 +242,18 @@ def test_random_shapes_of_the_other_calls_match_oracle_bit_for_bit(seed):
         dense_ref, _, _ = oracle.quantize_pack(g3, bucket=b3)
         sel = torch.full((M, L3.code_stride), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
         cnt = torch.zeros((M, L3.n_buckets), dtype=torch.int32, device=DEV)
-        qa.qa_select_codes(L3, dev(dense_ref.view(np.int32)), ind, NW, sel, cnt)
+        ws3 = workspace(qa.qa_workspace_bytes(L3, qa.QA_OP_SELECT))
+        qa.qa_select_codes(L3, dev(dense_ref.view(np.int32)), ind, NW, sel, cnt, ws3)
         back = torch.full((M, L3.code_stride), -1, dtype=torch.int32, device=DEV)
-        qa.qa_decode_selected(L3, ind, NW, sel, back)
+        qa.qa_decode_selected(L3, ind, NW, sel, back, ws3)
         torch.cuda.synchronize()
-        area = 256 if b3 else (d3 + 15) // 16
+        area = ((b3 or d3) + 15) // 16
         for m in range(M):
             o_sel, o_cnt = oracle.select_codes(dense_ref[m], ref[m], d3, b3)
             assert np.array_equal(host(cnt).view(np.uint32)[m], o_cnt), what
             for k in range(L3.n_buckets):
                 nwk = (int(o_cnt[k]) + 15) // 16
-                assert np.array_equal(host(sel).view(np.uint32)[m, k * 256:k * 256 + nwk],
+                assert np.array_equal(host(sel).view(np.uint32)[m, k * area:k * area + nwk],
                                       o_sel[k * area:k * area + nwk]), what
             assert np.array_equal(host(back).view(np.uint32)[m, :L3.words],
                                   oracle.decode_selected(ref[m], o_sel, d3, bucket=b3)), what

@@ -96,9 +96,23 @@ def random_indicator(rng, M, d, p):
     return ind
 
 
+GENERAL_BUCKETS = [
+    # one scale per message over many tiles (the 32 + d + 2k bit message), dense / sparse / full / empty
+    (70001, 3, 0, 0.2), (300000, 2, 0, 0.004), (70001, 2, 0, 1.0), (20000, 2, 0, 0.0), (4097, 1, 0, 0.5),
+    # buckets inside a tile
+    (70001, 2, 64, 0.5), (70001, 2, 256, 0.3), (12289, 3, 1024, 0.05), (70001, 2, 2048, 0.1),
+    # buckets over several tiles
+    (70001, 2, 8192, 0.3), (70001, 3, 16384, 0.02), (5000, 2, 65536, 0.5),
+]
+
+
+def area_words(d, bucket):
+    return ((bucket or d) + 15) // 16
+
+
 @pytest.mark.parametrize("d,M,bucket,p", [(1, 1, 0, 1.0), (1000, 2, 0, 0.3), (4096, 2, 4096, 0.5),
                                           (4097, 2, 4096, 0.01), (70001, 3, 4096, 0.2),
-                                          (70001, 2, 4096, 1.0), (20000, 2, 4096, 0.0)])
+                                          (70001, 2, 4096, 1.0), (20000, 2, 4096, 0.0)] + GENERAL_BUCKETS)
 def test_quantize_selected_and_decode_match_oracle(d, M, bucket, p):
     rng = np.random.default_rng(d + M)
     g = (rng.standard_normal((M, d)) * 1e-2).astype(np.float32)
@@ -115,11 +129,14 @@ def test_quantize_selected_and_decode_match_oracle(d, M, bucket, p):
     th = torch.full((M, nb), -1.0, dtype=torch.float32, device=DEV)
     dense = torch.full((M, L.code_stride), -1, dtype=torch.int32, device=DEV)
     ind_d = dev(ind.view(np.int32))
-    qa.qa_quantize_pack_selected(L, dev(gp), gs, ind_d, NW, sel, cnt, sc, th)
-    qa.qa_decode_selected(L, ind_d, NW, sel, dense)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_SELECT))
+    qa.qa_quantize_pack_selected(L, dev(gp), gs, ind_d, NW, sel, cnt, sc, th, ws)
+    if ws is not None:
+        ws.fill_(0x77)                                               # nothing may be carried between calls
+    qa.qa_decode_selected(L, ind_d, NW, sel, dense, ws)
     torch.cuda.synchronize()
     sel_h, cnt_h = host(sel).view(np.uint32), host(cnt).view(np.uint32)
-    area = 256 if bucket else (d + 15) // 16
+    area = area_words(d, bucket)
     for m in range(M):
         o_sel, o_cnt, o_sc, o_th = oracle.quantize_selected(g[m], ind[m], bucket=bucket)
         assert np.array_equal(cnt_h[m], o_cnt)
@@ -127,8 +144,8 @@ def test_quantize_selected_and_decode_match_oracle(d, M, bucket, p):
         for k in range(nb):
             nwk = (int(o_cnt[k]) + 15) // 16
             lo = k * area
-            assert np.array_equal(sel_h[m, k * 256: k * 256 + nwk], o_sel[lo: lo + nwk]), (m, k)
-            untouched = sel_h[m, k * 256 + nwk: min((k + 1) * 256, L.code_stride)]
+            assert np.array_equal(sel_h[m, lo: lo + nwk], o_sel[lo: lo + nwk]), (m, k)
+            untouched = sel_h[m, lo + nwk: min(lo + area, L.code_stride)]
             assert np.all(untouched == 0x5A5A5A5A)                   # only ceil(count/16) words written
         assert np.array_equal(host(dense).view(np.uint32)[m, :W], oracle.decode_selected(ind[m], o_sel, d, bucket=bucket))
 
@@ -136,7 +153,7 @@ def test_quantize_selected_and_decode_match_oracle(d, M, bucket, p):
 @pytest.mark.parametrize("shared", [False, True])
 @pytest.mark.parametrize("d,M,bucket,p", [(1, 1, 0, 1.0), (1000, 2, 0, 0.3), (4096, 1, 4096, 0.5),
                                           (4097, 2, 4096, 0.02), (70001, 3, 4096, 0.2),
-                                          (70001, 1, 4096, 1.0), (20000, 2, 4096, 0.0)])
+                                          (70001, 1, 4096, 1.0), (20000, 2, 4096, 0.0)] + GENERAL_BUCKETS)
 def test_select_codes_matches_oracle_and_decode_inverts_it(d, M, bucket, p, shared):
     """S(q, I) on coded messages (the server's push): bit-exact with the checker, only the words
     that hold codes are written, and the decoder restores the marked components."""
@@ -149,20 +166,22 @@ def test_select_codes_matches_oracle_and_decode_inverts_it(d, M, bucket, p, shar
     cnt = torch.full((M, nb), -1, dtype=torch.int32, device=DEV)
     back = torch.full((M, L.code_stride), -1, dtype=torch.int32, device=DEV)
     codes_d, ind_d = dev(codes.view(np.int32)), dev(ind.view(np.int32))
-    qa.qa_select_codes(L, codes_d, ind_d, 0 if shared else NW, sel, cnt)
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_SELECT))
+    qa.qa_select_codes(L, codes_d, ind_d, 0 if shared else NW, sel, cnt, ws)
     if not shared:
-        qa.qa_decode_selected(L, ind_d, NW, sel, back)
+        qa.qa_decode_selected(L, ind_d, NW, sel, back, ws)
     torch.cuda.synchronize()
     sel_h, cnt_h = host(sel).view(np.uint32), host(cnt).view(np.uint32)
-    area = 256 if bucket else (d + 15) // 16
+    area = area_words(d, bucket)
     for m in range(M):
         im = ind[0 if shared else m]
         o_sel, o_cnt = oracle.select_codes(codes[m, :W], im, d, bucket=bucket)
         assert np.array_equal(cnt_h[m], o_cnt)
         for k in range(nb):
             nwk = (int(o_cnt[k]) + 15) // 16
-            assert np.array_equal(sel_h[m, k * 256: k * 256 + nwk], o_sel[k * area: k * area + nwk]), (m, k)
-            assert np.all(sel_h[m, k * 256 + nwk: min((k + 1) * 256, L.code_stride)] == 0x5A5A5A5A)
+            lo = k * area
+            assert np.array_equal(sel_h[m, lo: lo + nwk], o_sel[lo: lo + nwk]), (m, k)
+            assert np.all(sel_h[m, lo + nwk: min(lo + area, L.code_stride)] == 0x5A5A5A5A)
         if not shared:
             want = oracle.decode_selected(im, o_sel, d, bucket=bucket)
             assert np.array_equal(host(back).view(np.uint32)[m, :W], want)
@@ -281,11 +300,20 @@ def test_server_and_worker_roles_as_separate_calls_equal_the_fused_step(method):
     assert 0 < int(host(push_cnt).sum()) < d and np.count_nonzero(host(xa)) > 0
 
 
-def test_unsupported_bucket_sizes_are_refused():
-    L = qa.Layout.make(100000, 2, 1024)
+def test_sparse_encoding_refuses_what_it_cannot_do_before_launching():
     t = torch.zeros(8, dtype=torch.int32, device=DEV)
+    # buckets over several tiles need the scan's workspace
+    L = qa.Layout.make(100000, 2, 0)
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_SELECT) > 0
     with pytest.raises(qa.QaError) as e:
         qa.qa_decode_selected(L, t, 100000, t, t)
+    assert e.value.code == -3
+    # buckets inside a tile need none
+    assert qa.qa_workspace_bytes(qa.Layout.make(100000, 2, 1024), qa.QA_OP_SELECT) == 0
+    # a bucket's count is kept in 32 bits
+    L = qa.Layout.make(1 << 33, 1, 0)
+    with pytest.raises(qa.QaError) as e:
+        qa.qa_decode_selected(L, t, 1 << 28, t, t)
     assert e.value.code == -5
 
 
@@ -298,6 +326,10 @@ SPARSE_STEP_CASES = [
     (70001, 3, 4096, 0.2, 2, False, False), (20000, 2, 4096, 0.0, 0, False, False),
     (70001, 1, 4096, 0.2, 0, True, False), (70001, 4, 4096, 0.2, 1, True, False),
     (70001, 20, 4096, 0.3, 0, False, True), (9000, 4, 4096, 0.4, 1, False, True),
+    # other bucket sizes: decoded into the workspace, then the dense step
+    (70001, 4, 0, 0.2, 0, False, False), (70001, 3, 0, 0.3, 2, False, False), (70001, 2, 0, 0.2, 0, True, False),
+    (70001, 5, 256, 0.3, 1, False, False), (70001, 4, 2048, 0.1, 0, False, False),
+    (70001, 3, 16384, 0.2, 1, False, False), (70001, 20, 1024, 0.3, 0, False, True),
 ]
 
 
@@ -312,7 +344,8 @@ def test_steps_on_sparse_messages_match_oracle_decode_then_step(d, M, bucket, p,
     nb, W, NW = L.n_buckets, L.words, (d + 31) // 32
     ox, oG, oz = rand_state(rng, d)
     xd, Gd, zd = dev(ox), dev(oG), dev(oz)
-    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP_SELECTED))
+    area = area_words(d, bucket)
     for t in (1, 2, 3):
         g = (rng.standard_normal((M, d)) * rng.choice([1e-3, 0.02], (M, d))).astype(np.float32)
         ind = random_indicator(rng, 1 if shared else M, d, p)
@@ -326,8 +359,8 @@ def test_steps_on_sparse_messages_match_oracle_decode_then_step(d, M, bucket, p,
             o_sel, o_cnt, o_sc, _ = oracle.quantize_selected(g[m], im, bucket=bucket)
             for k in range(nb):
                 nwk = (int(o_cnt[k]) + 15) // 16
-                lo = k * (256 if bucket else (d + 15) // 16)
-                sel[m, k * 256: k * 256 + nwk] = o_sel[lo: lo + nwk]
+                lo = k * area
+                sel[m, lo: lo + nwk] = o_sel[lo: lo + nwk]
             sc[m] = o_sc
             dense[m] = oracle.decode_selected(im, o_sel, d, bucket=bucket)
         if wide:
@@ -356,7 +389,8 @@ def test_steps_on_sparse_messages_match_oracle_decode_then_step(d, M, bucket, p,
 
 @pytest.mark.parametrize("d,M,bucket,p,requant,shared", [
     (1000, 3, 0, 0.3, 2, False), (4097, 5, 4096, 0.05, 1, False), (70001, 16, 4096, 0.3, 1, False),
-    (70001, 3, 4096, 0.2, 2, False), (70001, 4, 4096, 0.2, 1, True), (20000, 2, 4096, 0.0, 1, False)])
+    (70001, 3, 4096, 0.2, 2, False), (70001, 4, 4096, 0.2, 1, True), (20000, 2, 4096, 0.0, 1, False),
+    (70001, 4, 0, 0.2, 2, False), (70001, 3, 512, 0.3, 1, False), (70001, 3, 8192, 0.3, 1, True)])
 def test_server_call_on_sparse_messages_matches_oracle(d, M, bucket, p, requant, shared):
     """qa_aggregate_quantize_selected == oracle decode, average, quantizer on the average; then
     qa_select_codes with the synchronous indicator gives the pushed message."""
@@ -368,13 +402,14 @@ def test_server_call_on_sparse_messages_matches_oracle(d, M, bucket, p, requant,
     sel = np.full((M, L.code_stride), 0x5A5A5A5A, np.uint32)
     sc = np.zeros((M, nb), np.float32)
     dense = np.zeros((M, W), np.uint32)
+    area = area_words(d, bucket)
     for m in range(M):
         im = ind[0 if shared else m]
         o_sel, o_cnt, o_sc, _ = oracle.quantize_selected(g[m], im, bucket=bucket)
         for k in range(nb):
             nwk = (int(o_cnt[k]) + 15) // 16
-            lo = k * (256 if bucket else (d + 15) // 16)
-            sel[m, k * 256: k * 256 + nwk] = o_sel[lo: lo + nwk]
+            lo = k * area
+            sel[m, lo: lo + nwk] = o_sel[lo: lo + nwk]
         sc[m] = o_sc
         dense[m] = oracle.decode_selected(im, o_sel, d, bucket=bucket)
     bq = bucket if requant == 1 else 0
@@ -383,7 +418,7 @@ def test_server_call_on_sparse_messages_matches_oracle(d, M, bucket, p, requant,
     L1 = qa.Layout.make(d, 1, bq)
     qc = torch.full((1, L1.code_stride), -1, dtype=torch.int32, device=DEV)
     qs = torch.full((1, L1.scale_stride), -7.0, dtype=torch.float32, device=DEV)
-    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP_SELECTED))
     ind_d = dev(ind.view(np.int32))
     syn_k = torch.full((NW + 2,), -1, dtype=torch.int32, device=DEV)
     qa.qa_aggregate_quantize_selected(L, ind_d, 0 if shared else NW, dev(sel.view(np.int32)), dev(sc),
@@ -401,23 +436,22 @@ def test_server_call_on_sparse_messages_matches_oracle(d, M, bucket, p, requant,
         L1s = qa.Layout.make(d, 1, bucket)
         push = torch.zeros((1, L1s.code_stride), dtype=torch.int32, device=DEV)
         cnt = torch.zeros((1, nb), dtype=torch.int32, device=DEV)
-        qa.qa_select_codes(L1s, qc, syn, 0, push, cnt)
+        qa.qa_select_codes(L1s, qc, syn, 0, push, cnt, workspace(qa.qa_workspace_bytes(L1s, qa.QA_OP_SELECT)))
         torch.cuda.synchronize()
         o_push, o_cnt = oracle.select_codes(qc_ref[0], oracle.indicator_or(ind if not shared else np.repeat(ind, M, 0), d), d, bucket)
         assert np.array_equal(host(cnt).view(np.uint32)[0], o_cnt)
-        area = 256 if bucket else (d + 15) // 16
         for k in range(nb):
             nwk = (int(o_cnt[k]) + 15) // 16
-            assert np.array_equal(host(push).view(np.uint32)[0, k * 256: k * 256 + nwk], o_push[k * area: k * area + nwk])
+            assert np.array_equal(host(push).view(np.uint32)[0, k * area: k * area + nwk], o_push[k * area: k * area + nwk])
 
 
 def test_sparse_steps_check_their_arguments():
     L = qa.Layout.make(100000, 2, 1024)
     t = torch.zeros(8, dtype=torch.int32, device=DEV)
     f = torch.zeros(8, dtype=torch.float32, device=DEV)
-    with pytest.raises(qa.QaError) as e:
+    with pytest.raises(qa.QaError) as e:                             # needs room for the decoded codes
         qa.qa_step_qcmd_selected(L, t, 100000, t, f, f, f, None, 0.1, 0.0, 1e-8, 0, None)
-    assert e.value.code == -5
+    assert e.value.code == -3
     L = qa.Layout.make(100000, 2, 4096)
     with pytest.raises(qa.QaError) as e:                             # indicator rows overlap
         qa.qa_step_qrda_selected(L, t, 5, t, f, f, f, f, 1, 0.1, 0.0, 1e-8, 0, None)
@@ -427,12 +461,14 @@ def test_sparse_steps_check_their_arguments():
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("b", [4096, 0])
 @pytest.mark.parametrize("method", ["qcmd", "qrda"])
-def test_training_with_selection_matches_oracle(method):
+def test_training_with_selection_matches_oracle(method, b):
     """Algorithm 1 with the indicator: local gradients -> indicator -> Q(S(g, I)) -> decode ->
-    fused step (alternating with the step that decodes on the fly), on the CSR stand-in
-    (d = 2^18 here), T = 25.  Both sides run the whole loop."""
-    d, M, B, b, T = 1 << 18, 8, 128, 4096, 25
+    fused step (alternating with the step that takes the sparse messages), on the CSR stand-in
+    (d = 2^18 here), T = 25.  Both sides run the whole loop.  b = 0 is the paper's own message:
+    one scale, d indicator bits and 2k code bits per worker."""
+    d, M, B, T = 1 << 18, 8, 128, 25
     eta, lam, delta = 0.1, 1e-4, 1e-8
     p = synth.csr_problem(n=1 << 13, d=d, nnz_per_row=50, M=M, seed=3)
     L = qa.Layout.make(d, M, b)
@@ -446,6 +482,8 @@ def test_training_with_selection_matches_oracle(method):
     cnt = torch.zeros((M, nb), dtype=torch.int32, device=DEV)
     sc = torch.zeros((M, nb), dtype=torch.float32, device=DEV)
     ws_g = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR))
+    ws_sel = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_SELECT))
+    ws_step = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP_SELECTED))
     ox, oG, oz = (np.zeros(d, np.float32) for _ in range(3))
     mth = qa.QA_METHOD_QCMD if method == "qcmd" else qa.QA_METHOD_QRDA
     bits_sparse = bits_dense = 0
@@ -453,8 +491,8 @@ def test_training_with_selection_matches_oracle(method):
         rows = synth.minibatch_rows(p.n, M, B, t, 3)
         qa.qa_local_grad_batched(qa.QA_CSR, A, ip, ix, p.n, d, y, dev(rows), B, M, x, g, gs, None, ws_g)
         qa.qa_indicator(L, mth, g, gs, x, G, z, t, eta, lam, delta, ind, NW)
-        qa.qa_quantize_pack_selected(L, g, gs, ind, NW, sel, cnt, sc, None)
-        qa.qa_decode_selected(L, ind, NW, sel, dense)
+        qa.qa_quantize_pack_selected(L, g, gs, ind, NW, sel, cnt, sc, None, ws_sel)
+        qa.qa_decode_selected(L, ind, NW, sel, dense, ws_sel)
         if t % 2:                                # odd steps: dense step on the decoded codes
             if method == "qcmd":
                 qa.qa_step_qcmd(L, dense, sc, x, G, z, eta, lam, delta, 0, None)
@@ -462,9 +500,9 @@ def test_training_with_selection_matches_oracle(method):
                 qa.qa_step_qrda(L, dense, sc, x, G, z, t, eta, lam, delta, 0, None)
         else:                                    # even steps: the step reads the sparse messages itself
             if method == "qcmd":
-                qa.qa_step_qcmd_selected(L, ind, NW, sel, sc, x, G, z, eta, lam, delta, 0, None)
+                qa.qa_step_qcmd_selected(L, ind, NW, sel, sc, x, G, z, eta, lam, delta, 0, ws_step)
             else:
-                qa.qa_step_qrda_selected(L, ind, NW, sel, sc, x, G, z, t, eta, lam, delta, 0, None)
+                qa.qa_step_qrda_selected(L, ind, NW, sel, sc, x, G, z, t, eta, lam, delta, 0, ws_step)
         # oracle side
         og = np.stack([oracle.local_grad_csr(p.vals, p.indptr, p.indices, d, p.y, rows[m], ox)[0] for m in range(M)])
         oind = np.stack([oracle.indicator(mth, og[m], ox, oG, oz, t, eta, lam, delta) for m in range(M)])
