@@ -60,3 +60,22 @@ def test_stochastic_quantizer_buckets_zero_and_nan():
     assert not code[:200].any() and code[250] == 0 and code[200] == -1 and code[299] == 1
     c2, _ = oracle.quantize_stochastic(v, bucket=100, seed=1, m=1)    # another worker, other draws
     assert not np.array_equal(code, c2)
+
+
+@pytest.mark.parametrize("bucket", [64, 256, 0])
+def test_bucketed_stochastic_quantizer_follows_its_definition_elementwise(bucket):
+    """Per bucket s = max|v|; component i (index in the whole vector, which is also what the
+    generator's counter takes) is kept iff u_i < |v_i| / s in binary32, and coded as its sign."""
+    rng = np.random.default_rng(bucket)
+    d, seed, step, m = 700, 99, 5, 3
+    v = (rng.standard_normal(d) * 10.0 ** rng.integers(-3, 2, d)).astype(np.float32)
+    code, sc = oracle.quantize_stochastic(v, bucket=bucket, seed=seed, step=step, m=m)
+    b = bucket or d
+    for k in range((d + b - 1) // b):
+        lo, hi = k * b, min((k + 1) * b, d)
+        s = np.abs(v[lo:hi]).max()
+        assert sc[k] == s
+        for i in range(lo, hi):
+            u = np.float32(oracle.uniform(seed, step, m, i))
+            keep = u < np.float32(np.abs(v[i])) / np.float32(s)
+            assert code[i] == (int(np.sign(v[i])) if keep else 0), (k, i)
