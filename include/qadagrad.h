@@ -185,8 +185,8 @@ int qa_quantize_pack_static(const qa_layout* layout, const float* g, int64_t g_s
  * encoding as qa_quantize_pack (codes, scales; no thresholds).  The uniform numbers are
  * Philox4x32-10 (Salmon et al., SC'11) with key = seed, counter = (i/4 low, i/4 high, worker
  * m, step), component i taking output word i%4, u = (r >> 8) * 2^-24, kept iff u < |v_i|/s in
- * binary32: the result is a pure function of (g, seed, step).  bucket must be 0 or >= 4096
- * (QA_ERR_UNSUPPORTED otherwise); no workspace. */
+ * binary32: the result is a pure function of (g, seed, step).  Any bucket of the layout; no
+ * workspace. */
 int qa_quantize_pack_stochastic(const qa_layout* layout, const float* g, int64_t g_stride,
                                 uint32_t* codes, float* scales, uint64_t seed, uint32_t step,
                                 void* stream);

@@ -386,8 +386,8 @@ __global__ __launch_bounds__(kThreads) void quantize_tile_kernel(QuantArgs a) {
   }
 }
 
-// ---- exact optimal threshold by ranking (Section 3.4: "rank the components of the gradient
-//      and treat them as potential thresholds") for one 4096-tile ---------------------------------
+// ---- exact optimal threshold by ranking (Section 3.4: the magnitudes are sorted and each one
+//      is tried as the threshold) for one 4096-tile ----------------------------------------------
 //
 // |v| of the tile is sorted in descending order (bitonic network on the bit patterns, which
 // order like the non-negative floats), prefix sums are formed in binary64, and the k that
@@ -733,14 +733,16 @@ __device__ __forceinline__ float wave_max_f32(float s) {
   return r;
 }
 
-// codes of the tile for scale s; element (j, e) of thread t is vector index base + 4*(j*256+t)+e
-__device__ __forceinline__ void stochastic_codes(const StochArgs& a, const float v[4][4], float s,
-                                                 int64_t tile, int m) {
+// codes of the tile, float4 group j of every thread with scale sj[j]; element (j, e) of thread t
+// is vector index base + 4*(j*256+t)+e
+__device__ __forceinline__ void stochastic_codes(const StochArgs& a, const float v[4][4],
+                                                 const float sj[4], int64_t tile, int m) {
   const int t = threadIdx.x;
-  const float rs = __builtin_amdgcn_rcpf(s);
   uint32_t mine = 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
+    const float s = sj[j];
+    const float rs = __builtin_amdgcn_rcpf(s);
     const uint64_t grp = (uint64_t)tile * (kTile / 4) + (uint64_t)(j * kThreads + t);
     uint32_t r[4];
     philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), (uint32_t)m, a.step, a.seed_lo, a.seed_hi, r);
@@ -786,7 +788,66 @@ __global__ __launch_bounds__(kThreads) void quantize_stochastic_tile_kernel(Stoc
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) s = lds_m[w] > s ? lds_m[w] : s;
   if (threadIdx.x == 0) a.q.scales[(int64_t)m * a.q.scale_stride + tile] = s;
-  stochastic_codes(a, v, s, tile, m);
+  const float sj[4] = {s, s, s, s};
+  stochastic_codes(a, v, sj, tile, m);
+}
+
+// Maximum over aligned segments of `seg` consecutive threads (a power of two, 16 <= seg <= 256);
+// every thread receives its segment's maximum.  Barriers when seg > 64: all threads must call.
+__device__ __forceinline__ float segment_max_f32(float v, int seg, float* lds) {
+  const int lim = seg < kWave ? seg : kWave;
+  for (int off = 1; off < lim; off <<= 1) {
+    const float o = __shfl_xor(v, off, kWave);
+    v = o > v ? o : v;
+  }
+  if (seg > kWave) {
+    const int wave = threadIdx.x / kWave;
+    __syncthreads();
+    if ((threadIdx.x % kWave) == 0) lds[wave] = v;
+    __syncthreads();
+    const int wps = seg / kWave, w0 = wave & ~(wps - 1);
+    float r = lds[w0];
+    for (int k = 1; k < wps; ++k) r = lds[w0 + k] > r ? lds[w0 + k] : r;
+    v = r;
+  }
+  return v;
+}
+
+// buckets of 64 .. 2048 elements: float4 group f = j*256 + t of the tile lies in the tile's bucket
+// f / (bucket/4), so a bucket is a segment of bucket/4 consecutive threads of one j (two j's for
+// 2048).  Not tuned: one segmented maximum per j.
+__global__ __launch_bounds__(kThreads) void quantize_stochastic_bucket_kernel(StochArgs a) {
+  __shared__ float lds_m[kWaves];
+  const int t = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int m = blockIdx.y;
+  float v[4][4];
+  load_tile_stream(a.q.g + (int64_t)m * a.q.g_stride, a.q.d, tile, v);
+  const int groups = (int)(a.q.bucket_len / 4);          // float4 groups per bucket: 16 .. 512
+  const int seg = groups < kThreads ? groups : kThreads;
+  float sj[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float s = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { const float av = fabsf(v[j][e]); s = av > s ? av : s; }
+    sj[j] = segment_max_f32(s, seg, lds_m);
+  }
+  if (groups > kThreads) {                               // 2048: j = 0,1 and j = 2,3 share a bucket
+    const float lo = sj[0] > sj[1] ? sj[0] : sj[1], hi = sj[2] > sj[3] ? sj[2] : sj[3];
+    sj[0] = sj[1] = lo; sj[2] = sj[3] = hi;
+  }
+  if ((t & (seg - 1)) == 0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int f = j * kThreads + t;
+      if (f % groups == 0) {
+        const int64_t kb = tile * (kTile / a.q.bucket_len) + f / groups;
+        if (kb < a.q.nb) a.q.scales[(int64_t)m * a.q.scale_stride + kb] = sj[j];
+      }
+    }
+  }
+  stochastic_codes(a, v, sj, tile, m);
 }
 
 // bucket > 4096 or one scale per large vector: pass 0 folds tile maxima into scales[] (which
@@ -803,7 +864,9 @@ __global__ __launch_bounds__(kThreads) void quantize_stochastic_twopass_kernel(S
     const float s = wave_max_f32(tile_abs_max(v));
     if ((threadIdx.x % kWave) == 0) atomicMax(reinterpret_cast<unsigned int*>(sc), __float_as_uint(s));
   } else {
-    stochastic_codes(a, v, *sc, tile, m);
+    const float s = *sc;
+    const float sj[4] = {s, s, s, s};
+    stochastic_codes(a, v, sj, tile, m);
   }
 }
 
@@ -986,7 +1049,6 @@ extern "C" int qa_quantize_pack_stochastic(const qa_layout* layout, const float*
   if (rc != QA_OK) return rc;
   if (!g || !codes || !scales) return QA_ERR_INVALID_ARG;
   if (g_stride < layout->d || (g_stride % 4) != 0) return QA_ERR_INVALID_ARG;
-  if (layout->bucket != 0 && layout->bucket < kTile) return QA_ERR_UNSUPPORTED;
   if (!aligned(g, 16) || !aligned(codes, 4) || !aligned(scales, 4)) return QA_ERR_ALIGNMENT;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   StochArgs a{};
@@ -998,6 +1060,11 @@ extern "C" int qa_quantize_pack_stochastic(const qa_layout* layout, const float*
   a.seed_lo = (uint32_t)seed; a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
   if (a.q.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
   const dim3 block(kThreads), grid((unsigned)a.q.ntiles, (unsigned)layout->M);
+  if (layout->bucket != 0 && layout->bucket < kTile) {
+    a.q.bucket_len = layout->bucket;
+    hipLaunchKernelGGL(quantize_stochastic_bucket_kernel, grid, block, 0, stream, a);
+    return launch_status();
+  }
   if (layout->bucket == kTile || a.q.ntiles == 1) {
     hipLaunchKernelGGL(quantize_stochastic_tile_kernel, grid, block, 0, stream, a);
     return launch_status();

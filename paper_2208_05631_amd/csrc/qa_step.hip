@@ -264,8 +264,8 @@ __device__ __forceinline__ uint32_t byte_times_8(uint32_t v, uint32_t three) {
 // Cost: 8 merges that split the words into low-bit and high-bit pairs, then the 16 merges of a
 // 4 x 2-bit gather; then per coordinate one address instruction, one LDS read and one binary64
 // addition.
-__device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t wc, uint32_t wd,
-                                             const double* __restrict__ T, double acc[16]) {
+__device__ __forceinline__ void gather_group(uint32_t wa, uint32_t wb, uint32_t wc, uint32_t wd,
+                                             uint32_t zq[4]) {
   // field i (bits 2i, 2i+1) of p0 = low bits of (a, b) for coordinate i; p1: (c, d); p2, p3: high bits
   const uint32_t p0 = (wa & 0x55555555u) | ((wb << 1) & 0xAAAAAAAAu);
   const uint32_t p1 = (wc & 0x55555555u) | ((wd << 1) & 0xAAAAAAAAu);
@@ -275,11 +275,14 @@ __device__ __forceinline__ void lookup_group(uint32_t wa, uint32_t wb, uint32_t 
   const uint32_t xo = ((p0 >> 2) & 0x33333333u) | (p1 & 0xCCCCCCCCu);
   const uint32_t ye = (p2 & 0x33333333u) | ((p3 << 2) & 0xCCCCCCCCu);
   const uint32_t yo = ((p2 >> 2) & 0x33333333u) | (p3 & 0xCCCCCCCCu);
-  uint32_t zq[4];
   zq[0] = (xe & 0x0F0F0F0Fu) | ((ye << 4) & 0xF0F0F0F0u);
   zq[1] = (xo & 0x0F0F0F0Fu) | ((yo << 4) & 0xF0F0F0F0u);
   zq[2] = ((xe >> 4) & 0x0F0F0F0Fu) | (ye & 0xF0F0F0F0u);
   zq[3] = ((xo >> 4) & 0x0F0F0F0Fu) | (yo & 0xF0F0F0F0u);
+}
+// the 16 look-ups and additions of one group from its gathered index words
+__device__ __forceinline__ void lookup_indices(const uint32_t zq[4], const double* __restrict__ T,
+                                               double acc[16]) {
   const uint32_t three = 3u;
   const char* Tb = reinterpret_cast<const char*>(T);
 #pragma unroll
@@ -398,8 +401,17 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   double dj[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) dj[j] = ((t >> j) & 1) ? (((t >> (4 + j)) & 1) ? -1.0 : 1.0) : 0.0;
-  // tables of the chunk that starts at worker m0, then the look-ups of its code words wc
-  auto chunk = [&](const uint32_t (&wc)[kChunk], int m0) {
+  // The chunk that starts at worker m0 in three parts.  gather(): the code words become index
+  // words, four per group, in the same registers' worth of space, so the code words are dead
+  // afterwards and the next chunk's can be requested into them before the tables are built:
+  // memory requests stay in flight during the table build and the look-ups at no register cost.
+  uint32_t zq[kChunk];
+  auto gather = [&](const uint32_t (&wc)[kChunk]) {
+#pragma unroll
+    for (int g = 0; g < kGroupsPerChunk; ++g)
+      gather_group(wc[4 * g], wc[4 * g + 1], wc[4 * g + 2], wc[4 * g + 3], zq + 4 * g);
+  };
+  auto tables_and_lookups = [&](int m0) {
     const int left = a.M - m0;
     const int ng = (FULL || left >= kChunk) ? kGroupsPerChunk : (left + 3) / 4;
     if (m0 > 0) __syncthreads();                         // readers of the previous tables are done
@@ -414,8 +426,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     __syncthreads();
 #pragma unroll
     for (int g = 0; g < kGroupsPerChunk; ++g)
-      if (FULL || g < ng)
-        lookup_group(wc[4 * g], wc[4 * g + 1], wc[4 * g + 2], wc[4 * g + 3], tab + g * 256, acc);
+      if (FULL || g < ng) lookup_indices(zq + 4 * g, tab + g * 256, acc);
+  };
+  auto chunk = [&](const uint32_t (&wc)[kChunk], int m0) {
+    gather(wc);
+    tables_and_lookups(m0);
   };
 
   if (SPARSE) {
@@ -504,15 +519,27 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       if ((t & 1) == 0 && iw < NW) a.ind_syn[iw] = syn | (other << 16);
     }
   } else if (reorder_ok) {
+    // The kernels that go on to update the state request the next chunk right after the gather.
+    // The aggregate-only kernels do not: they are small enough for five waves per SIMD, which
+    // the longer live ranges would cost them (measured: 3.65 ms against 3.96 ms at d = 2^30, M = 64).
+    constexpr bool kEarlyLoads = MODE != kAggregate;
     for (int m0 = 0; m0 < a.M; m0 += kChunk) {
-      if (m0 > 0) {
+      if (!kEarlyLoads && m0 > 0) {
         const int left = a.M - m0;
         const uint32_t* cc = ctile + (int64_t)m0 * a.code_stride;
 #pragma unroll
         for (int i = 0; i < kChunk; ++i)
           w[i] = (FULL || i < left) ? stream_load(cc + (int64_t)i * a.code_stride, tw4, row_bytes) : 0u;
       }
-      chunk(w, m0);
+      gather(w);
+      const int left = a.M - (m0 + kChunk);                // workers after this chunk
+      if (kEarlyLoads && left > 0) {
+        const uint32_t* cc = ctile + (int64_t)(m0 + kChunk) * a.code_stride;
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+          w[i] = (FULL || i < left) ? stream_load(cc + (int64_t)i * a.code_stride, tw4, row_bytes) : 0u;
+      }
+      tables_and_lookups(m0);
     }
   } else {
     // ordered loop, as the sum is written: worker 0, 1, 2, ...; eight code words are requested

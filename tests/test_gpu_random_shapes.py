@@ -212,7 +212,7 @@ def test_random_shapes_of_the_other_calls_match_oracle_bit_for_bit(seed):
         assert np.array_equal(host(codes).view(np.uint32)[:, :L2.words], c_ref), (what, "exact codes")
         assert same_bits(host(scales)[:, :L2.n_buckets], s_ref), (what, "exact scales")
         rseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 1000))
-        bs = int(rng.choice([0, 4096, 8192]))
+        bs = int(rng.choice([0, 64, 256, 2048, 4096, 8192]))
         Ls = qa.Layout.make(d2, M, bs)
         oc, osc = oracle.quantize_pack_stochastic(g2, bucket=bs, seed=rseed, step=step)
         codes = torch.full((M, Ls.code_stride), -1, dtype=torch.int32, device=DEV)
