@@ -48,6 +48,9 @@ WORKLOADS = {
     "sparse_train": dict(train="csr", d=1 << 20, n=1 << 16, M=16, B=256, bucket=4096, lam=1e-4),
     # worker/server side of the sparse encoding: indicator -> Q(S(g, I)) -> decode
     "select": dict(select=True, d=1 << 28, M=8, bucket=4096),
+    # the same with the paper's own message: one scale, d indicator bits, one stream of 2k code bits
+    "select_one_scale": dict(select=True, d=1 << 28, M=8, bucket=0),
+    "select_bucket_256": dict(select=True, d=1 << 28, M=8, bucket=256),
     # stochastic (TernGrad/Philox) quantizer against the threshold quantizer on the same input
     "stochastic": dict(stoch=True, d=1 << 28, M=4, bucket=4096),
     # a convolutional net's parameter list in one flat vector, each tensor quantized on its own
@@ -156,12 +159,17 @@ def select_bench(args, wl, qa, synth, torch, np, dev):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / args.steps
 
+    def wsp(op):
+        n = qa.qa_workspace_bytes(L, op)
+        return torch.empty(n, dtype=torch.uint8, device=dev) if n else None
+
+    ws_sel, ws_step = wsp(qa.QA_OP_SELECT), wsp(qa.QA_OP_STEP_SELECTED)
     t_ind = timed(lambda: qa.qa_indicator(L, qa.QA_METHOD_QCMD, g, d, x, G, z, 1, eta, lam, delta, ind, NW))
-    t_q = timed(lambda: qa.qa_quantize_pack_selected(L, g, d, ind, NW, sel, cnt, sc, None))
-    t_dec = timed(lambda: qa.qa_decode_selected(L, ind, NW, sel, dense))
+    t_q = timed(lambda: qa.qa_quantize_pack_selected(L, g, d, ind, NW, sel, cnt, sc, None, ws_sel))
+    t_dec = timed(lambda: qa.qa_decode_selected(L, ind, NW, sel, dense, ws_sel))
     again = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
     cnt2 = torch.zeros((M, nb), dtype=torch.int32, device=dev)
-    t_selc = timed(lambda: qa.qa_select_codes(L, dense, ind, NW, again, cnt2))   # the pull direction's S
+    t_selc = timed(lambda: qa.qa_select_codes(L, dense, ind, NW, again, cnt2, ws_sel))   # the pull direction's S
     # the server's update: dense step on the decoded codes vs the step that reads the sparse
     # messages directly (state copies so that both start from the same x, G, z each time)
     xs, Gs, zs = x.clone(), G.clone(), z.clone()
@@ -169,7 +177,7 @@ def select_bench(args, wl, qa, synth, torch, np, dev):
                                                  qa.QA_REQUANT_NONE, None))
     xs.copy_(x); Gs.copy_(G); zs.copy_(z)
     t_step_sparse = timed(lambda: qa.qa_step_qcmd_selected(L, ind, NW, sel, sc, xs, Gs, zs, eta, lam,
-                                                           delta, qa.QA_REQUANT_NONE, None))
+                                                           delta, qa.QA_REQUANT_NONE, ws_step))
     k = int(cnt.sum().item())
     frac = k / (M * d)
     by = {"indicator": (4 * M + 8 + M / 8) * d, "quantize_selected": M * d * (4 + 1 / 8) + k / 4,
@@ -183,7 +191,7 @@ def select_bench(args, wl, qa, synth, torch, np, dev):
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_ind + t_q + t_dec,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
            "data": "synthetic",
-           "config": {"workload": f"select: d={d}, M={M}, bucket={bucket}, selected fraction {frac:.4f}"},
+           "config": {"workload": f"{args.workload}: d={d}, M={M}, bucket={bucket}, selected fraction {frac:.4f}"},
            "kernels": {n: {"ms": ms[n], "algorithmic_GBps": by[n] / (ms[n] * 1e-3) / 1e9,
                            "frac_of_peak": by[n] / (ms[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS} for n in ms},
            "message_bits_vs_dense": (M * (32 * nb + d) + 2 * k) / (M * (32 * nb + 2 * d))}

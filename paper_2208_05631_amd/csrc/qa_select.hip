@@ -450,6 +450,20 @@ __device__ __forceinline__ uint32_t live_mask16(const SelArgs& a, const uint32_t
   return left >= 16 ? m : (left > 0 ? (m & ((1u << left) - 1u)) : 0u);
 }
 
+// the thread's 16 gradient components (coordinates 16t .. 16t+15 of the tile), 0 beyond d
+__device__ __forceinline__ void load16(const float* __restrict__ g, int64_t d, int64_t i0, float v[16]) {
+  if (i0 + 16 <= d) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 f = *reinterpret_cast<const float4*>(g + i0 + 4 * q);
+      v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = (i0 + j < d) ? g[i0 + j] : 0.0f;
+  }
+}
+
 // Where the thread's selected codes sit: `pos` counts 2-bit codes from bit 0 of word `base[0]`.
 struct StreamPos {
   int64_t base;        // word offset into the worker's sel_codes row (the same for the whole tile)
@@ -529,12 +543,12 @@ __global__ __launch_bounds__(kThreads) void gsel_count_kernel(SelArgs a) {
   uint32_t K;
   block_exclusive_scan((uint32_t)__popc(mask), lds_w, &K);
   if (HAS_G) {
-    const float* g = a.g + (int64_t)m * a.g_stride;
-    const int64_t i0 = tile * kTile + 16 * (int64_t)t;
+    float v[16];
+    load16(a.g + (int64_t)m * a.g_stride, a.d, tile * kTile + 16 * (int64_t)t, v);
     double s1 = 0.0;
 #pragma unroll
     for (int j = 0; j < 16; ++j)
-      if ((mask >> j) & 1u) s1 += (double)fabsf(g[i0 + j]);     // marked bits lie below d
+      if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
     const double S1 = block_sum_f64(s1, lds_d);
     if (t == 0) a.ws_s1[(int64_t)m * a.ntiles + tile] = S1;
   }
@@ -542,8 +556,10 @@ __global__ __launch_bounds__(kThreads) void gsel_count_kernel(SelArgs a) {
 }
 
 // pass 2: per (bucket, worker), in tile order: each tile's first position in the bucket's stream,
-// the bucket's count and (with a gradient) its threshold.  One work-group per bucket; the tiles
-// are taken 256 at a time with a running offset, so the order of the binary64 additions is fixed.
+// the bucket's count and (with a gradient) its threshold.  One work-group per bucket; a round takes
+// 256 x 16 consecutive tiles (thread t the 16 from t*16 on) with a running offset, so the order
+// of the binary64 additions is fixed.
+constexpr int kScanRun = 16;
 template <bool HAS_G>
 __global__ __launch_bounds__(kThreads) void gsel_scan_kernel(SelArgs a) {
   __shared__ uint32_t lds_w[kWaves];
@@ -554,19 +570,27 @@ __global__ __launch_bounds__(kThreads) void gsel_scan_kernel(SelArgs a) {
   const int64_t t0 = k * a.tiles_per_bucket;
   const int64_t t1 = t0 + a.tiles_per_bucket < a.ntiles ? t0 + a.tiles_per_bucket : a.ntiles;
   const uint32_t* cnt = a.ws_count + (int64_t)m * a.ntiles;
+  const double* s1p = a.ws_s1 + (int64_t)m * a.ntiles;
+  int64_t* start = a.ws_start + (int64_t)m * a.ntiles;
   int64_t running = 0;
   double s1 = 0.0;
-  for (int64_t i = t0; i < t1; i += kThreads) {
-    const int64_t j = i + t;
-    const uint32_t c = j < t1 ? cnt[j] : 0u;
+  for (int64_t i = t0; i < t1; i += (int64_t)kThreads * kScanRun) {
+    const int64_t j0 = i + (int64_t)t * kScanRun;
+    uint32_t c[kScanRun], mine = 0;
+#pragma unroll
+    for (int u = 0; u < kScanRun; ++u) {
+      c[u] = j0 + u < t1 ? cnt[j0 + u] : 0u;
+      mine += c[u];
+      if (HAS_G && j0 + u < t1) s1 += s1p[j0 + u];
+    }
     uint32_t total;
-    const uint32_t ex = block_exclusive_scan(c, lds_w, &total);
-    if (j < t1) {
-      a.ws_start[(int64_t)m * a.ntiles + j] = running + ex;
-      if (HAS_G) s1 += a.ws_s1[(int64_t)m * a.ntiles + j];
+    uint32_t ex = block_exclusive_scan(mine, lds_w, &total);   // at most 256 x 16 x 4096 = 2^24
+#pragma unroll
+    for (int u = 0; u < kScanRun; ++u) {
+      if (j0 + u < t1) start[j0 + u] = running + ex;
+      ex += c[u];
     }
     running += total;
-    __syncthreads();                                     // lds_w is reused by the next round
   }
   if (HAS_G) s1 = block_sum_f64(s1, lds_d);
   if (t == 0) {
@@ -603,10 +627,8 @@ __global__ __launch_bounds__(kThreads) void gsel_quantize_kernel(SelArgs a) {
   const int m = blockIdx.y;
   const float* g = a.g + (int64_t)m * a.g_stride;
   const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
-  const int64_t i0 = tile * kTile + 16 * (int64_t)t;
   float v[16];
-#pragma unroll
-  for (int j = 0; j < 16; ++j) v[j] = (i0 + j < a.d) ? g[i0 + j] : 0.0f;
+  load16(g, a.d, tile * kTile + 16 * (int64_t)t, v);
   stream[t] = 0u;
   if (t < 2) stream[kTileWords + t] = 0u;
   const uint32_t n = (uint32_t)__popc(mask);
