@@ -192,6 +192,29 @@ __device__ __forceinline__ uint32_t cached_load(const uint32_t* row, uint32_t by
       const_cast<uint32_t*>(row), 0, (int)row_bytes, 0x00020000);
   return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0);
 }
+// A whole tile row of one worker (256 code words) straight into LDS with one instruction of one
+// wave, no vector registers involved: lane l brings bytes [16 l, 16 l + 16) of the row to the same
+// offsets of lds_row; bytes at or beyond row_bytes arrive as 0.  The data is in LDS once the
+// issuing wave's count of outstanding vector-memory operations has reached zero; other waves see
+// it after a barrier that follows that.
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+__device__ __forceinline__ void stream_row_to_lds(const uint32_t* row, uint32_t row_bytes,
+                                                  uint32_t* lds_row) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(row), 0, (int)row_bytes, 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)lds_row, 16,
+                                           (int)(threadIdx.x % kWave) * 16, 0, 0, 2 /* nt */);
+}
+__device__ __forceinline__ void wait_vector_memory() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0), the other counters untouched
+}
+// Work-group barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for
+// outstanding vector-memory operations, so rows on their way into LDS stay in flight across it.
+// (A fence would wait for them: to the compiler they are pending writes to LDS.)  The asm
+// statement is also a compiler-level memory barrier: no LDS access moves across it.
+__device__ __forceinline__ void barrier_lds_only() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 __device__ __forceinline__ void stream_store4(float* p, const float4& v) {
   floatx4 t = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(t, reinterpret_cast<floatx4*>(p));
@@ -316,8 +339,14 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   constexpr bool FULL = NGT > 1;
   constexpr int kGroupsPerChunk = NGT >= 1 ? NGT : kMaxGroups;
   constexpr int kChunk = 4 * kGroupsPerChunk;
-  constexpr int kTabEntries = kGroupsPerChunk * 256 > kTile / 2 ? kGroupsPerChunk * 256 : kTile / 2;
+  // The server's kernel that sends Q(SynQ) stages complete chunks of code words through LDS (see
+  // the loop over chunks below).  It ends before the hand-over of q, so its tables' array is small.
+  constexpr bool kStaged = MODE == kAggregate && REQUANT && FULL && !SPARSE;
+  constexpr int kTabDoubles = kGroupsPerChunk * 256;
+  constexpr int kHandoverDoubles = (MODE == kAggregate && REQUANT) ? 0 : kTile / 2;
+  constexpr int kTabEntries = kTabDoubles > kHandoverDoubles ? kTabDoubles : kHandoverDoubles;
   __shared__ double tab[kTabEntries];                   // also carries q (4096 floats) at the end
+  __shared__ uint32_t stage[kStaged ? kChunk * kTileWords : 1];
   __shared__ double s_scale[kChunk];
   __shared__ double lds_d[kWaves];
   __shared__ uint32_t lds_u[kWaves];
@@ -353,7 +382,18 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 
   // ---- request the first chunk of code words ----
   uint32_t w[kChunk];
-  if (!SPARSE) {
+  // wave v brings rows v*kChunk/4 .. of the chunk that starts at worker m0 into the staging area
+  auto stage_request = [&](int m0) {
+    const int wave = __builtin_amdgcn_readfirstlane(t / kWave);   // known uniform: scalar addressing
+#pragma unroll
+    for (int i = 0; i < kChunk / kWaves; ++i) {
+      const int r = wave * (kChunk / kWaves) + i;
+      stream_row_to_lds(ctile + (int64_t)(m0 + r) * a.code_stride, row_bytes, stage + r * kTileWords);
+    }
+  };
+  if (kStaged) {
+    if (!own_scales) stage_request(0);
+  } else if (!SPARSE) {
     const int left = own_scales ? 0 : a.M;
 #pragma unroll
     for (int i = 0; i < kChunk; ++i)
@@ -406,6 +446,11 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   // afterwards and the next chunk's can be requested into them before the tables are built:
   // memory requests stay in flight during the table build and the look-ups at no register cost.
   uint32_t zq[kChunk];
+  // Thread i < kChunk fetches worker (chunk start + i)'s scale for the tile.
+  auto chunk_scale = [&](int m0) -> float {
+    return (t < kChunk && m0 + t < a.M && !own_scales) ? sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0f;
+  };
+  float sc_ahead = kStaged ? chunk_scale(0) : 0.0f;     // (staged loop only: elsewhere it measured slower)
   auto gather = [&](const uint32_t (&wc)[kChunk]) {
 #pragma unroll
     for (int g = 0; g < kGroupsPerChunk; ++g)
@@ -415,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     const int left = a.M - m0;
     const int ng = (FULL || left >= kChunk) ? kGroupsPerChunk : (left + 3) / 4;
     if (m0 > 0) __syncthreads();                         // readers of the previous tables are done
-    if (t < kChunk) s_scale[t] = t < left ? (double)sc[(int64_t)(m0 + t) * a.scale_stride] : 0.0;
+    if (t < kChunk) s_scale[t] = (double)chunk_scale(m0);
     __syncthreads();
     for (int g = 0; g < ng; ++g) {
       const double e = fma(dj[3], s_scale[4 * g + 3],
@@ -518,6 +563,32 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       const int64_t iw = tile * (kTile / 32) + (t >> 1);
       if ((t & 1) == 0 && iw < NW) a.ind_syn[iw] = syn | (other << 16);
     }
+  } else if (kStaged && reorder_ok) {
+    // The next chunk's code words travel from memory into LDS while this chunk's tables are built
+    // and read, at no cost in vector registers: six waves per SIMD with requests in flight nearly
+    // all the time (measured at d = 2^30, M = 64: 3.48 ms against 3.63 ms with register loads;
+    // the kernel that writes the average out, already at the rate of a plain copy, gained nothing).
+    for (int m0 = 0; m0 < a.M; m0 += kChunk) {
+      wait_vector_memory();                              // this wave's rows of the chunk have landed
+      __syncthreads();                                   // ... everyone's; the previous tables are free
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) w[i] = stage[i * kTileWords + t];
+      if (t < kChunk) s_scale[t] = (double)sc_ahead;
+      gather(w);
+      __syncthreads();                                   // the staging area has been read by all
+      sc_ahead = chunk_scale(m0 + kChunk);
+      if (m0 + kChunk < a.M) stage_request(m0 + kChunk);
+#pragma unroll
+      for (int g = 0; g < kGroupsPerChunk; ++g) {
+        const double e = fma(dj[3], s_scale[4 * g + 3],
+                             fma(dj[2], s_scale[4 * g + 2],
+                                 fma(dj[1], s_scale[4 * g + 1], dj[0] * s_scale[4 * g])));
+        tab[g * 256 + t] = e;
+      }
+      barrier_lds_only();                                // tables complete; the rows stay in flight
+#pragma unroll
+      for (int g = 0; g < kGroupsPerChunk; ++g) lookup_indices(zq + 4 * g, tab + g * 256, acc);
+    }
   } else if (reorder_ok) {
     // The kernels that go on to update the state request the next chunk right after the gather.
     // The aggregate-only kernels do not: they are small enough for five waves per SIMD, which
@@ -544,6 +615,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   } else {
     // ordered loop, as the sum is written: worker 0, 1, 2, ...; eight code words are requested
     // at a time so that their latencies overlap
+    if (kStaged) wait_vector_memory();                   // rows requested into LDS above: unused here
     for (int m0 = 0; m0 < a.M; m0 += 8) {
       uint32_t wv[8];
       double sv[8];

@@ -147,7 +147,11 @@ def test_quantize_degenerate_inputs(bucket):
 # ------------------------------------------------------------------ aggregate
 
 @pytest.mark.parametrize("d,M,bucket", [(1, 1, 0), (1000, 4, 0), (5000, 3, 64), (70001, 6, 4096),
-                                        (70001, 64, 4096), (33333, 7, 16384), (20000, 33, 1024)])
+                                        (70001, 64, 4096), (33333, 7, 16384), (20000, 33, 1024),
+                                        # complete chunks of 16 and of 8 workers whose last tile ends
+                                        # inside a 16-byte group of a row of code words
+                                        (9000, 48, 4096), (8192 + 16 * 5 + 3, 8, 4096), (70001, 24, 0),
+                                        (4096 + 16 * 62 + 1, 32, 8192)])
 def test_aggregate_matches_oracle(d, M, bucket):
     g = make_grad("mixed_scale" if M <= 7 else "gauss", M, d, seed=M + d)
     oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
