@@ -32,6 +32,11 @@ struct SelArgs {
   uint32_t* ws_count; double* ws_s1; double* ws_s2; uint32_t* ws_c2; int64_t* ws_start; float* ws_thr;
 };
 
+// Granularity of a sparse message's buckets: one 4096-tile each; 64 .. 2048 coordinates, inside a
+// tile (bucket j of a tile = the segment of seg = bucket/16 consecutive code words, its compact
+// stream starts at word j*seg of the tile's 256 words); or spanning several tiles.
+enum SelKind { kSelTile, kSelLocal, kSelMulti };
+
 // The worker's own would-be parameter from gradient component g (same operation order as the
 // update of the fused steps).
 __device__ __forceinline__ float local_update(const SelArgs& a, float g, float x, float G, float z) {
@@ -280,6 +285,13 @@ __global__ __launch_bounds__(kThreads) void quantize_selected_kernel(SelArgs a) 
 // fields four components at a time through the deposit table (copied to LDS once per block).
 constexpr int kDecodeTiles = 2;
 
+// kSelMulti: buckets that span tiles (and one scale per message of a long vector): a tile's codes
+// start at code `start` of its bucket's stream, start being the tile's entry of the scan in the
+// workspace: word start/16 of the bucket's area, code start%16 of that word.
+// kSelLocal: a word's codes are counted from the start of its own bucket's stream, i.e. its
+// position in the tile minus the position of the bucket's first word (same j and a lane of the
+// wave for buckets up to 1024 coordinates, lane 0 of an even j for 2048).
+template <int KIND>
 __global__ __launch_bounds__(kThreads) void decode_selected_kernel(SelArgs a) {
   __shared__ uint8_t lut[16 * 256];
   reinterpret_cast<uint4*>(lut)[threadIdx.x] = reinterpret_cast<const uint4*>(kDepositLut.v)[threadIdx.x];
@@ -312,20 +324,40 @@ __global__ __launch_bounds__(kThreads) void decode_selected_kernel(SelArgs a) {
   for (int u = 0; u < kDecodeTiles; ++u) {
     // clamped for tiles beyond the vector: their masks are 0, so nothing is read through it
     const int64_t tile = (tile0 + u) * kTile < a.d ? tile0 + u : 0;
-    const uint32_t* sel = a.sel_in + (int64_t)m * a.code_stride + tile * kTileWords;
+    const uint32_t* sel = a.sel_in + (int64_t)m * a.code_stride;
     uint32_t start = 0;                                  // marked components in earlier j
+    if (KIND == kSelMulti) {
+      const int64_t first = a.ws_start[(int64_t)m * a.ntiles + tile];
+      sel += (tile / a.tiles_per_bucket) * a.area_words + (first >> 4);
+      start = (uint32_t)(first & 15);
+    } else {
+      sel += tile * kTileWords;
+    }
+    uint32_t ex[4];                                      // marked components of the tile before the word
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      // the word's n <= 16 codes are codes before .. before+n-1 of the tile's compact stream:
-      // word before/16 and, only if they cross a word boundary, the next one; both lie below
-      // ceil(K/16) <= the words that exist for this tile (K = marked components of the tile)
-      const uint32_t n = (uint32_t)__popc(mask[u][j]);
-      const uint32_t before = start + incl[u][j] - n;
+      ex[j] = start + incl[u][j] - (uint32_t)__popc(mask[u][j]);
       start += (uint32_t)__builtin_amdgcn_readlane((int)incl[u][j], kWave - 1);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // the word's n <= 16 codes are codes before .. before+n-1 of the compact stream `src`:
+      // word before/16 and, only if they cross a word boundary, the next one; both lie below
+      // ceil(K/16) <= the words that exist for the stream (K = its marked components)
+      const uint32_t n = (uint32_t)__popc(mask[u][j]);
+      uint32_t before = ex[j];
+      const uint32_t* src = sel;
+      if (KIND == kSelLocal) {
+        const int s0 = (j * 64 + lane) & ~(a.seg - 1);     // first code word of the bucket
+        const uint32_t e0 = a.seg <= kWave ? (uint32_t)__shfl((int)ex[j], lane & ~(a.seg - 1), kWave)
+                                           : (uint32_t)__builtin_amdgcn_readlane((int)ex[j & ~1], 0);
+        before = ex[j] - e0;
+        src = sel + s0;
+      }
       const uint32_t w0 = before / 16;
       sh[u][j] = 2 * (before % 16);
-      win_lo[u][j] = n != 0u ? sel[w0] : 0u;
-      win_hi[u][j] = (before % 16) + n > 16u ? sel[w0 + 1] : 0u;
+      win_lo[u][j] = n != 0u ? src[w0] : 0u;
+      win_hi[u][j] = (before % 16) + n > 16u ? src[w0 + 1] : 0u;
     }
   }
   __syncthreads();                                       // the table is in LDS
@@ -367,9 +399,15 @@ __device__ const DepositLut kExtractLut = make_extract_lut();
 // tile (as in the decoder).  Each word's marked codes are packed through the extract table and
 // appended at their position in the tile's compact stream, which is assembled in LDS (one area
 // per wave) and written out in whole words.
+// kSelMulti (buckets that span tiles): the tile's codes start at code start%16 of word start/16
+// of the bucket's area (start from the scan in the workspace); words that a neighbouring tile may
+// also touch are OR-ed into memory that was zeroed before, the others stored.
+// kSelLocal (buckets inside a tile): bucket j's stream starts at word j*seg; its first
+// ceil(K_j/16) words are written, and K_j by the bucket's first lane.
+template <int KIND>
 __global__ __launch_bounds__(kThreads) void select_codes_kernel(SelArgs a) {
   __shared__ uint8_t lut[16 * 256];
-  __shared__ uint32_t stream_all[kWaves][kTileWords + 1];
+  __shared__ uint32_t stream_all[kWaves][kTileWords + 2];
   reinterpret_cast<uint4*>(lut)[threadIdx.x] = reinterpret_cast<const uint4*>(kExtractLut.v)[threadIdx.x];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   uint32_t* stream = stream_all[wave];
@@ -394,16 +432,41 @@ __global__ __launch_bounds__(kThreads) void select_codes_kernel(SelArgs a) {
     word[j] = lo | (raw & (lo << 1));                    // reserved pattern 10 reads as 0
     stream[wl] = 0u;
   }
-  if (lane == 0) stream[kTileWords] = 0u;
+  if (lane < 2) stream[kTileWords + lane] = 0u;
 #pragma unroll
   for (int j = 0; j < 4; ++j) incl[j] = wave_inclusive_scan_u32((uint32_t)__popc(mask[j]));
   __syncthreads();                                       // table and zeroed streams are in LDS
-  uint32_t start = 0;
+  int64_t base = tile * kTileWords;
+  uint32_t first = 0;
+  if (KIND == kSelMulti) {
+    const int64_t st = a.ws_start[(int64_t)m * a.ntiles + tile];
+    base = (tile / a.tiles_per_bucket) * a.area_words + (st >> 4);
+    first = (uint32_t)(st & 15);
+  }
+  uint32_t start = first, ex[4], total[4], in_bucket[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    total[j] = (uint32_t)__builtin_amdgcn_readlane((int)incl[j], kWave - 1);
+    ex[j] = start + incl[j] - (uint32_t)__popc(mask[j]);
+    start += total[j];
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t n = (uint32_t)__popc(mask[j]);
-    const uint32_t before = start + incl[j] - n;
-    start += (uint32_t)__builtin_amdgcn_readlane((int)incl[j], kWave - 1);
+    uint32_t before = ex[j];
+    if (KIND == kSelLocal) {
+      const int s0 = (j * 64 + lane) & ~(a.seg - 1);       // first code word of the bucket
+      uint32_t e0, Kb = n;
+      if (a.seg <= kWave) {
+        e0 = (uint32_t)__shfl((int)ex[j], lane & ~(a.seg - 1), kWave);
+        for (int off = 1; off < a.seg; off <<= 1) Kb += (uint32_t)__shfl_xor((int)Kb, off, kWave);
+      } else {
+        e0 = (uint32_t)__builtin_amdgcn_readlane((int)ex[j & ~1], 0);
+        Kb = total[j] + total[j ^ 1];
+      }
+      in_bucket[j] = Kb;
+      before = 16u * (uint32_t)s0 + (ex[j] - e0);
+    }
     uint32_t bits = 0, filled = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -419,23 +482,40 @@ __global__ __launch_bounds__(kThreads) void select_codes_kernel(SelArgs a) {
   }
   __syncthreads();
   if (exists) {
-    const uint32_t K = start, nwords = (K + 15) / 16;
-    uint32_t* out = a.sel_codes + (int64_t)m * a.code_stride + tile * kTileWords;
+    const uint32_t end = start, nwords = (end + 15) / 16;  // one past the tile's last code
+    uint32_t* out = a.sel_codes + (int64_t)m * a.code_stride + base;
+    if (KIND == kSelMulti) {
+      if (end != first)
+        for (uint32_t w = lane; w < nwords; w += kWave) {  // at most 257 words
+          const bool shared = (w == 0 && first != 0) || (w == nwords - 1 && (end % 16) != 0);
+          if (shared) atomicOr(&out[w], stream[w]);
+          else out[w] = stream[w];
+        }
+    } else if (KIND == kSelLocal) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if ((uint32_t)(j * 64 + lane) < nwords) out[j * 64 + lane] = stream[j * 64 + lane];
-    if (lane == 0) a.counts[(int64_t)m * a.scale_stride + tile] = K;
+      for (int j = 0; j < 4; ++j) {
+        const int wl = j * 64 + lane, s0 = wl & ~(a.seg - 1);
+        if ((uint32_t)(wl - s0) < (in_bucket[j] + 15) / 16) out[wl] = stream[wl];
+        const int64_t kb = (tile * kTile + 16 * (int64_t)wl) / (16 * (int64_t)a.seg);
+        if (wl == s0 && kb < a.nb) a.counts[(int64_t)m * a.scale_stride + kb] = in_bucket[j];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if ((uint32_t)(j * 64 + lane) < nwords) out[j * 64 + lane] = stream[j * 64 + lane];
+      if (lane == 0) a.counts[(int64_t)m * a.scale_stride + tile] = end;
+    }
   }
 }
 
 // ---- any bucket size -------------------------------------------------------------------------
 //
-// The kernels above are specialised for one threshold/scale per 4096-tile.  The general ones
-// below take every other granularity of the layout, in the plain mapping "thread t = code word t
-// of the tile" (16 coordinates), and are not tuned:
+// The decoder and S above take every granularity (their KIND parameter); the quantizer above is
+// the one for one threshold/scale per 4096-tile.  Below: the quantizers of the other
+// granularities and the passes that buckets spanning tiles need.
 //   * buckets of 64 .. 2048 coordinates lie inside a tile: bucket j of a tile is the segment of
-//     seg = bucket/16 consecutive threads, its compact stream starts at word j*seg of the tile's
-//     256 words, and a thread's codes start at (selected components of its bucket before it);
+//     seg = bucket/16 consecutive code words, its compact stream starts at word j*seg of the
+//     tile's 256 words, and a word's codes start at (selected components of its bucket before it);
 //   * buckets above 4096, and one scale for a vector of several tiles (the 32 + d + 2k bit
 //     message of the Encode paragraph), span tiles: a first pass counts every tile's selected
 //     components, a scan per bucket turns the counts into each tile's first position in the
@@ -464,39 +544,25 @@ __device__ __forceinline__ void load16(const float* __restrict__ g, int64_t d, i
   }
 }
 
-// Where the thread's selected codes sit: `pos` counts 2-bit codes from bit 0 of word `base[0]`.
+// Where the thread's selected codes sit inside a tile whose buckets are segments of a.seg threads.
 struct StreamPos {
-  int64_t base;        // word offset into the worker's sel_codes row (the same for the whole tile)
-  uint32_t pos;        // this thread's first selected code
-  uint32_t in_bucket;  // selected components of the thread's bucket (tile-local buckets only)
-  uint32_t in_tile;    // selected components of the tile
-  uint32_t first;      // position of the tile's first selected code (multi-tile: start % 16)
+  uint32_t pos;        // this thread's first selected code, counted from the tile's word 0
+  uint32_t in_bucket;  // selected components of the thread's bucket
 };
 
 // n = number of selected components of this thread.  Contains barriers.
-template <bool MULTI>
-__device__ __forceinline__ StreamPos stream_position(const SelArgs& a, int64_t tile, int m, uint32_t n,
-                                                     uint32_t* lds_w, uint32_t* lds_ex) {
+__device__ __forceinline__ StreamPos stream_position(const SelArgs& a, uint32_t n, uint32_t* lds_w,
+                                                     uint32_t* lds_ex) {
   StreamPos p;
   const int t = threadIdx.x;
-  const uint32_t ex = block_exclusive_scan(n, lds_w, &p.in_tile);
-  if (MULTI) {
-    const int64_t start = a.ws_start[(int64_t)m * a.ntiles + tile];
-    const int64_t k = tile / a.tiles_per_bucket;
-    p.base = k * a.area_words + (start >> 4);
-    p.first = (uint32_t)(start & 15);
-    p.pos = p.first + ex;
-    p.in_bucket = 0;
-  } else {
-    lds_ex[t] = ex;
-    if (t == 0) lds_ex[kThreads] = p.in_tile;
-    __syncthreads();
-    const int s0 = t & ~(a.seg - 1);
-    p.in_bucket = lds_ex[s0 + a.seg] - lds_ex[s0];
-    p.base = tile * kTileWords;
-    p.first = 0;
-    p.pos = 16u * (uint32_t)s0 + (ex - lds_ex[s0]);
-  }
+  uint32_t in_tile;
+  const uint32_t ex = block_exclusive_scan(n, lds_w, &in_tile);
+  lds_ex[t] = ex;
+  if (t == 0) lds_ex[kThreads] = in_tile;
+  __syncthreads();
+  const int s0 = t & ~(a.seg - 1);
+  p.in_bucket = lds_ex[s0 + a.seg] - lds_ex[s0];
+  p.pos = 16u * (uint32_t)s0 + (ex - lds_ex[s0]);
   return p;
 }
 
@@ -508,31 +574,8 @@ __device__ __forceinline__ void stream_append(uint32_t* stream, uint32_t pos, ui
   if (sh && (2 * n + sh > 32)) atomicOr(&stream[word + 1], bits >> (32 - sh));
 }
 
-// Write the tile's part of the stream from LDS.  Tile-local buckets: the first ceil(K/16) words
-// of each bucket's area, nothing else.  Multi-tile buckets: the words the tile's codes touch;
-// a word that other tiles may also touch is OR-ed into (it was zeroed before), the others stored.
-template <bool MULTI>
-__device__ __forceinline__ void stream_flush(const SelArgs& a, const StreamPos& p, const uint32_t* stream,
-                                             uint32_t* row) {
-  const int t = threadIdx.x;
-  if (MULTI) {
-    const uint32_t end = p.first + p.in_tile;              // one past the tile's last code
-    const uint32_t words = (end + 15) / 16;
-    if (p.in_tile == 0) return;
-    for (uint32_t w = t; w < words; w += kThreads) {       // at most 257 words
-      const bool shared = (w == 0 && p.first != 0) || (w == words - 1 && (end % 16) != 0);
-      if (shared) atomicOr(&row[p.base + w], stream[w]);
-      else row[p.base + w] = stream[w];
-    }
-  } else {
-    const int s0 = t & ~(a.seg - 1);
-    if ((uint32_t)(t - s0) < (p.in_bucket + 15) / 16) row[p.base + t] = stream[t];
-  }
-}
-
-// pass 1 of the multi-tile path: selected components of every tile and, with a gradient, the sum
-// of their magnitudes
-template <bool HAS_G>
+// pass 1 of the multi-tile quantizer: selected components of every tile and the sum of their
+// magnitudes
 __global__ __launch_bounds__(kThreads) void gsel_count_kernel(SelArgs a) {
   __shared__ uint32_t lds_w[kWaves];
   __shared__ double lds_d[kWaves];
@@ -542,17 +585,46 @@ __global__ __launch_bounds__(kThreads) void gsel_count_kernel(SelArgs a) {
   const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
   uint32_t K;
   block_exclusive_scan((uint32_t)__popc(mask), lds_w, &K);
-  if (HAS_G) {
-    float v[16];
-    load16(a.g + (int64_t)m * a.g_stride, a.d, tile * kTile + 16 * (int64_t)t, v);
-    double s1 = 0.0;
+  float v[16];
+  load16(a.g + (int64_t)m * a.g_stride, a.d, tile * kTile + 16 * (int64_t)t, v);
+  double s1 = 0.0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
-    const double S1 = block_sum_f64(s1, lds_d);
-    if (t == 0) a.ws_s1[(int64_t)m * a.ntiles + tile] = S1;
+  for (int j = 0; j < 16; ++j)
+    if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
+  const double S1 = block_sum_f64(s1, lds_d);
+  if (t == 0) {
+    a.ws_s1[(int64_t)m * a.ntiles + tile] = S1;
+    a.ws_count[(int64_t)m * a.ntiles + tile] = K;
   }
-  if (t == 0) a.ws_count[(int64_t)m * a.ntiles + tile] = K;
+}
+
+// pass 1 without a gradient (decoder, S of a coded message): a wave counts kCountTiles
+// consecutive tiles, lane l the indicator words 2l and 2l+1 of each tile (bits at or beyond d
+// are not components).
+constexpr int kCountTiles = 8;
+__global__ __launch_bounds__(kThreads) void gsel_count_ind_kernel(SelArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t tile0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kCountTiles;
+  const int m = blockIdx.y;
+  const uint32_t* ind = a.ind_in + (int64_t)m * a.ind_stride;
+  uint32_t c[kCountTiles];
+#pragma unroll
+  for (int u = 0; u < kCountTiles; ++u) {
+    c[u] = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int64_t iw = (tile0 + u) * (kTile / 32) + 2 * lane + h;
+      uint32_t v = iw < a.NW ? ind[iw] : 0u;
+      const int64_t left = a.d - 32 * iw;
+      if (left < 32) v = left > 0 ? (v & ((1u << left) - 1u)) : 0u;
+      c[u] += (uint32_t)__popc(v);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kCountTiles; ++u) {
+    const uint32_t K = wave_sum_u32(c[u]);
+    if (lane == 0 && tile0 + u < a.ntiles) a.ws_count[(int64_t)m * a.ntiles + tile0 + u] = K;
+  }
 }
 
 // pass 2: per (bucket, worker), in tile order: each tile's first position in the bucket's stream,
@@ -603,20 +675,25 @@ __global__ __launch_bounds__(kThreads) void gsel_scan_kernel(SelArgs a) {
   }
 }
 
-// zero the first ceil(K/16) words of every bucket's area (tile `blockIdx.x` covers 256 of them)
+// zero the first ceil(K/16) words of every bucket's area (a tile covers 256 of them, a work-group
+// kZeroTiles consecutive tiles)
+constexpr int kZeroTiles = 8;
 __global__ __launch_bounds__(kThreads) void gsel_zero_kernel(SelArgs a) {
-  const int64_t tile = blockIdx.x;
   const int m = blockIdx.y;
-  const int64_t k = tile / a.tiles_per_bucket;
-  const int64_t w = (tile - k * a.tiles_per_bucket) * kTileWords + threadIdx.x;   // word of the area
-  const int64_t K = a.counts[(int64_t)m * a.scale_stride + k];
-  if (w < (K + 15) / 16) a.sel_codes[(int64_t)m * a.code_stride + k * a.area_words + w] = 0u;
+#pragma unroll
+  for (int u = 0; u < kZeroTiles; ++u) {
+    const int64_t tile = (int64_t)blockIdx.x * kZeroTiles + u;
+    if (tile >= a.ntiles) break;
+    const int64_t k = tile / a.tiles_per_bucket;
+    const int64_t w = (tile - k * a.tiles_per_bucket) * kTileWords + threadIdx.x;   // word of the area
+    const int64_t K = a.counts[(int64_t)m * a.scale_stride + k];
+    if (w < (K + 15) / 16) a.sel_codes[(int64_t)m * a.code_stride + k * a.area_words + w] = 0u;
+  }
 }
 
-// Q(S(g, I)) for any bucket size.  MULTI: thresholds come from pass 2, the kept sums of the tile
-// go to the workspace for gsel_scale_kernel.
-template <bool MULTI>
-__global__ __launch_bounds__(kThreads) void gsel_quantize_kernel(SelArgs a) {
+// Q(S(g, I)) for buckets of 64 .. 2048 coordinates: thread t = code word t of the tile, a bucket =
+// a.seg consecutive threads.
+__global__ __launch_bounds__(kThreads) void gsel_quantize_local_kernel(SelArgs a) {
   __shared__ uint32_t stream[kTileWords + 2];
   __shared__ uint32_t lds_w[kWaves];
   __shared__ uint32_t lds_ex[kThreads + 1];
@@ -632,19 +709,14 @@ __global__ __launch_bounds__(kThreads) void gsel_quantize_kernel(SelArgs a) {
   stream[t] = 0u;
   if (t < 2) stream[kTileWords + t] = 0u;
   const uint32_t n = (uint32_t)__popc(mask);
-  const StreamPos p = stream_position<MULTI>(a, tile, m, n, lds_w, lds_ex);   // barriers: stream is zero
+  const StreamPos p = stream_position(a, n, lds_w, lds_ex);   // barriers: stream is zero
 
-  float Delta;
-  if (MULTI) {
-    Delta = a.ws_thr[(int64_t)m * a.nb + tile / a.tiles_per_bucket];
-  } else {
-    double s1 = 0.0;
+  double s1 = 0.0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
-    const double S1 = segment_sum(s1, a.seg, lds_d);
-    Delta = p.in_bucket ? threshold_from_sum(S1, a.thr_coef, (int64_t)p.in_bucket) : 0.0f;
-  }
+  for (int j = 0; j < 16; ++j)
+    if ((mask >> j) & 1u) s1 += (double)fabsf(v[j]);
+  const double S1 = segment_sum(s1, a.seg, lds_d);
+  const float Delta = p.in_bucket ? threshold_from_sum(S1, a.thr_coef, (int64_t)p.in_bucket) : 0.0f;
   double s2 = 0.0;
   uint32_t c2 = 0, bits = 0, k = 0;
 #pragma unroll
@@ -657,23 +729,97 @@ __global__ __launch_bounds__(kThreads) void gsel_quantize_kernel(SelArgs a) {
     }
   }
   stream_append(stream, p.pos, n, bits);
-  const int seg = MULTI ? kThreads : a.seg;
   __syncthreads();                                       // lds_d of the first sum has been read
-  const double S2 = segment_sum(s2, seg, lds_d);
-  const uint32_t C2 = segment_sum_u32(c2, seg, lds_u);
+  const double S2 = segment_sum(s2, a.seg, lds_d);
+  const uint32_t C2 = segment_sum_u32(c2, a.seg, lds_u);
   __syncthreads();                                       // the stream is complete
-  stream_flush<MULTI>(a, p, stream, a.sel_codes + (int64_t)m * a.code_stride);
-  if (MULTI) {
-    if (t == 0) {
-      a.ws_s2[(int64_t)m * a.ntiles + tile] = S2;
-      a.ws_c2[(int64_t)m * a.ntiles + tile] = C2;
-    }
-  } else if ((t & (a.seg - 1)) == 0) {
+  // the first ceil(K/16) words of each bucket's area, nothing else
+  const int s0 = t & ~(a.seg - 1);
+  uint32_t* row = a.sel_codes + (int64_t)m * a.code_stride + tile * kTileWords;
+  if ((uint32_t)(t - s0) < (p.in_bucket + 15) / 16) row[t] = stream[t];
+  if (t == s0) {
     const int64_t kb = (tile * kTile + 16 * (int64_t)t) / (16 * (int64_t)a.seg);
     if (kb < a.nb) {
       a.counts[(int64_t)m * a.scale_stride + kb] = p.in_bucket;
       a.scales[(int64_t)m * a.scale_stride + kb] = scale_from_sum(S2, C2);
       if (a.thresholds) a.thresholds[(int64_t)m * a.scale_stride + kb] = Delta;
+    }
+  }
+}
+
+// Q(S(g, I)) for buckets that span tiles, one wave per tile and no work-group barrier on the way
+// (lane l holds code words j*64 + l of the tile, j = 0..3, as in the decoder): the threshold comes
+// from pass 2, the tile's codes go to their place in the bucket's stream (words that a
+// neighbouring tile may also touch are OR-ed into memory zeroed before), the tile's kept sum and
+// count to the workspace for gsel_scale_kernel.
+__global__ __launch_bounds__(kThreads) void gsel_quantize_multi_kernel(SelArgs a) {
+  __shared__ uint32_t stream_all[kWaves][kTileWords + 2];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  uint32_t* stream = stream_all[wave];
+  const int64_t tile_raw = (int64_t)blockIdx.x * kWaves + wave;
+  const bool exists = tile_raw < a.ntiles;
+  const int64_t tile = exists ? tile_raw : 0;            // clamped: every wave runs the same code
+  const int m = blockIdx.y;
+  const uint32_t* ind = a.ind_in + (int64_t)m * a.ind_stride;
+  const float* g = a.g + (int64_t)m * a.g_stride;
+  uint32_t mask[4], incl[4];
+  float v[4][16];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int wl = j * 64 + lane;
+    const int64_t iw = tile * (kTile / 32) + wl / 2;
+    const uint32_t iv = iw < a.NW ? ind[iw] : 0u;
+    mask[j] = (iv >> (16 * (wl & 1))) & 0xFFFFu;
+    const int64_t left = a.d - (tile * kTile + (int64_t)wl * 16);
+    if (left < 16) mask[j] = left > 0 ? (mask[j] & ((1u << left) - 1u)) : 0u;
+    load16(g, a.d, tile * kTile + (int64_t)wl * 16, v[j]);
+    stream[wl] = 0u;
+  }
+  if (lane < 2) stream[kTileWords + lane] = 0u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) incl[j] = wave_inclusive_scan_u32((uint32_t)__popc(mask[j]));
+  const int64_t st = a.ws_start[(int64_t)m * a.ntiles + tile];
+  const int64_t k = tile / a.tiles_per_bucket;
+  const uint32_t first = (uint32_t)(st & 15);
+  const float Delta = a.ws_thr[(int64_t)m * a.nb + k];
+  __syncthreads();                                       // the zeroed streams are in LDS
+  double s2 = 0.0;
+  uint32_t c2 = 0, start = first;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t n = (uint32_t)__popc(mask[j]);
+    const uint32_t before = start + incl[j] - n;
+    start += (uint32_t)__builtin_amdgcn_readlane((int)incl[j], kWave - 1);
+    uint32_t bits = 0, filled = 0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c)
+      if ((mask[j] >> c) & 1u) {
+        const float av = fabsf(v[j][c]);
+        if (av > Delta) { s2 += (double)av; ++c2; }
+        bits |= ternary_field(v[j][c], Delta) << filled;
+        filled += 2;
+      }
+    if (n) {
+      const uint32_t w0 = before / 16, sh = 2 * (before % 16);
+      atomicOr(&stream[w0], bits << sh);
+      if (sh && 2 * n + sh > 32) atomicOr(&stream[w0 + 1], bits >> (32 - sh));
+    }
+  }
+  const double S2 = wave_sum_f64(s2);
+  const uint32_t C2 = wave_sum_u32(c2);
+  __syncthreads();                                       // the streams are complete
+  if (exists) {
+    const uint32_t end = start, nwords = (end + 15) / 16;  // one past the tile's last code
+    uint32_t* out = a.sel_codes + (int64_t)m * a.code_stride + k * a.area_words + (st >> 4);
+    if (end != first)
+      for (uint32_t w = lane; w < nwords; w += kWave) {    // at most 257 words
+        const bool shared = (w == 0 && first != 0) || (w == nwords - 1 && (end % 16) != 0);
+        if (shared) atomicOr(&out[w], stream[w]);
+        else out[w] = stream[w];
+      }
+    if (lane == 0) {
+      a.ws_s2[(int64_t)m * a.ntiles + tile] = S2;
+      a.ws_c2[(int64_t)m * a.ntiles + tile] = C2;
     }
   }
 }
@@ -693,76 +839,7 @@ __global__ __launch_bounds__(kThreads) void gsel_scale_kernel(SelArgs a) {
   if (threadIdx.x == 0) a.scales[(int64_t)m * a.scale_stride + k] = scale_from_sum(s, (uint64_t)c);
 }
 
-// S^{-1} for any bucket size: thread t writes dense code word t of the tile.
-template <bool MULTI>
-__global__ __launch_bounds__(kThreads) void gsel_decode_kernel(SelArgs a) {
-  __shared__ uint8_t lut[16 * 256];
-  __shared__ uint32_t lds_w[kWaves];
-  __shared__ uint32_t lds_ex[kThreads + 1];
-  const int t = threadIdx.x;
-  reinterpret_cast<uint4*>(lut)[t] = reinterpret_cast<const uint4*>(kDepositLut.v)[t];
-  const int64_t tile = blockIdx.x;
-  const int m = blockIdx.y;
-  const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
-  const uint32_t n = (uint32_t)__popc(mask);
-  const StreamPos p = stream_position<MULTI>(a, tile, m, n, lds_w, lds_ex);   // barriers: lut is in LDS
-  const uint32_t* row = a.sel_in + (int64_t)m * a.code_stride + p.base;
-  // the thread's n codes are codes pos .. pos+n-1 counted from row[0]; they exist (n > 0), so
-  // the words read lie inside what the producer wrote
-  const uint32_t w0 = p.pos / 16, sh = 2 * (p.pos % 16);
-  const uint32_t lo = n ? row[w0] : 0u;
-  const uint32_t hi = (p.pos % 16) + n > 16u ? row[w0 + 1] : 0u;
-  uint32_t win = lo >> sh;
-  if (sh) win |= hi << (32 - sh);
-  uint32_t out = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const uint32_t nib = (mask >> (4 * q)) & 15u;
-    out |= (uint32_t)lut[nib * 256 + (win & 0xFFu)] << (8 * q);
-    win >>= 2 * __popc(nib);
-  }
-  const int64_t w = tile * kTileWords + t;
-  if (w < a.W) (a.dense + (int64_t)m * a.dense_stride)[w] = out;
-}
-
-// S applied to a coded message for any bucket size.
-template <bool MULTI>
-__global__ __launch_bounds__(kThreads) void gsel_select_codes_kernel(SelArgs a) {
-  __shared__ uint8_t lut[16 * 256];
-  __shared__ uint32_t stream[kTileWords + 2];
-  __shared__ uint32_t lds_w[kWaves];
-  __shared__ uint32_t lds_ex[kThreads + 1];
-  const int t = threadIdx.x;
-  reinterpret_cast<uint4*>(lut)[t] = reinterpret_cast<const uint4*>(kExtractLut.v)[t];
-  stream[t] = 0u;
-  if (t < 2) stream[kTileWords + t] = 0u;
-  const int64_t tile = blockIdx.x;
-  const int m = blockIdx.y;
-  const uint32_t mask = live_mask16(a, a.ind_in + (int64_t)m * a.ind_stride, tile, t);
-  const uint32_t n = (uint32_t)__popc(mask);
-  const int64_t w = tile * kTileWords + t;
-  const uint32_t raw = w < a.W ? (a.sel_in + (int64_t)m * a.code_stride)[w] : 0u;
-  const uint32_t low = raw & 0x55555555u;
-  const uint32_t word = low | (raw & (low << 1));        // reserved pattern 10 reads as 0
-  const StreamPos p = stream_position<MULTI>(a, tile, m, n, lds_w, lds_ex);   // barriers: lut, stream ready
-  uint32_t bits = 0, filled = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const uint32_t nib = (mask >> (4 * q)) & 15u;
-    bits |= (uint32_t)lut[nib * 256 + ((word >> (8 * q)) & 0xFFu)] << filled;
-    filled += 2 * __popc(nib);
-  }
-  stream_append(stream, p.pos, n, bits);
-  __syncthreads();
-  stream_flush<MULTI>(a, p, stream, a.sel_codes + (int64_t)m * a.code_stride);
-  if (!MULTI && (t & (a.seg - 1)) == 0) {
-    const int64_t kb = (tile * kTile + 16 * (int64_t)t) / (16 * (int64_t)a.seg);
-    if (kb < a.nb) a.counts[(int64_t)m * a.scale_stride + kb] = p.in_bucket;
-  }
-}
-
 // Which kernels serve a layout's sparse messages.
-enum SelKind { kSelTile, kSelLocal, kSelMulti };
 static SelKind sel_kind(const qa_layout* L) {
   if (L->bucket == kTile || (L->bucket == 0 && L->d <= kTile)) return kSelTile;   // the tuned kernels
   if (L->bucket != 0 && L->bucket < kTile) return kSelLocal;                        // buckets inside a tile
@@ -770,6 +847,12 @@ static SelKind sel_kind(const qa_layout* L) {
 }
 
 static inline size_t sel_align(size_t v) { return (v + 255) & ~size_t(255); }
+static inline dim3 zero_grid(const qa_layout* L) {
+  return dim3((unsigned)((tiles_of(L->d) + kZeroTiles - 1) / kZeroTiles), (unsigned)L->M);
+}
+static inline dim3 count_grid(const qa_layout* L) {
+  return dim3((unsigned)((tiles_of(L->d) + kWaves * kCountTiles - 1) / (kWaves * kCountTiles)), (unsigned)L->M);
+}
 
 // Workspace of the multi-tile path: per (worker, tile) a count, two binary64 sums, a kept count and
 // the tile's first position in its bucket's stream; per (worker, bucket) a threshold.
@@ -897,14 +980,16 @@ extern "C" int qa_quantize_pack_selected(const qa_layout* layout, const float* g
   rc = general_args(layout, a, ws, ws_bytes);
   if (rc != QA_OK) return rc;
   if (kind == kSelLocal) {
-    hipLaunchKernelGGL(gsel_quantize_kernel<false>, tiles, block, 0, stream, a);
+    hipLaunchKernelGGL(gsel_quantize_local_kernel, tiles, block, 0, stream, a);
     return launch_status();
   }
   const dim3 buckets((unsigned)a.nb, (unsigned)layout->M);
-  hipLaunchKernelGGL(gsel_count_kernel<true>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_count_kernel, tiles, block, 0, stream, a);
   hipLaunchKernelGGL(gsel_scan_kernel<true>, buckets, block, 0, stream, a);
-  hipLaunchKernelGGL(gsel_zero_kernel, tiles, block, 0, stream, a);
-  hipLaunchKernelGGL(gsel_quantize_kernel<true>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_zero_kernel, zero_grid(layout), block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_quantize_multi_kernel,
+                     dim3((unsigned)((tiles_of(layout->d) + kWaves - 1) / kWaves), (unsigned)layout->M),
+                     block, 0, stream, a);
   hipLaunchKernelGGL(gsel_scale_kernel, buckets, block, 0, stream, a);
   return launch_status();
 }
@@ -921,25 +1006,24 @@ int decode_selected_launch(const qa_layout* layout, const uint32_t* ind, int64_t
   a.dense_stride = out_stride;
   const dim3 block(kThreads), tiles((unsigned)tiles_of(layout->d), (unsigned)layout->M);
   const SelKind kind = sel_kind(layout);
+  const dim3 wave_tiles((unsigned)((tiles_of(layout->d) + kWaves * kDecodeTiles - 1) / (kWaves * kDecodeTiles)),
+                        (unsigned)layout->M);
   if (kind == kSelTile) {
-    hipLaunchKernelGGL(decode_selected_kernel,
-                       dim3((unsigned)((tiles_of(layout->d) + kWaves * kDecodeTiles - 1) / (kWaves * kDecodeTiles)),
-                            (unsigned)layout->M),
-                       block, 0, stream, a);
+    hipLaunchKernelGGL(decode_selected_kernel<kSelTile>, wave_tiles, block, 0, stream, a);
     return launch_status();
   }
   int rc = general_args(layout, a, ws, ws_bytes);
   if (rc != QA_OK) return rc;
   if (kind == kSelLocal) {
-    hipLaunchKernelGGL(gsel_decode_kernel<false>, tiles, block, 0, stream, a);
+    hipLaunchKernelGGL(decode_selected_kernel<kSelLocal>, wave_tiles, block, 0, stream, a);
     return launch_status();
   }
   // the scan also leaves each bucket's count; nobody asked for it here: the kept-count slots of
   // the workspace (unused by a decode) take it, M*nb <= M*ntiles words
   a.counts = a.ws_c2; a.scale_stride = a.nb;
-  hipLaunchKernelGGL(gsel_count_kernel<false>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_count_ind_kernel, count_grid(layout), block, 0, stream, a);
   hipLaunchKernelGGL(gsel_scan_kernel<false>, dim3((unsigned)a.nb, (unsigned)layout->M), block, 0, stream, a);
-  hipLaunchKernelGGL(gsel_decode_kernel<true>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(decode_selected_kernel<kSelMulti>, wave_tiles, block, 0, stream, a);
   return launch_status();
 }
 }  // namespace qa
@@ -975,21 +1059,20 @@ extern "C" int qa_select_codes(const qa_layout* layout, const uint32_t* codes, c
   a.ind_in = ind; a.ind_stride = ind_stride; a.sel_in = codes; a.sel_codes = sel_codes; a.counts = counts;
   const dim3 block(kThreads), tiles((unsigned)tiles_of(layout->d), (unsigned)layout->M);
   const SelKind kind = sel_kind(layout);
+  const dim3 wave_tiles((unsigned)((tiles_of(layout->d) + kWaves - 1) / kWaves), (unsigned)layout->M);
   if (kind == kSelTile) {
-    hipLaunchKernelGGL(select_codes_kernel,
-                       dim3((unsigned)((tiles_of(layout->d) + kWaves - 1) / kWaves), (unsigned)layout->M),
-                       block, 0, stream, a);
+    hipLaunchKernelGGL(select_codes_kernel<kSelTile>, wave_tiles, block, 0, stream, a);
     return launch_status();
   }
   rc = general_args(layout, a, ws, ws_bytes);
   if (rc != QA_OK) return rc;
   if (kind == kSelLocal) {
-    hipLaunchKernelGGL(gsel_select_codes_kernel<false>, tiles, block, 0, stream, a);
+    hipLaunchKernelGGL(select_codes_kernel<kSelLocal>, wave_tiles, block, 0, stream, a);
     return launch_status();
   }
-  hipLaunchKernelGGL(gsel_count_kernel<false>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_count_ind_kernel, count_grid(layout), block, 0, stream, a);
   hipLaunchKernelGGL(gsel_scan_kernel<false>, dim3((unsigned)a.nb, (unsigned)layout->M), block, 0, stream, a);
-  hipLaunchKernelGGL(gsel_zero_kernel, tiles, block, 0, stream, a);
-  hipLaunchKernelGGL(gsel_select_codes_kernel<true>, tiles, block, 0, stream, a);
+  hipLaunchKernelGGL(gsel_zero_kernel, zero_grid(layout), block, 0, stream, a);
+  hipLaunchKernelGGL(select_codes_kernel<kSelMulti>, wave_tiles, block, 0, stream, a);
   return launch_status();
 }
