@@ -93,6 +93,40 @@ def test_exact_thresholds_realise_the_optimum_through_the_strict_quantizer(seed)
     assert oracle.exact_thresholds(np.array([2.0, -2.0, 2.0], np.float32))[0] == 0.0
 
 
+@pytest.mark.parametrize("j,bucket", [(10000, 0), (3000, 16384), (2730, 8192)])
+def test_exact_threshold_of_a_long_ramp_has_a_closed_form(j, bucket):
+    """Section 3.4 over a vector longer than any tile: for the magnitudes 1, 2, ..., n the sum of
+    the k largest is k n - k (k - 1) / 2, so the objective is k (n - (k - 1) / 2)^2, a cubic whose
+    only maximum over k >= 1 lies at k = (2 n + 1) / 3.  With n = 3 j + 1 that is the integer
+    2 j + 1: the kept set is {j + 1, ..., n}, the largest magnitude not kept is j, the scale is
+    the mean (n + j + 1) / 2 of the kept ones.  Every quantity is an integer below 2^53.  With
+    buckets, every full bucket is a shuffled ramp of its own length."""
+    rng = np.random.default_rng(j)
+    if bucket == 0:
+        n = 3 * j + 1
+        v = rng.permutation(np.arange(1, n + 1)).astype(np.float32)
+        v *= rng.choice([-1.0, 1.0], n).astype(np.float32)
+        kept_min, s, obj, k = oracle.exact_threshold(v)
+        assert (k, kept_min) == (2 * j + 1, float(j + 1))
+        assert s == (n + j + 1) / 2
+        assert obj == k * s * s
+        assert oracle.exact_thresholds(v)[0] == float(j)
+    else:
+        # full buckets hold a ramp 1..bucket (bucket = 3 jb + 1 does not hold for powers of two, so
+        # the optimum there is found by evaluating the cubic at the two integers around its peak);
+        # the last, short bucket holds a ramp of length 3 j + 1
+        nfull = 3
+        pieces = [rng.permutation(np.arange(1, bucket + 1)) for _ in range(nfull)]
+        pieces.append(rng.permutation(np.arange(1, 3 * j + 2)))
+        v = np.concatenate(pieces).astype(np.float32)
+        assert 3 * j + 1 < bucket
+        th = oracle.exact_thresholds(v, bucket=bucket)
+        f = lambda k, n: k * (n - (k - 1) / 2) ** 2
+        kf = (2 * bucket + 1) // 3
+        kbest = max((kf, kf + 1), key=lambda k: f(k, bucket))
+        assert np.array_equal(th, np.array([bucket - kbest] * nfull + [j], np.float32))
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_approx_threshold_never_beats_exact(seed):
     rng = np.random.default_rng(100 + seed)
