@@ -77,6 +77,7 @@ extern "C" {
 #define QA_OP_GRAD_DENSE 4
 #define QA_OP_SELECT 5        /* qa_quantize_pack_selected, qa_decode_selected, qa_select_codes   */
 #define QA_OP_STEP_SELECTED 6 /* qa_step_*_selected, qa_aggregate_quantize_selected               */
+#define QA_OP_QUANTIZE_EXACT 7 /* qa_quantize_pack with QA_THRESH_EXACT (any bucket size)          */
 
 /* data formats of qa_local_grad */
 #define QA_DENSE 0
@@ -152,8 +153,16 @@ int qa_local_grad_batched(int format, const float* A_or_vals, const int64_t* ind
  * With QA_THRESH_GIVEN thresholds must be non-NULL and is read instead of computed.
  * With QA_THRESH_EXACT each bucket's threshold is the largest magnitude NOT kept by the k that
  * maximises (sum of the k largest |v|)^2 / k (equal magnitudes are never split), so that the
- * strict comparisons keep exactly the optimal set; scale and codes follow as usual.
- * g_stride >= d and a multiple of 4.  ws: qa_workspace_bytes(layout, QA_OP_QUANTIZE). */
+ * strict comparisons keep exactly the optimal set; scale and codes follow as usual.  Buckets of
+ * up to 4096 components are ranked inside one work-group; longer buckets, and one threshold for
+ * a vector of more than 4096 components (Section 3.4's optimum over the whole gradient), are
+ * ranked by a device-wide sort, worker after worker, in 16.5 bytes of workspace per component
+ * (d < 2^32, else QA_ERR_TOO_LARGE).  Candidates whose objectives agree to binary64 rounding
+ * (likely only beyond some 1e7 components per bucket) may be resolved differently from a
+ * strictly sequential summation.
+ * g_stride >= d and a multiple of 4.  ws: qa_workspace_bytes(layout, QA_OP_QUANTIZE), or
+ * qa_workspace_bytes(layout, QA_OP_QUANTIZE_EXACT) with QA_THRESH_EXACT (the two agree for
+ * buckets of up to 4096 components). */
 int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, uint32_t* codes,
                      float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
                      void* stream);
@@ -167,7 +176,9 @@ int qa_quantize_pack(const qa_layout* layout, const float* g, int64_t g_stride, 
  *   - Limit: qa_workspace_bytes(layout, QA_OP_QUANTIZE) <= 4 MiB (QA_STATIC_SCRATCH_BYTES), about
  *     12 bytes per worker and 4096 coordinates: e.g. M * ceil(d/4096) <= 349 000.  Larger
  *     problems return QA_ERR_TOO_LARGE and launch nothing.  Layouts that need no workspace
- *     (bucket <= 4096, or a vector of at most 4096 coordinates) have no limit.
+ *     (bucket <= 4096, or a vector of at most 4096 coordinates) have no limit.  QA_THRESH_EXACT
+ *     for buckets longer than 4096 components needs a sort's worth of scratch and is refused
+ *     with QA_ERR_TOO_LARGE as well.
  *   - Each GPU holds one such array for the life of the process.  The first call on a device
  *     looks its address up (the device of the calling thread must be the one `stream` belongs
  *     to); make that first call outside stream capture.

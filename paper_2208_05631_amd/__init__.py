@@ -5,7 +5,7 @@ the path runs in the HIP kernels of libqadagrad.so; torch is used for device mem
 streams only.  Importing `binding` fails loudly if the shared library has not been built.
 """
 from .binding import (  # noqa: F401
-    QA_CSR, QA_DENSE, QA_METHOD_QCMD, QA_METHOD_QRDA, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE, QA_OP_QUANTIZE, QA_OP_STEP, QA_OP_SELECT, QA_OP_STEP_SELECTED,
+    QA_CSR, QA_DENSE, QA_METHOD_QCMD, QA_METHOD_QRDA, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE, QA_OP_QUANTIZE, QA_OP_STEP, QA_OP_SELECT, QA_OP_STEP_SELECTED, QA_OP_QUANTIZE_EXACT,
     QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL, QA_REQUANT_NONE, QA_THRESH_GIVEN, QA_THRESH_EXACT, Layout, QaError,
     lib_path, qa_aggregate_unpack, qa_local_grad, qa_local_grad_batched, qa_quantize_pack, qa_step_qcmd, qa_step_qrda,
     qa_strerror, qa_version, qa_workspace_bytes, qa_indicator, qa_indicator_or,

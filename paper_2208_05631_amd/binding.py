@@ -17,7 +17,7 @@ QA_REQUANT_NONE, QA_REQUANT_BUCKET, QA_REQUANT_GLOBAL = 0, 1, 2
 QA_THRESH_GIVEN = 1
 QA_THRESH_EXACT = 2
 QA_OP_QUANTIZE, QA_OP_STEP, QA_OP_GRAD_CSR, QA_OP_GRAD_DENSE = 1, 2, 3, 4
-QA_OP_SELECT, QA_OP_STEP_SELECTED = 5, 6
+QA_OP_SELECT, QA_OP_STEP_SELECTED, QA_OP_QUANTIZE_EXACT = 5, 6, 7
 QA_DENSE, QA_CSR = 0, 1
 QA_METHOD_QCMD, QA_METHOD_QRDA = 0, 1
 

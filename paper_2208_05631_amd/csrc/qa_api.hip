@@ -3,6 +3,7 @@
 
 namespace qa {
 size_t quantize_workspace_bytes(const qa_layout* L);
+size_t exact_sort_workspace_bytes(const qa_layout* L);
 size_t step_workspace_bytes(const qa_layout* L);
 size_t select_workspace_bytes(const qa_layout* L);
 size_t step_selected_workspace_bytes(const qa_layout* L);
@@ -33,6 +34,8 @@ extern "C" size_t qa_workspace_bytes(const qa_layout* layout, int op) {
   }
   if (check_layout(layout) != QA_OK) return 0;
   if (op == QA_OP_QUANTIZE) return quantize_workspace_bytes(layout);
+  if (op == QA_OP_QUANTIZE_EXACT)
+    return quantize_workspace_bytes(layout) + exact_sort_workspace_bytes(layout);
   if (op == QA_OP_STEP) return step_workspace_bytes(layout);
   if (op == QA_OP_SELECT) return select_workspace_bytes(layout);
   if (op == QA_OP_STEP_SELECTED) return step_selected_workspace_bytes(layout);

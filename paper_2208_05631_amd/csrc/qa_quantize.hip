@@ -879,6 +879,10 @@ __global__ __launch_bounds__(kThreads) void zero_scales_kernel(float* scales, in
 
 static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
+size_t exact_sort_workspace_bytes(const qa_layout* L);
+int exact_thresholds_sorted(const qa_layout* L, const float* g, int64_t g_stride, float* thresholds,
+                            void* ws, size_t ws_bytes, hipStream_t stream);
+
 size_t quantize_workspace_bytes(const qa_layout* L) {
   if (L->bucket != 0 && L->bucket <= kTile) return 0;
   if (L->bucket == 0 && tiles_of(L->d) == 1) return 0;   // one tile: one pass
@@ -901,10 +905,19 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   const dim3 block(kThreads);
   if (a.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
   const dim3 grid_tiles((unsigned)a.ntiles, (unsigned)L->M);
-  if (flags & QA_THRESH_EXACT) {
+  const bool one_pass = (L->bucket != 0 && L->bucket <= kTile) || (L->bucket == 0 && a.ntiles == 1);
+  if ((flags & QA_THRESH_EXACT) && !one_pass) {
+    // buckets that span tiles: device-wide ranking, in the part of the workspace that follows
+    // the multi-pass quantizer's own
+    const size_t own = quantize_workspace_bytes(L), more = exact_sort_workspace_bytes(L);
+    if (!ws || ws_bytes < own + more) return QA_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+    const int rc = exact_thresholds_sorted(L, g, g_stride, thresholds, static_cast<char*>(ws) + own,
+                                           ws_bytes - own, stream);
+    if (rc != QA_OK) return rc;
+    a.thresh_given = 1;                                  // the passes below read what it wrote
+  } else if (flags & QA_THRESH_EXACT) {
     // one ranking network per tile: buckets that fit a tile
-    if (!((L->bucket != 0 && L->bucket <= kTile) || (L->bucket == 0 && a.ntiles == 1)))
-      return QA_ERR_UNSUPPORTED;
     switch (L->bucket ? ilog2(L->bucket) : 12) {
       case 6: hipLaunchKernelGGL(exact_threshold_kernel<6>, grid_tiles, block, 0, stream, a); break;
       case 7: hipLaunchKernelGGL(exact_threshold_kernel<7>, grid_tiles, block, 0, stream, a); break;
@@ -1013,6 +1026,8 @@ extern "C" int qa_quantize_pack_static(const qa_layout* layout, const float* g, 
     return QA_ERR_ALIGNMENT;
   const size_t need = quantize_workspace_bytes(layout);
   if (need > kScratchBytes) return QA_ERR_TOO_LARGE;
+  // the device-wide ranking needs a sort's worth of scratch: not from this array
+  if ((flags & QA_THRESH_EXACT) && exact_sort_workspace_bytes(layout) != 0) return QA_ERR_TOO_LARGE;
   void* ws = nullptr;
   if (need) {
     rc = scratch_address(&ws);

@@ -42,7 +42,7 @@ def gpu_quantize_pack(g, bucket, thr_coef=0.75, thresholds=None, code_stride=Non
         flags = qa.QA_THRESH_GIVEN
     if exact:
         flags = qa.QA_THRESH_EXACT
-    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE))
+    ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE_EXACT if exact else qa.QA_OP_QUANTIZE))
     qa.qa_quantize_pack(L, gd, gs, codes, scales, th, flags, ws)
     torch.cuda.synchronize()
     return host(codes).view(np.uint32), host(scales), host(th), L

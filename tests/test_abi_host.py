@@ -41,6 +41,11 @@ def test_workspace_sizes():
     Lg = qa.Layout.make(10**6, 8, 0)
     nt = (10**6 + 4095) // 4096
     assert qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE) >= 8 * nt * 12
+    # the exact threshold: nothing more for buckets inside a tile; a sort's worth of scratch
+    # (two buffers of 64-bit keys, independent of the worker count) for buckets that span tiles
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE_EXACT) == 0
+    more = qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE_EXACT) - qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE)
+    assert 16 * 10**6 <= more <= 18 * 10**6
     assert qa.qa_workspace_bytes(L, qa.QA_OP_STEP) >= 4 * 10**6       # averaged vector for GLOBAL
     assert qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR) >= 8 * 8 * 10**6      # M = 8 accumulators
     assert 0 < qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_DENSE) < 8 * 10**6

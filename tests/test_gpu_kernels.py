@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_05631_amd as qa
-    from gpu_util import DEV, GpuState, dev, gpu_quantize_pack, host, quantizer_parity, workspace
+    from gpu_util import DEV, GpuState, dev, gpu_quantize_pack, host, quantizer_parity, ulp_distance, workspace
 
 RTOL = 1e-5
 
@@ -556,18 +556,83 @@ def test_exact_threshold_never_splits_equal_magnitudes_and_handles_zeros(bucket)
     assert th[2, first_empty] == 0 and s[2, first_empty] == 0 and not c[2, 256:].any()
 
 
-def test_exact_threshold_refuses_other_buckets_and_missing_output():
+# buckets longer than one tile, and one threshold for a long vector: device-wide ranking
+@pytest.mark.parametrize("d,M,bucket", [(70001, 2, 0), (70001, 2, 8192), (4096 * 5 + 1, 3, 16384),
+                                        (4097, 1, 0), (300001, 1, 0), (8192 * 3, 2, 8192),
+                                        ((1 << 20) + 17, 1, 65536)])
+@pytest.mark.parametrize("kind", ["gauss", "student", "laplace_sparse"])
+def test_exact_threshold_over_several_tiles_matches_oracle(d, M, bucket, kind):
+    """Section 3.4's optimum over a bucket (or a whole gradient) of many tiles.  At these sizes the
+    objectives of neighbouring k differ by far more than the rounding of the binary64 sums, so
+    the k, and with it threshold, codes and scale, must be the oracle's."""
+    g = make_grad(kind, M, d, seed=d % 977 + M)
+    th_ref = np.stack([oracle.exact_thresholds(g[m], bucket) for m in range(M)])
+    c_ref, s_ref, _ = oracle.quantize_pack(g, bucket, thresholds=th_ref)
+    c, s, th, L = gpu_quantize_pack(g, bucket, exact=True)
+    nb = L.n_buckets
+    assert np.array_equal(th[:, :nb].view(np.uint32), th_ref.view(np.uint32))
+    assert np.array_equal(c[:, :L.words], c_ref)
+    assert int(ulp_distance(s[:, :nb], s_ref).max()) <= 1   # binary64 sums over many tiles, rounded once
+
+
+@pytest.mark.parametrize("bucket", [0, 8192])
+def test_exact_threshold_over_several_tiles_with_ties_zeros_and_a_ramp(bucket):
+    rng = np.random.default_rng(11)
+    d = 8192 * 4 + 300
+    g = np.zeros((4, d), np.float32)
+    g[0] = rng.integers(-3, 4, d)                       # many ties, many zeros, sums exact
+    g[1, ::7] = 2.5                                      # all kept magnitudes equal
+    g[2, :5000] = rng.standard_normal(5000)              # all-zero buckets after the first
+    g[3] = rng.permutation(np.arange(1, d + 1))          # a ramp: the closed form of the pin
+    th_ref = np.stack([oracle.exact_thresholds(g[m], bucket) for m in range(4)])
+    c_ref, s_ref, _ = oracle.quantize_pack(g, bucket, thresholds=th_ref)
+    c, s, th, L = gpu_quantize_pack(g, bucket, exact=True)
+    assert np.array_equal(th.view(np.uint32), th_ref.view(np.uint32))
+    assert np.array_equal(c, c_ref)
+    assert np.array_equal(s.view(np.uint32), s_ref.view(np.uint32))
+    if bucket:
+        assert th[2, 1] == 0 and s[2, 1] == 0 and not c[2, 512:].any()
+
+
+def test_exact_threshold_of_a_long_vector_is_optimal_to_binary64_resolution():
+    """Beyond some 1e7 components the objectives of neighbouring k near the optimum agree to
+    binary64 rounding and the association of the sums may decide between them; what must hold
+    at any size: the GPU's kept set is {|v| > its threshold}, no candidate the oracle finds is
+    better than it by more than that rounding, and codes and scale follow from the threshold."""
+    d, M = (1 << 24) + 12345, 1
+    g = np.empty((M, d), np.float32)
+    g[0] = host(synth.grad_laplace_sparse(d, 0, 1, device=DEV, seed=77, keep=0.5))
+    c, s, th, L = gpu_quantize_pack(g, 0, exact=True)
+    a = np.abs(g[0].astype(np.float64))
+    kept = a > float(th[0, 0])
+    k = int(kept.sum())
+    assert k > 0 and (th[0, 0] == 0 or (a == float(th[0, 0])).any())      # an actual magnitude
+    obj_gpu = a[kept].sum() ** 2 / k
+    _, _, obj_ref, k_ref = oracle.exact_threshold(g[0])
+    assert obj_gpu >= obj_ref * (1 - 1e-12)
+    print(f"\n[exact, d=2^24] kept {k} (oracle {k_ref}), objective ratio - 1 = {obj_gpu / obj_ref - 1:.2e}")
+    c_ref, s_ref, _ = oracle.quantize_pack(g, 0, thresholds=th[:, :1])
+    assert np.array_equal(c[:, :L.words], c_ref)
+    assert int(ulp_distance(s[:, :1], s_ref[:, :1]).max()) <= 1
+
+
+def test_exact_threshold_checks_workspace_and_missing_output():
     g = dev(np.ones((1, 8192), np.float32))
     codes = torch.zeros((1, 512), dtype=torch.int32, device=DEV)
     scales = torch.zeros((1, 128), dtype=torch.float32, device=DEV)
     th = torch.zeros((1, 128), dtype=torch.float32, device=DEV)
-    for bucket in (8192, 0):                            # buckets beyond one tile
+    for bucket in (8192, 0):                            # buckets beyond one tile need the larger workspace
         L = qa.Layout.make(8192, 1, bucket)
+        assert qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE_EXACT) > qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE)
         ws = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE))
         with pytest.raises(qa.QaError) as e:
             qa.qa_quantize_pack(L, g, 8192, codes, scales, th, qa.QA_THRESH_EXACT, ws)
-        assert e.value.code == -5
+        assert e.value.code == -3
+        with pytest.raises(qa.QaError) as e:            # and are refused without it
+            qa.qa_quantize_pack_static(L, g, 8192, codes, scales, th, qa.QA_THRESH_EXACT)
+        assert e.value.code == -6
     L = qa.Layout.make(8192, 1, 4096)
+    assert qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE_EXACT) == qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE)
     with pytest.raises(qa.QaError) as e:
         qa.qa_quantize_pack(L, g, 8192, codes, scales, None, qa.QA_THRESH_EXACT, None)
     assert e.value.code == -1
