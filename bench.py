@@ -307,6 +307,28 @@ def segments_bench(args, wl, qa, synth, torch, np, dev):
     print(json.dumps(out))
 
 
+DEVICE_STATE = None
+
+
+def device_state():
+    """Clocks and power cap of GPU 0 as rocm-smi reports them (a child process, read-only), or
+    None if the tool is missing, fails or prints something else than JSON."""
+    import json
+    import shutil
+    import subprocess
+    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([tool, "-d", "0", "--showclocks", "--showmaxpower", "--showperflevel", "--json"],
+                             capture_output=True, text=True, timeout=30)
+        txt = out.stdout[out.stdout.index("{"):out.stdout.rindex("}") + 1]
+        card = next(iter(json.loads(txt).values()))
+        keep = {k: v for k, v in card.items()
+                if any(w in k.lower() for w in ("sclk", "mclk", "fclk", "power", "performance"))}
+        return dict(keep, read="before the run, GPU idle") if keep else None
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -325,6 +347,9 @@ def main():
         print("bench.py: this build runs on exactly one GPU (workers and server are slices of "
               "one GPU's memory); --gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
+
+    global DEVICE_STATE
+    DEVICE_STATE = device_state()          # before this process touches the GPU
 
     import numpy as np
     import torch
@@ -545,6 +570,7 @@ def main():
                                    v["bytes_per_coord"] * v["launches"] for v in kernels.values()) / args.steps},
         "nnz_x_after": nnz_x,
         "device": torch.cuda.get_device_name(0),
+        "device_state": DEVICE_STATE,
     }
 
     # ---- CPU baseline: the oracle as it stands, one host thread pinned to one core, on a
