@@ -21,4 +21,8 @@ def test_c_program_matches_checker():
          env.get("LD_LIBRARY_PATH", "")])
     r = subprocess.run([EXE], env=env, capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, r.stdout + r.stderr
-    assert r.stdout.count("identical") == 4
+    out = r.stdout
+    assert sum(line.startswith("step ") and "identical" in line for line in out.splitlines()) == 4
+    assert "qa_aggregate_unpack: identical" in out
+    assert "qa_quantize_pack_static: identical" in out
+    assert "qa_local_grad: within 1e-6" in out
