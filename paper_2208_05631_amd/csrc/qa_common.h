@@ -90,6 +90,17 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
          (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
 }
 
+// The same pattern for any associative, commutative operation on 32-bit integers.
+template <typename F>
+__device__ __forceinline__ int wave_reduce_i32(int v, F f) {
+  v = f(v, dpp_i32<kDppQuadXor1>(v));
+  v = f(v, dpp_i32<kDppQuadXor2>(v));
+  v = f(v, dpp_i32<kDppRowHalfMirror>(v));
+  v = f(v, dpp_i32<kDppRowMirror>(v));
+  return f(f(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+           f(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+
 // Sum over the whole 256-thread work-group, returned to every thread.  One barrier; `lds`
 // (kWaves doubles) must not be reused by another call before a later barrier.
 __device__ __forceinline__ double block_sum_f64(double v, double* lds) {

@@ -349,6 +349,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   __shared__ uint32_t stage[kStaged ? kChunk * kTileWords : 1];
   __shared__ double s_scale[kChunk];
   __shared__ double lds_d[kWaves];
+  __shared__ double lds_d2[kWaves];
   __shared__ uint32_t lds_u[kWaves];
   __shared__ int lds_e[3 * kWaves];
   __shared__ uint8_t dep[SPARSE ? 16 * 256 : 16];
@@ -412,11 +413,17 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     emax = f > emax ? f : emax;
     emin = f < emin ? f : emin;
   }
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int o1 = __shfl_xor(emax, off, kWave), o2 = __shfl_xor(emin, off, kWave);
-    bad |= __shfl_xor(bad, off, kWave);
-    emax = o1 > emax ? o1 : emax;
-    emin = o2 < emin ? o2 : emin;
+  if (!SPARSE) {
+    emax = wave_reduce_i32(emax, [](int p, int q) { return p > q ? p : q; });
+    emin = wave_reduce_i32(emin, [](int p, int q) { return p < q ? p : q; });
+    bad = wave_reduce_i32(bad, [](int p, int q) { return p | q; });
+  } else {                                                // (the sparse variants: fewer registers this way)
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int o1 = __shfl_xor(emax, off, kWave), o2 = __shfl_xor(emin, off, kWave);
+      bad |= __shfl_xor(bad, off, kWave);
+      emax = o1 > emax ? o1 : emax;
+      emin = o2 < emin ? o2 : emin;
+    }
   }
   if ((t % kWave) == 0) {
     lds_e[t / kWave] = emax; lds_e[kWaves + t / kWave] = emin; lds_e[2 * kWaves + t / kWave] = bad;
@@ -685,7 +692,8 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     double s1 = 0.0;
 #pragma unroll
     for (int j = 0; j < 16; ++j) s1 += (double)fabsf(q[j]);   // dead lanes hold zeros
-    s1 = segment_sum(s1, seg, lds_d);
+    // a bucket that is the whole tile: sums over the work-group without lane shuffles
+    s1 = own_scales ? segment_sum(s1, seg, lds_d) : block_sum_f64(s1, lds_d);
     const float Delta = n > 0 ? threshold_from_sum(s1, a.thr_coef, n) : 0.0f;
     double s2 = 0.0;
     uint32_t cnt = 0;
@@ -694,8 +702,17 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
       const float av = fabsf(q[j]);
       if (av > Delta) { s2 += (double)av; ++cnt; }
     }
-    s2 = segment_sum(s2, seg, lds_d);
-    cnt = segment_sum_u32(cnt, seg, lds_u);
+    if (own_scales) {
+      s2 = segment_sum(s2, seg, lds_d);
+      cnt = segment_sum_u32(cnt, seg, lds_u);
+    } else {
+      s2 = wave_sum_f64(s2);
+      cnt = wave_sum_u32(cnt);
+      if ((t % kWave) == 0) { lds_d2[t / kWave] = s2; lds_u[t / kWave] = cnt; }
+      __syncthreads();                                    // (lds_d of the first sum is not touched)
+      s2 = (lds_d2[0] + lds_d2[1]) + (lds_d2[2] + lds_d2[3]);
+      cnt = (lds_u[0] + lds_u[1]) + (lds_u[2] + lds_u[3]);
+    }
     const float s = scale_from_sum(s2, cnt);
     if (MODE == kAggregate) {
       // the server's output: q_t = Q(SynQ_t) as a message (the thread's 16 coordinates are
