@@ -182,11 +182,7 @@ __global__ __launch_bounds__(kThreads) void indicator_or_kernel(SelArgs a) {
 // Exclusive prefix sum of `v` over the 256 threads and the total; two barriers.
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* lds_w, uint32_t* total) {
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  uint32_t incl = v;
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t o = __shfl_up(incl, off, kWave);
-    if (lane >= off) incl += o;
-  }
+  const uint32_t incl = wave_inclusive_scan_u32(v);
   __syncthreads();
   if (lane == kWave - 1) lds_w[wave] = incl;
   __syncthreads();
