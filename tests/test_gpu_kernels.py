@@ -466,6 +466,8 @@ AGGQ_CASES = [
     (1, 1, 0, 2), (1000, 4, 0, 2), (4096, 8, 4096, 1), (4097, 8, 4096, 1), (70001, 16, 4096, 1),
     (70001, 20, 4096, 2), (10000, 3, 64, 1), (10000, 5, 256, 1), (70001, 6, 2048, 1),
     (70001, 4, 16384, 1), (70001, 4, 0, 2), (9000, 48, 4096, 1), (4100, 8, 512, 2),
+    # complete chunks of 16 and of 8 workers, one to four of them, rows ending inside a 16-byte group
+    (70001, 32, 4096, 1), (70001, 64, 4096, 1), (9000, 24, 4096, 1), (8192 + 16 * 7 + 5, 40, 4096, 1),
 ]
 
 
