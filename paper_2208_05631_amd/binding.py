@@ -46,6 +46,15 @@ class Layout(C.Structure):
         nb = (d + bucket - 1) // bucket if bucket else 1
         return Layout(d, M, bucket, thr_coef, code_stride or W, scale_stride or nb)
 
+    @staticmethod
+    def spaced_code_stride(d):
+        """A code_stride (in words) for large d: every worker's row starts on a 1 KiB boundary,
+        3 KiB (mod 16 KiB) after the previous one.  Rows a power of two apart send the M code
+        streams of a tile to the same memory channels (see the note on qa_layout in the header)."""
+        stride = (d + 15) // 16
+        stride += (-stride) % 256
+        return stride + 256 * ((3 - stride // 256) % 16)
+
     @property
     def words(self):
         return (self.d + 15) // 16

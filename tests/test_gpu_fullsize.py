@@ -45,7 +45,7 @@ def test_sampled_buckets_at_full_size(name):
     rng = np.random.default_rng(17)
     sample = np.unique(np.concatenate([[0, 1, nb - 2, nb - 1], rng.integers(0, nb, 60)]))
     W = (d + 15) // 16
-    L = qa.Layout.make(d, M, b, code_stride=W + (-W) % 64)      # bench.py's stride: 256-byte rows
+    L = qa.Layout.make(d, M, b, code_stride=qa.Layout.spaced_code_stride(d))   # bench.py's stride
     L1 = qa.Layout.make(d, 1, b, code_stride=L.code_stride, scale_stride=L.scale_stride)
     codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
     scales = torch.zeros((M, L.scale_stride), dtype=torch.float32, device=DEV)
