@@ -340,6 +340,15 @@ def main():
                          "worker's stream starts on a 1 KiB boundary, 3 KiB (mod 16 KiB) after "
                          "the previous one: with a power-of-two distance the M streams of a tile "
                          "meet in the same memory channels, measured 1-6 %% slower)")
+    ap.add_argument("--state-placement", choices=("spread", "block"), default=None,
+                    help="x, G, z as rows chosen by a short probe among five allocations lying "
+                         "about 44 GiB apart (spread: the default from d = 2^26 on), or as one "
+                         "contiguous [3][d] block (block).  The record carries the probe's table "
+                         "and, for spread, the block's step times measured after the timed steps")
+    ap.add_argument("--placement-rows", default=None,
+                    help="with spread placement: take these three of the five candidate rows as "
+                         "x, G, z (e.g. 0,1,4) instead of probing, and skip the block's measurement: "
+                         "for profiler runs, whose per-kernel statistics count every launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="tiny_train / sparse_train: replay the timed steps from one HIP graph")
@@ -384,8 +393,20 @@ def main():
     # lie relative to each other (measured in one process: +4 % when G and z are shifted by 4 KiB
     # and 8 KiB against x), and three separate allocations leave that to the allocator.
     row = (d + 16383) // 16384 * 16384
-    state = torch.zeros((3, row), dtype=torch.float32, device=dev)
-    x, G, z = state[0, :d], state[1, :d], state[2, :d]
+    if args.state_placement is None:
+        args.state_placement = "spread" if d >= (1 << 26) else "block"
+    placement = {"mode": args.state_placement}
+    if args.state_placement == "spread":
+        # Five candidate rows far apart in device memory; which three serve as x, G, z is decided
+        # by a probe once the messages exist (below), before the warm-up.
+        from paper_2208_05631_amd import placement as qa_placement
+        cand, spacer = qa_placement.spread_rows(5, row, dev)
+        placement.update(candidates=len(cand), spacer_GiB=round(spacer / 2**30, 1))
+        state = None
+        x, G, z = cand[0][:d], cand[1][:d], cand[2][:d]
+    else:
+        state = torch.zeros((3, row), dtype=torch.float32, device=dev)
+        x, G, z = state[0, :d], state[1, :d], state[2, :d]
 
     # ---- inputs: generate each worker's gradient on the device, quantize, keep only codes ----
     codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=dev)
@@ -439,6 +460,36 @@ def main():
             qa.qa_step_qcmd(L, codes, scales, x, G, z if k == "qcmd_z" else None, eta, lam, delta,
                             requant, wss)
         return k
+
+    def probe_ms(rx, rG, rz, n=4):
+        # n steps of the timed schedule on these rows (after one untimed step)
+        nonlocal x, G, z
+        x, G, z = rx[:d], rG[:d], rz[:d]
+        step(1)
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        for s_ in range(n):
+            step(2 + s_)
+        p1.record()
+        torch.cuda.synchronize()
+        return p0.elapsed_time(p1) / n
+
+    if args.state_placement == "spread":
+        if args.placement_rows:
+            best = tuple(int(v) for v in args.placement_rows.split(","))
+            assert len(best) == 3 and len(set(best)) == 3 and all(0 <= v < len(cand) for v in best)
+            placement.update(chosen=list(best), probe_ms_per_step=None)
+        else:
+            best, table = qa_placement.choose_rows(cand, 3, probe_ms)
+            placement.update(chosen=list(best),
+                             probe_ms_per_step={str(c): round(v, 3) for c, v in table.items()})
+        placement["row_ptrs"] = [hex(r.data_ptr()) for r in cand]
+        keep = [cand[i] for i in best]
+        del cand
+        for r in keep:
+            r.zero_()                                     # the probe stepped on them
+        x, G, z = keep[0][:d], keep[1][:d], keep[2][:d]
+        torch.cuda.empty_cache()
 
     t = 0
     for _ in range(args.warmup):
@@ -520,6 +571,17 @@ def main():
             also["aggregate_quantize_bucket"] = entry(avg, n_also, M / 4 + 0.25)
             del qc, qs
 
+    # ---- the same schedule with x, G, z as one contiguous block, for the record ----
+    if args.state_placement == "spread" and wl["schedule"] == "alternate" and not args.placement_rows:
+        blk = torch.zeros((3, row), dtype=torch.float32, device=dev)
+        kx, kG, kz = x, G, z
+        x, G, z = blk[0, :d], blk[1, :d], blk[2, :d]
+        placement["block_ms"] = {
+            "qcmd_z": timed_launches(lambda: step(1), n_also),
+            "qrda": timed_launches(lambda: step(2), n_also)}
+        x, G, z = kx, kG, kz
+        del blk
+
     # ---- what this machine's memory system gives a plain copy: fp32 elementwise kernel with 128-bit
     # accesses (torch's), min(d, 2^30) elements, 8 B moved per element ----
     n_copy = min(d, 1 << 30)
@@ -543,7 +605,13 @@ def main():
                    "code_pad_words": args.code_pad_words,
                    "messages": "one set of M quantized gradients, generated and quantized before the "
                                "timed region, is re-used by every step (the step time depends on "
-                               "the values by about 2 %)"},
+                               "the values by about 2 %)",
+                   "state_placement": ("x, G, z: the fastest of the ordered choices of three among five "
+                                       "rows allocated about 44 GiB apart, by a probe of four steps each "
+                                       "before the warm-up (state_placement in this record has the table "
+                                       "and the contiguous block's times)"
+                                       if args.state_placement == "spread" else
+                                       "x, G, z: one contiguous [3][d] block")},
         "roofline": {"bound": "hbm", "kernel": f"step_lut_kernel[{dominant}]",
                      "achieved": dk["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": dk["achieved_GBps"] / HBM_PEAK_GBPS,
@@ -572,6 +640,10 @@ def main():
         "nnz_x_after": nnz_x,
         "device": torch.cuda.get_device_name(0),
         "device_state": DEVICE_STATE,
+        # where the two big blocks lie (the step time varies between processes)
+        "buffers": {"state": hex(x.data_ptr()), "codes": hex(codes.data_ptr())},
+        # how x, G, z were placed in device memory (see paper_2208_05631_amd/placement.py)
+        "state_placement": placement,
     }
 
     # ---- CPU baseline: the oracle as it stands, one host thread pinned to one core, on a

@@ -15,3 +15,4 @@ from .binding import (  # noqa: F401
     qa_step_qcmd_selected, qa_step_qrda_selected, qa_aggregate_quantize, qa_aggregate_quantize_selected,
     qa_quantize_pack_static,
 )
+from . import placement  # noqa: F401,E402  (where large arrays lie in device memory)
