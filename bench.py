@@ -311,22 +311,40 @@ DEVICE_STATE = None
 
 
 def device_state():
-    """Clocks and power cap of GPU 0 as rocm-smi reports them (a child process, read-only), or
-    None if the tool is missing, fails or prints something else than JSON."""
-    import json
-    import shutil
-    import subprocess
-    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    """Clocks, performance level and power cap of the first AMD GPU as sysfs shows them (plain
+    file reads: no child process), or None where those files are not visible."""
+    import glob
     try:
-        out = subprocess.run([tool, "-d", "0", "--showclocks", "--showmaxpower", "--showperflevel", "--json"],
-                             capture_output=True, text=True, timeout=30)
-        txt = out.stdout[out.stdout.index("{"):out.stdout.rindex("}") + 1]
-        card = next(iter(json.loads(txt).values()))
-        keep = {k: v for k, v in card.items()
-                if any(w in k.lower() for w in ("sclk", "mclk", "fclk", "power", "performance"))}
-        return dict(keep, read="before the run, GPU idle") if keep else None
+        for dev_dir in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+            if not os.path.exists(os.path.join(dev_dir, "pp_dpm_sclk")):
+                continue
+
+            def read(rel):
+                try:
+                    with open(os.path.join(dev_dir, rel)) as f:
+                        return f.read().strip()
+                except OSError:
+                    return None
+
+            def current(rel):                    # the level marked with '*'
+                txt = read(rel)
+                if not txt:
+                    return None
+                cur = [ln for ln in txt.splitlines() if ln.rstrip().endswith("*")]
+                return (cur[0] if cur else txt.splitlines()[-1]).replace("*", "").strip()
+
+            out = {"sclk": current("pp_dpm_sclk"), "mclk": current("pp_dpm_mclk"),
+                   "fclk": current("pp_dpm_fclk"),
+                   "performance_level": read("power_dpm_force_performance_level")}
+            caps = glob.glob(os.path.join(dev_dir, "hwmon", "hwmon*", "power1_cap"))
+            if caps:
+                with open(caps[0]) as f:
+                    out["power_cap_W"] = int(f.read().strip()) / 1e6
+            out = {k: v for k, v in out.items() if v is not None}
+            return dict(out, read="sysfs, before the run, GPU idle") if out else None
     except Exception:
-        return None
+        pass
+    return None
 
 
 def main():
