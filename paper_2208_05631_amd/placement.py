@@ -3,8 +3,9 @@
 Device-memory plumbing only (torch allocations): no step of the method runs here.
 
 On MI355X the time of the fused step depends on where x, G and z lie relative to each other and
-to the code rows, by up to 8 % at d = 2^30: the step streams M + 3 arrays at once, and arrays
-whose addresses differ only in certain high bits meet in the same memory channels and banks.
+to the code rows, by up to 8 % at d = 2^30: the step streams M + 3 arrays at once, and
+(presumably) arrays whose addresses differ only in certain high bits meet in the same memory
+channels and banks; plain two-array copies between any two such rows run at the same rate.
 Measured in one process (M = 64, same messages): x, G, z as one contiguous [3][d] block
 7.2-7.6 ms per QCMD+z step depending on the block's offset (period 16 GiB); the same three rows
 taken from allocations 48 GiB apart 6.7-7.0 ms, every one of the 60 ordered choices among five such
