@@ -14,7 +14,10 @@ rows being faster than the block.
 The address mapping is not documented, so the helpers here do not compute a placement, they
 measure one: `spread_rows` allocates candidate rows far apart (temporary spacer allocations
 between them, returned to the driver afterwards) and `choose_rows` times a caller-supplied probe
-for every ordered choice of k rows and returns the fastest.
+for choices of k rows until one is as fast as the caller asks, and returns the fastest tried.
+Candidates should come from several allocations of different kinds (separate rows and a
+contiguous block): in some processes every choice among the separate rows is slow and the block
+is fast, in most it is the other way round.
 """
 import itertools
 
@@ -41,9 +44,16 @@ def spread_rows(n, numel, device, dtype=torch.float32, spacer_bytes=44 << 30, re
     return rows, spacer
 
 
-def choose_rows(rows, k, probe_ms):
-    """probe_ms(*k rows) -> milliseconds, called for every ordered choice of k of the rows.
-    Returns (indices of the fastest choice, {choice: ms})."""
-    table = {c: float(probe_ms(*[rows[i] for i in c])) for c in itertools.permutations(range(len(rows)), k)}
+def choose_rows(rows, k, probe_ms, good_enough_ms=None, ordered=False):
+    """probe_ms(*k rows) -> milliseconds, called for choices of k of the rows (every ordered choice
+    with ordered=True, else every combination in index order) until one takes at most
+    `good_enough_ms` (if given) or all have been tried.  Returns (indices of the fastest choice
+    tried, {choice: ms})."""
+    pick = itertools.permutations if ordered else itertools.combinations
+    table = {}
+    for c in pick(range(len(rows)), k):
+        table[c] = float(probe_ms(*[rows[i] for i in c]))
+        if good_enough_ms is not None and table[c] <= good_enough_ms:
+            break
     best = min(table, key=table.get)
     return best, table

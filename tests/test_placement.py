@@ -14,10 +14,16 @@ def test_choose_rows_takes_the_fastest_ordered_choice():
         seen.append((r0, r1))
         return 2 * cost[r0] + cost[r1]
 
-    best, table = placement.choose_rows(rows, 2, probe)
+    best, table = placement.choose_rows(rows, 2, probe, ordered=True)
     assert best == (2, 0)                    # c then a: 2 * 0.5 + 1.0
     assert len(table) == 12 and len(seen) == 12 and table[(2, 0)] == 2.0
     assert table[(0, 2)] == 2.5              # the reverse order is a different choice
+    # combinations in index order, stopping at the first that is good enough
+    del seen[:]
+    best, table = placement.choose_rows(rows, 2, probe, good_enough_ms=2.6)
+    assert best == (0, 2) and list(table) == [(0, 1), (0, 2)] and len(seen) == 2
+    best, table = placement.choose_rows(rows, 2, probe, good_enough_ms=0.1)      # never met: all tried
+    assert len(table) == 6 and best == (0, 2)
 
 
 @pytest.mark.gpu
