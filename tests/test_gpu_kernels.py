@@ -561,7 +561,10 @@ def test_exact_threshold_never_splits_equal_magnitudes_and_handles_zeros(bucket)
 # buckets longer than one tile, and one threshold for a long vector: device-wide ranking
 @pytest.mark.parametrize("d,M,bucket", [(70001, 2, 0), (70001, 2, 8192), (4096 * 5 + 1, 3, 16384),
                                         (4097, 1, 0), (300001, 1, 0), (8192 * 3, 2, 8192),
-                                        ((1 << 20) + 17, 1, 65536)])
+                                        ((1 << 20) + 17, 1, 65536),
+                                        # one bucket that is longer than the vector, buckets ending one
+                                        # past a tile, several workers with a padded gradient stride
+                                        (5000, 2, 8192), (8193, 3, 8192), (4097, 2, 16384)])
 @pytest.mark.parametrize("kind", ["gauss", "student", "laplace_sparse"])
 def test_exact_threshold_over_several_tiles_matches_oracle(d, M, bucket, kind):
     """Section 3.4's optimum over a bucket (or a whole gradient) of many tiles.  At these sizes the
