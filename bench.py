@@ -681,7 +681,7 @@ def main():
         "nnz_x_after": nnz_x,
         "device": torch.cuda.get_device_name(0),
         "device_state": DEVICE_STATE,
-        # where the two big blocks lie (the step time varies between processes)
+        # where the big blocks lie: the step time depends on their placement in device memory
         "buffers": {"state": hex(x.data_ptr()), "codes": hex(codes.data_ptr())},
         # how x, G, z were placed in device memory (see paper_2208_05631_amd/placement.py)
         "state_placement": placement,
