@@ -161,7 +161,7 @@ int qa_local_grad_batched(int format, const float* A_or_vals, const int64_t* ind
  * strict comparisons keep exactly the optimal set; scale and codes follow as usual.  Buckets of
  * up to 4096 components are ranked inside one work-group; longer buckets, and one threshold for
  * a vector of more than 4096 components (Section 3.4's optimum over the whole gradient), are
- * ranked by a device-wide sort, worker after worker, in 16.5 bytes of workspace per component
+ * ranked by a device-wide sort, worker after worker, in 17 bytes of workspace per component
  * (d < 2^32, else QA_ERR_TOO_LARGE); that form calls a library sort, which may enqueue memset
  * operations: do not record it into a HIP graph.  Candidates whose objectives agree to binary64 rounding
  * (likely only beyond some 1e7 components per bucket) may be resolved differently from a

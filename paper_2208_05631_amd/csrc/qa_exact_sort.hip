@@ -207,12 +207,12 @@ static bool bucket_spans_tiles(const qa_layout* L) {
 
 // Bytes this file's passes need beyond the quantizer's own workspace: sorted keys, the per-tile
 // arrays and the sort's temporary storage (another buffer of keys plus its histograms; measured
-// 8.17 bytes per key, declared here with room to spare and checked against the sort's own
-// figure at the call).
+// 8.17 bytes per key, declared here as 9 bytes per key plus 4 MiB and checked against the sort's
+// own figure at the call).
 size_t exact_sort_workspace_bytes(const qa_layout* L) {
   if (!bucket_spans_tiles(L)) return 0;
   const size_t d = (size_t)L->d, nt = (size_t)tiles_of(L->d);
-  return xalign(d * 8) + 4 * xalign(nt * 8) + xalign(d * 8 + d / 2 + (size_t(1) << 20));
+  return xalign(d * 8) + 4 * xalign(nt * 8) + xalign(d * 8 + d + (size_t(4) << 20));
 }
 
 int exact_thresholds_sorted(const qa_layout* L, const float* g, int64_t g_stride, float* thresholds,

@@ -45,7 +45,7 @@ def test_workspace_sizes():
     # (two buffers of 64-bit keys, independent of the worker count) for buckets that span tiles
     assert qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE_EXACT) == 0
     more = qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE_EXACT) - qa.qa_workspace_bytes(Lg, qa.QA_OP_QUANTIZE)
-    assert 16 * 10**6 <= more <= 18 * 10**6
+    assert 16 * 10**6 <= more <= 22 * 10**6
     assert qa.qa_workspace_bytes(L, qa.QA_OP_STEP) >= 4 * 10**6       # averaged vector for GLOBAL
     assert qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_CSR) >= 8 * 8 * 10**6      # M = 8 accumulators
     assert 0 < qa.qa_workspace_bytes(L, qa.QA_OP_GRAD_DENSE) < 8 * 10**6
