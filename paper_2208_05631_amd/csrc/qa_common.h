@@ -41,6 +41,12 @@ inline int check_layout(const qa_layout* L) {
 // already in the workspace, whose first M*ntiles doubles hold them (worker-major), so the first
 // pass over the input is skipped.  Used when the producer of the input computed them on the way.
 constexpr uint32_t kQuantAbsPartialsGiven = 0x80000000u;
+// Internal flags of quantize_launch for a producer that never materialises the quantizer's input
+// (the step kernel recomputing the average from the messages): run only the finalize kernel that
+// turns the workspace's tile sums of |v| into thresholds, or only the one that turns its tile
+// sums and counts of the kept magnitudes into scales.  The input and code pointers are unused.
+constexpr uint32_t kQuantThresholdsOnly = 0x40000000u;
+constexpr uint32_t kQuantScalesOnly = 0x20000000u;
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? QA_OK : QA_ERR_LAUNCH; }
 
@@ -148,22 +154,59 @@ __device__ __forceinline__ uint32_t segment_sum_u32(uint32_t v, int seg, uint32_
   return v;
 }
 
-// This thread's share of part[i0 .. i1): elements i0 + threadIdx.x + k*256, eight loads in
-// flight at a time (a fixed order: the result does not depend on scheduling).
+// This thread's share of part[i0 .. i1): elements i0 + threadIdx.x + k*256, sixteen loads in
+// flight at a time (a fixed order: the result does not depend on scheduling).  These sums run
+// in a single work-group per bucket, so the number of dependent rounds of loads is their time.
+constexpr int kPartialLoads = 16;
+// For the kernels that call them: one or two waves per SIMD is all they ever run at, and saying so
+// keeps the compiler from serialising the loads to save registers (it did: one load, one wait).
+#define QA_FEW_WAVES __attribute__((amdgpu_waves_per_eu(1, 2)))
+__device__ __forceinline__ double fold_partials(const double (&acc)[kPartialLoads]) {
+  double r[kPartialLoads / 2];
+#pragma unroll
+  for (int u = 0; u < kPartialLoads / 2; ++u) r[u] = acc[2 * u] + acc[2 * u + 1];
+#pragma unroll
+  for (int w = kPartialLoads / 4; w >= 1; w /= 2)
+#pragma unroll
+    for (int u = 0; u < w; ++u) r[u] = r[2 * u] + r[2 * u + 1];
+  return r[0];
+}
 template <typename T>
 __device__ __forceinline__ double strided_partial_sum(const T* __restrict__ part, int64_t i0,
                                                       int64_t i1) {
-  double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+  double acc[kPartialLoads];
+#pragma unroll
+  for (int u = 0; u < kPartialLoads; ++u) acc[u] = 0.0;
   int64_t i = i0 + threadIdx.x;
-  for (; i + 7 * kThreads < i1; i += 8 * kThreads) {
-    T v[8];
+  for (; i + (kPartialLoads - 1) * kThreads < i1; i += kPartialLoads * kThreads) {
+    T v[kPartialLoads];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = part[i + u * kThreads];
+    for (int u = 0; u < kPartialLoads; ++u) v[u] = part[i + u * kThreads];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc[u] += (double)v[u];
+    for (int u = 0; u < kPartialLoads; ++u) acc[u] += (double)v[u];
   }
   for (; i < i1; i += kThreads) acc[0] += (double)part[i];
-  return ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+  return fold_partials(acc);
+}
+// The same for a pair of arrays (sums and counts of the same tiles), their loads interleaved.
+template <typename T, typename U>
+__device__ __forceinline__ void strided_partial_sums(const T* __restrict__ pa, const U* __restrict__ pb,
+                                                     int64_t i0, int64_t i1, double* sa, double* sb) {
+  double acc[kPartialLoads], bcc[kPartialLoads];
+#pragma unroll
+  for (int u = 0; u < kPartialLoads; ++u) { acc[u] = 0.0; bcc[u] = 0.0; }
+  int64_t i = i0 + threadIdx.x;
+  for (; i + (kPartialLoads - 1) * kThreads < i1; i += kPartialLoads * kThreads) {
+    T v[kPartialLoads];
+    U w[kPartialLoads];
+#pragma unroll
+    for (int u = 0; u < kPartialLoads; ++u) { v[u] = pa[i + u * kThreads]; w[u] = pb[i + u * kThreads]; }
+#pragma unroll
+    for (int u = 0; u < kPartialLoads; ++u) { acc[u] += (double)v[u]; bcc[u] += (double)w[u]; }
+  }
+  for (; i < i1; i += kThreads) { acc[0] += (double)pa[i]; bcc[0] += (double)pb[i]; }
+  *sa = fold_partials(acc);
+  *sb = fold_partials(bcc);
 }
 
 // Threshold and scale from the binary64 sums, rounded once (Sections 3.4-3.5).

@@ -618,7 +618,7 @@ __global__ __launch_bounds__(kThreads) void quantize_abs_partial_kernel(QuantArg
 }
 
 // finalize 1: one work-group per (bucket, worker): threshold from the tile partials
-__global__ __launch_bounds__(kThreads) void quantize_threshold_finalize_kernel(QuantArgs a) {
+__global__ __launch_bounds__(kThreads) QA_FEW_WAVES void quantize_threshold_finalize_kernel(QuantArgs a) {
   __shared__ double lds_d[kWaves];
   const int64_t k = blockIdx.x;
   const int m = blockIdx.y;
@@ -667,7 +667,7 @@ __global__ __launch_bounds__(kThreads) void quantize_codes_partial_kernel(QuantA
 }
 
 // finalize 2: scale of each (bucket, worker)
-__global__ __launch_bounds__(kThreads) void quantize_scale_finalize_kernel(QuantArgs a) {
+__global__ __launch_bounds__(kThreads) QA_FEW_WAVES void quantize_scale_finalize_kernel(QuantArgs a) {
   __shared__ double lds_d[kWaves];
   __shared__ double lds_c[kWaves];
   const int64_t k = blockIdx.x;
@@ -675,8 +675,8 @@ __global__ __launch_bounds__(kThreads) void quantize_scale_finalize_kernel(Quant
   const int64_t t0 = k * a.tiles_per_bucket;
   const int64_t t1 = (t0 + a.tiles_per_bucket) < a.ntiles ? (t0 + a.tiles_per_bucket) : a.ntiles;
   // counts are integers < 2^53: exact in binary64
-  double s = strided_partial_sum(a.part_sum + (int64_t)m * a.ntiles, t0, t1);
-  double c = strided_partial_sum(a.part_cnt + (int64_t)m * a.ntiles, t0, t1);
+  double s, c;
+  strided_partial_sums(a.part_sum + (int64_t)m * a.ntiles, a.part_cnt + (int64_t)m * a.ntiles, t0, t1, &s, &c);
   s = segment_sum(s, kThreads, lds_d);
   c = segment_sum(c, kThreads, lds_c);
   if (threadIdx.x == 0)
@@ -891,6 +891,19 @@ size_t quantize_workspace_bytes(const qa_layout* L) {
          align256((size_t)L->M * nb * sizeof(float));
 }
 
+// Where the multi-pass quantizer keeps its per-tile sums, counts and per-bucket thresholds inside
+// its workspace (all worker-major).
+void quantize_workspace_parts(const qa_layout* L, void* ws, double** part_sum, uint32_t** part_cnt,
+                              float** thr) {
+  char* p = static_cast<char*>(ws);
+  const int64_t nt = tiles_of(L->d);
+  *part_sum = reinterpret_cast<double*>(p);
+  p += align256((size_t)L->M * nt * sizeof(double));
+  *part_cnt = reinterpret_cast<uint32_t*>(p);
+  p += align256((size_t)L->M * nt * sizeof(uint32_t));
+  *thr = reinterpret_cast<float*>(p);
+}
+
 int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32_t* codes,
                     float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
                     hipStream_t stream) {
@@ -906,6 +919,10 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   if (a.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
   const dim3 grid_tiles((unsigned)a.ntiles, (unsigned)L->M);
   const bool one_pass = (L->bucket != 0 && L->bucket <= kTile) || (L->bucket == 0 && a.ntiles == 1);
+  // the finalize-only forms exist for the multi-pass quantizer alone, and never with other flags
+  if ((flags & (kQuantThresholdsOnly | kQuantScalesOnly)) &&
+      (one_pass || (flags & (QA_THRESH_GIVEN | QA_THRESH_EXACT))))
+    return QA_ERR_INVALID_ARG;
   if ((flags & QA_THRESH_EXACT) && !one_pass) {
     // buckets that span tiles: device-wide ranking, in the part of the workspace that follows
     // the multi-pass quantizer's own
@@ -954,17 +971,20 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   const size_t need = quantize_workspace_bytes(L);
   if (!ws || ws_bytes < need) return QA_ERR_WORKSPACE;
   if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
-  char* p = static_cast<char*>(ws);
-  a.part_sum = reinterpret_cast<double*>(p);
-  p += align256((size_t)L->M * a.ntiles * sizeof(double));
-  a.part_cnt = reinterpret_cast<uint32_t*>(p);
-  p += align256((size_t)L->M * a.ntiles * sizeof(uint32_t));
-  a.thr_ws = reinterpret_cast<float*>(p);
+  quantize_workspace_parts(L, ws, &a.part_sum, &a.part_cnt, &a.thr_ws);
   a.bucket_len = L->bucket ? L->bucket : L->d;
   a.tiles_per_bucket = L->bucket ? L->bucket / kTile : a.ntiles;
   a.log2b = L->bucket ? ilog2(L->bucket) : 0;
   const dim3 grid_buckets((unsigned)a.nb, (unsigned)L->M);
 
+  if (flags & kQuantThresholdsOnly) {
+    hipLaunchKernelGGL(quantize_threshold_finalize_kernel, grid_buckets, block, 0, stream, a);
+    return launch_status();
+  }
+  if (flags & kQuantScalesOnly) {
+    hipLaunchKernelGGL(quantize_scale_finalize_kernel, grid_buckets, block, 0, stream, a);
+    return launch_status();
+  }
   if (!a.thresh_given) {
     if (!(flags & kQuantAbsPartialsGiven))
       hipLaunchKernelGGL(quantize_abs_partial_kernel, grid_tiles, block, 0, stream, a);

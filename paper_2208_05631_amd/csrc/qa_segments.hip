@@ -72,7 +72,7 @@ __device__ __forceinline__ void piece_range(const SegTable& T, int64_t s, int64_
   *p0 = a; *p1 = b;
 }
 
-__global__ __launch_bounds__(kThreads) void seg_threshold_finalize_kernel(SegQuantArgs a) {
+__global__ __launch_bounds__(kThreads) QA_FEW_WAVES void seg_threshold_finalize_kernel(SegQuantArgs a) {
   __shared__ double lds_d[kWaves];
   const int64_t s = blockIdx.x;
   const int m = blockIdx.y;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void seg_codes_partial_kernel(SegQuantArg
   }
 }
 
-__global__ __launch_bounds__(kThreads) void seg_scale_finalize_kernel(SegQuantArgs a) {
+__global__ __launch_bounds__(kThreads) QA_FEW_WAVES void seg_scale_finalize_kernel(SegQuantArgs a) {
   __shared__ double lds_d[kWaves];
   __shared__ double lds_c[kWaves];
   const int64_t s = blockIdx.x;
@@ -140,8 +140,9 @@ __global__ __launch_bounds__(kThreads) void seg_scale_finalize_kernel(SegQuantAr
   int64_t p0, p1;
   piece_range(a.seg, s, &p0, &p1);
   // counts are integers < 2^53: exact in binary64
-  double sum = strided_partial_sum(a.part_sum + (int64_t)m * a.seg.n_pieces, p0, p1);
-  double cnt = strided_partial_sum(a.part_cnt + (int64_t)m * a.seg.n_pieces, p0, p1);
+  double sum, cnt;
+  strided_partial_sums(a.part_sum + (int64_t)m * a.seg.n_pieces, a.part_cnt + (int64_t)m * a.seg.n_pieces, p0, p1,
+                       &sum, &cnt);
   sum = segment_sum(sum, kThreads, lds_d);
   cnt = segment_sum(cnt, kThreads, lds_c);
   if (threadIdx.x == 0)

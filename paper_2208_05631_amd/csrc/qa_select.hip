@@ -821,15 +821,15 @@ __global__ __launch_bounds__(kThreads) void gsel_quantize_multi_kernel(SelArgs a
 }
 
 // last pass of the multi-tile quantizer: scale of each (bucket, worker)
-__global__ __launch_bounds__(kThreads) void gsel_scale_kernel(SelArgs a) {
+__global__ __launch_bounds__(kThreads) QA_FEW_WAVES void gsel_scale_kernel(SelArgs a) {
   __shared__ double lds_d[kWaves];
   __shared__ double lds_c[kWaves];
   const int64_t k = blockIdx.x;
   const int m = blockIdx.y;
   const int64_t t0 = k * a.tiles_per_bucket;
   const int64_t t1 = t0 + a.tiles_per_bucket < a.ntiles ? t0 + a.tiles_per_bucket : a.ntiles;
-  double s = strided_partial_sum(a.ws_s2 + (int64_t)m * a.ntiles, t0, t1);
-  double c = strided_partial_sum(a.ws_c2 + (int64_t)m * a.ntiles, t0, t1);
+  double s, c;
+  strided_partial_sums(a.ws_s2 + (int64_t)m * a.ntiles, a.ws_c2 + (int64_t)m * a.ntiles, t0, t1, &s, &c);
   s = segment_sum(s, kThreads, lds_d);
   c = segment_sum(c, kThreads, lds_c);
   if (threadIdx.x == 0) a.scales[(int64_t)m * a.scale_stride + k] = scale_from_sum(s, (uint64_t)c);

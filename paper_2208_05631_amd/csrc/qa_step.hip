@@ -18,6 +18,10 @@
 namespace qa {
 
 enum StepMode { kAggregate = 0, kQcmd = 1, kQrda = 2 };
+// The second quantization q = Q(SynQ): none; formed inside the kernel (buckets that fit the tile);
+// or with the threshold and scale of each bucket handed in (buckets that span tiles and one
+// scale per vector, whose sums earlier launches of the same kernel have left in the workspace).
+enum Requant { kRqNone = 0, kRqInTile = 1, kRqGiven = 2 };
 
 struct StepArgs {
   const uint32_t* codes;
@@ -32,6 +36,12 @@ struct StepArgs {
   int span_limit;     // max exponent span of a tile's scales for which any order is exact
   float* x; float* G; float* z; float* gbar;
   double* abs_partials;   // aggregate mode, optional: sum of |gbar| of each tile (first pass of a quantizer)
+  // Second quantization over buckets of rq_tiles tiles each (kRqGiven; the vector's tiles when it
+  // has one scale): threshold and scale of every bucket, and (aggregate mode, optional, instead of
+  // gbar) each tile's sum and count of the |gbar| above its bucket's threshold
+  const float* rq_thr; const float* rq_scale;
+  double* kept_sum; uint32_t* kept_cnt;
+  int64_t rq_tiles;
   float eta, lam_eta, delta, t_lam, thr_coef;
   // Tiles whose scales all have biased exponents in [fast_emin, fast_emax] (and pass the span
   // test) may take the short forms of sqrt and division in the update: every numerator and
@@ -333,8 +343,9 @@ __device__ __forceinline__ void lookup_indices(const uint32_t zq[4], const doubl
 // two workers share one 32-bit prefix scan over the work-group); the codes are fetched from the
 // stream and spread to the marked fields through the deposit table.  The result is the word the
 // stand-alone decoder would have written, and everything after it is the dense path.
-template <int MODE, bool TRACK_Z, bool REQUANT, int NGT, bool SPARSE = false>
+template <int MODE, bool TRACK_Z, int RQ, int NGT, bool SPARSE = false>
 __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
+  constexpr bool REQUANT = RQ == kRqInTile;
   static_assert(!SPARSE || NGT == 0, "sparse input: chunks of 16 workers with guards");
   constexpr bool FULL = NGT > 1;
   constexpr int kGroupsPerChunk = NGT >= 1 ? NGT : kMaxGroups;
@@ -678,6 +689,34 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     s1 = block_sum_f64(s1, lds_d);
     if (t == 0) a.abs_partials[tile] = s1;
   }
+  if (MODE == kAggregate && RQ == kRqNone && a.kept_sum) {   // uniform
+    const float Delta = a.rq_thr[tile / a.rq_tiles];
+    double s2 = 0.0;
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float av = fabsf(q[j]);                       // dead lanes hold zeros
+      if (av > Delta) { s2 += (double)av; ++cnt; }
+    }
+    s2 = wave_sum_f64(s2);
+    cnt = wave_sum_u32(cnt);
+    if ((t % kWave) == 0) { lds_d2[t / kWave] = s2; lds_u[t / kWave] = cnt; }
+    __syncthreads();
+    if (t == 0) {
+      a.kept_sum[tile] = (lds_d2[0] + lds_d2[1]) + (lds_d2[2] + lds_d2[3]);
+      a.kept_cnt[tile] = (lds_u[0] + lds_u[1]) + (lds_u[2] + lds_u[3]);
+    }
+    return;
+  }
+  if (MODE == kAggregate && RQ == kRqNone && !a.gbar) return;   // uniform: only the sums were wanted
+
+  if (RQ == kRqGiven) {
+    static_assert(RQ != kRqGiven || MODE != kAggregate, "the server's call writes the average out");
+    const int64_t k2 = tile / a.rq_tiles;
+    const float Delta = a.rq_thr[k2], s = a.rq_scale[k2];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
+  }
 
   if (REQUANT) {
     // second quantization of the average, per bucket: the whole tile, or (buckets smaller than
@@ -817,6 +856,8 @@ size_t quantize_workspace_bytes(const qa_layout* L);
 int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32_t* codes,
                     float* scales, float* thresholds, uint32_t flags, void* ws, size_t ws_bytes,
                     hipStream_t stream);
+void quantize_workspace_parts(const qa_layout* L, void* ws, double** part_sum, uint32_t** part_cnt,
+                              float** thr);
 
 // Layout of the one-message vector that carries Q(SynQ) when it is formed in separate passes.
 static qa_layout requant_layout(const qa_layout* L, int requant) {
@@ -922,38 +963,74 @@ static void set_fast_limits(StepArgs& a, int mode, float eta, float lam_eta, flo
   a.fast_r_lo = lo_bits; a.fast_r_span = hi_bits - lo_bits;
 }
 
-template <int MODE, bool TRACK_Z, bool REQUANT, int NGT, bool SPARSE = false>
+template <int MODE, bool TRACK_Z, int RQ, int NGT, bool SPARSE = false>
 static void launch_lut(const StepArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
-  hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, REQUANT, NGT, SPARSE>), grid, block, 0, stream, a);
+  hipLaunchKernelGGL((step_lut_kernel<MODE, TRACK_Z, RQ, NGT, SPARSE>), grid, block, 0, stream, a);
 }
 
 // ngt: the NGT of the kernel variant
-template <int MODE, bool TRACK_Z, bool REQUANT>
+template <int MODE, bool TRACK_Z, int RQ>
 static void launch_one(const StepArgs& a, int ngt, hipStream_t stream) {
   const dim3 grid((unsigned)(a.seg.piece_tile ? a.seg.n_pieces : tiles_of(a.d))), block(kThreads);
-  if (a.ind) {                                           // sparse-encoded messages
-    launch_lut<MODE, TRACK_Z, REQUANT, 0, true>(a, grid, block, stream);
-    return;
+  if constexpr (RQ != kRqGiven) {                        // (never asked for with sparse messages)
+    if (a.ind) {                                         // sparse-encoded messages
+      launch_lut<MODE, TRACK_Z, RQ, 0, true>(a, grid, block, stream);
+      return;
+    }
   }
   switch (ngt) {
-    case 4: launch_lut<MODE, TRACK_Z, REQUANT, 4>(a, grid, block, stream); break;
-    case 2: launch_lut<MODE, TRACK_Z, REQUANT, 2>(a, grid, block, stream); break;
-    case 1: launch_lut<MODE, TRACK_Z, REQUANT, 1>(a, grid, block, stream); break;
-    default: launch_lut<MODE, TRACK_Z, REQUANT, 0>(a, grid, block, stream); break;
+    case 4: launch_lut<MODE, TRACK_Z, RQ, 4>(a, grid, block, stream); break;
+    case 2: launch_lut<MODE, TRACK_Z, RQ, 2>(a, grid, block, stream); break;
+    case 1: launch_lut<MODE, TRACK_Z, RQ, 1>(a, grid, block, stream); break;
+    default: launch_lut<MODE, TRACK_Z, RQ, 0>(a, grid, block, stream); break;
   }
 }
 
-template <int MODE>
-static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
+template <int MODE, int RQ>
+static void launch_mode_rq(const StepArgs& a, bool track_z, hipStream_t stream) {
   // buckets smaller than the tile take the ordered sum: the variant with the fewest registers
   const int which = !a.tile_uniform ? 1 : a.M % 16 == 0 ? 4 : a.M % 8 == 0 ? 2 : a.M <= 4 ? 1 : 0;
-  if (requant) {
-    if (track_z) launch_one<MODE, true, true>(a, which, stream);
-    else launch_one<MODE, false, true>(a, which, stream);
-  } else {
-    if (track_z) launch_one<MODE, true, false>(a, which, stream);
-    else launch_one<MODE, false, false>(a, which, stream);
+  if constexpr (MODE == kQcmd) {
+    if (track_z) { launch_one<MODE, true, RQ>(a, which, stream); return; }
   }
+  launch_one<MODE, false, RQ>(a, which, stream);
+}
+template <int MODE>
+static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream_t stream) {
+  if (requant) launch_mode_rq<MODE, kRqInTile>(a, track_z, stream);
+  else launch_mode_rq<MODE, kRqNone>(a, track_z, stream);
+}
+
+// A second quantization in separate passes needs the average three times (sums of |gbar|, sums of
+// the kept |gbar|, the update).  With few workers the steps form it from the messages each time
+// (M/4 bytes per coordinate and pass) instead of writing it out once and reading it back twice
+// (4 bytes each).  The sum passes are bound by instructions, not bytes, so the gain ends early:
+// measured at d = 1e8, one scale per vector, QCMD step 0.440 -> 0.400 ms at M = 2,
+// 0.446 -> 0.409 at M = 4, 0.464 -> 0.450 at M = 8, but 0.515 -> 0.600 at M = 12; the server's
+// call, which has no state to read, is faster with the average written out at every M.
+constexpr int kRecomputeMaxM = 8;
+
+// The first two of those passes and the two finalize kernels between and after them: leaves the
+// thresholds and scales of Q(SynQ) in thr[] and scales[] (one per bucket of R).
+static int requant_sums_from_messages(const StepArgs& messages, const qa_layout* R, float* scales,
+                                      float* thresholds, void* qws, size_t qws_bytes,
+                                      const float** thr_out, hipStream_t stream) {
+  if (!qws || qws_bytes == 0 || qws_bytes < quantize_workspace_bytes(R)) return QA_ERR_WORKSPACE;
+  double* part_sum; uint32_t* part_cnt; float* thr;
+  quantize_workspace_parts(R, qws, &part_sum, &part_cnt, &thr);
+  StepArgs ag = messages;
+  ag.abs_partials = part_sum;
+  launch_mode<kAggregate>(ag, false, false, stream);
+  int rc = quantize_launch(R, nullptr, 0, nullptr, scales, thresholds,
+                           kQuantAbsPartialsGiven | kQuantThresholdsOnly, qws, qws_bytes, stream);
+  if (rc != QA_OK) return rc;
+  ag.abs_partials = nullptr;
+  ag.kept_sum = part_sum; ag.kept_cnt = part_cnt; ag.rq_thr = thr;
+  ag.rq_tiles = R->bucket ? R->bucket / kTile : tiles_of(R->d);
+  launch_mode<kAggregate>(ag, false, false, stream);
+  *thr_out = thr;
+  return quantize_launch(R, nullptr, 0, nullptr, scales, thresholds, kQuantScalesOnly, qws, qws_bytes,
+                         stream);
 }
 
 // sparse: `codes` are compact per-bucket streams to be expanded through the indicators `ind`
@@ -997,13 +1074,29 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
   const uint32_t* use_codes = codes;
   const float* use_scales = scales;
   bool fused_requant = false;
+  const float* given_thr = nullptr;
+  const float* given_scale = nullptr;
   if (requant != QA_REQUANT_NONE) {
+    R = requant_layout(L, requant);
     if (requant_in_tile(L, requant)) {
       fused_requant = true;
+    } else if (!sparse && L->M <= kRecomputeMaxM && quantize_workspace_bytes(&R) != 0) {
+      // separate passes, each forming gbar from the messages: sums of |gbar| -> thresholds, sums
+      // of the kept |gbar| -> scales, then the update with both handed in.  (Not when Q(SynQ) is
+      // a one-pass quantization, i.e. one scale for a vector that is a single tile while the
+      // messages' buckets are smaller: that quantizer keeps no sums in a workspace.)
+      if (!ws || ws_bytes < requant_need(L, &R)) return QA_ERR_WORKSPACE;
+      if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+      char* p = static_cast<char*>(ws);
+      float* s1 = reinterpret_cast<float*>(p);            p += align256((size_t)R.scale_stride * 4);
+      const size_t qws = quantize_workspace_bytes(&R);
+      rc = requant_sums_from_messages(make_args(L, codes, scales), &R, s1, nullptr, p, qws, &given_thr,
+                                      stream);
+      if (rc != QA_OK) return rc;
+      given_scale = s1;
     } else {
       // separate passes: gbar -> workspace, quantize it as a one-worker message, then run the
       // update on that message (its decoded value s*c is q exactly)
-      R = requant_layout(L, requant);
       if (!ws || ws_bytes < requant_need(L, &R)) return QA_ERR_WORKSPACE;
       if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
       char* p = static_cast<char*>(ws);
@@ -1034,6 +1127,13 @@ static int step_common(int mode, const qa_layout* L, const uint32_t* codes, cons
   a.eta = eta; a.lam_eta = lambda * eta; a.delta = delta;
   a.t_lam = (float)t * lambda;
   set_fast_limits(a, mode, eta, a.lam_eta, delta);
+  if (given_thr) {
+    a.rq_thr = given_thr; a.rq_scale = given_scale;
+    a.rq_tiles = R.bucket ? R.bucket / kTile : tiles_of(L->d);
+    if (mode == kQcmd) launch_mode_rq<kQcmd, kRqGiven>(a, track_z, stream);
+    else launch_mode_rq<kQrda, kRqGiven>(a, false, stream);
+    return launch_status();
+  }
   if (mode == kQcmd) launch_mode<kQcmd>(a, track_z, fused_requant, stream);
   else launch_mode<kQrda>(a, false, fused_requant, stream);
   return launch_status();

@@ -226,6 +226,14 @@ STEP_CASES = [
     (10000, 3, 64, 0), (10000, 9, 256, 0), (70001, 16, 1024, 0), (70001, 64, 2048, 2), (4100, 8, 512, 2),
     # the largest worker count the layout accepts, and a large odd one
     (5000, 4096, 4096, 0), (3000, 1001, 0, 2),
+    # second quantization over buckets that span tiles: few workers (the average is formed from the
+    # messages in every pass) with chunks of 16, 8, 4 and guarded chunks; many workers (the average
+    # is written to the workspace once)
+    (70001, 16, 0, 2), (70001, 8, 8192, 1), (70001, 3, 0, 2), (70001, 13, 16384, 1), (9000, 16, 64, 2),
+    (70001, 24, 0, 2), (70001, 20, 16384, 1),
+    # ... and where that second quantization is a one-pass one although it is not formed in the
+    # step kernel (single tile, messages with smaller buckets), or spans "several" tiles of one
+    (3000, 4, 64, 2), (4096, 8, 1024, 2), (50, 3, 8192, 1),
 ]
 
 
@@ -466,6 +474,7 @@ AGGQ_CASES = [
     (1, 1, 0, 2), (1000, 4, 0, 2), (4096, 8, 4096, 1), (4097, 8, 4096, 1), (70001, 16, 4096, 1),
     (70001, 20, 4096, 2), (10000, 3, 64, 1), (10000, 5, 256, 1), (70001, 6, 2048, 1),
     (70001, 4, 16384, 1), (70001, 4, 0, 2), (9000, 48, 4096, 1), (4100, 8, 512, 2),
+    (70001, 16, 0, 2), (70001, 8, 8192, 1), (70001, 13, 0, 2), (70001, 24, 16384, 1),
     # complete chunks of 16 and of 8 workers, one to four of them, rows ending inside a 16-byte group
     (70001, 32, 4096, 1), (70001, 64, 4096, 1), (9000, 24, 4096, 1), (8192 + 16 * 7 + 5, 40, 4096, 1),
 ]
