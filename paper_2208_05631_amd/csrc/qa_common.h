@@ -41,13 +41,6 @@ inline int check_layout(const qa_layout* L) {
 // already in the workspace, whose first M*ntiles doubles hold them (worker-major), so the first
 // pass over the input is skipped.  Used when the producer of the input computed them on the way.
 constexpr uint32_t kQuantAbsPartialsGiven = 0x80000000u;
-// Internal flags of quantize_launch for a producer that never materialises the quantizer's input
-// (the step kernel recomputing the average from the messages): run only the finalize kernel that
-// turns the workspace's tile sums of |v| into thresholds, or only the one that turns its tile
-// sums and counts of the kept magnitudes into scales.  The input and code pointers are unused.
-constexpr uint32_t kQuantThresholdsOnly = 0x40000000u;
-constexpr uint32_t kQuantScalesOnly = 0x20000000u;
-
 inline int launch_status() { return hipGetLastError() == hipSuccess ? QA_OK : QA_ERR_LAUNCH; }
 
 // ---- device-side reductions (binary64, fixed order: run-to-run deterministic) -----------

@@ -919,10 +919,6 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   if (a.ntiles > 0x7fffffffLL) return QA_ERR_INVALID_ARG;
   const dim3 grid_tiles((unsigned)a.ntiles, (unsigned)L->M);
   const bool one_pass = (L->bucket != 0 && L->bucket <= kTile) || (L->bucket == 0 && a.ntiles == 1);
-  // the finalize-only forms exist for the multi-pass quantizer alone, and never with other flags
-  if ((flags & (kQuantThresholdsOnly | kQuantScalesOnly)) &&
-      (one_pass || (flags & (QA_THRESH_GIVEN | QA_THRESH_EXACT))))
-    return QA_ERR_INVALID_ARG;
   if ((flags & QA_THRESH_EXACT) && !one_pass) {
     // buckets that span tiles: device-wide ranking, in the part of the workspace that follows
     // the multi-pass quantizer's own
@@ -977,14 +973,6 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   a.log2b = L->bucket ? ilog2(L->bucket) : 0;
   const dim3 grid_buckets((unsigned)a.nb, (unsigned)L->M);
 
-  if (flags & kQuantThresholdsOnly) {
-    hipLaunchKernelGGL(quantize_threshold_finalize_kernel, grid_buckets, block, 0, stream, a);
-    return launch_status();
-  }
-  if (flags & kQuantScalesOnly) {
-    hipLaunchKernelGGL(quantize_scale_finalize_kernel, grid_buckets, block, 0, stream, a);
-    return launch_status();
-  }
   if (!a.thresh_given) {
     if (!(flags & kQuantAbsPartialsGiven))
       hipLaunchKernelGGL(quantize_abs_partial_kernel, grid_tiles, block, 0, stream, a);
@@ -992,6 +980,37 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
   }
   hipLaunchKernelGGL(quantize_codes_partial_kernel, grid_tiles, block, 0, stream, a);
   hipLaunchKernelGGL(quantize_scale_finalize_kernel, grid_buckets, block, 0, stream, a);
+  return launch_status();
+}
+
+// The multi-pass quantizer's finalize kernels alone, for a producer that leaves the partial sums in
+// the quantizer's workspace itself and never materialises the quantizer's input (the steps that
+// form Q(SynQ) from the messages).  which = 0: thresholds from the partial sums of |v| (also
+// written to thresholds[] if given); which = 1: scales from the partial sums and counts of the
+// kept |v|.  n_partials = 0: one partial per 4096-tile, as the quantizer's own passes leave them;
+// otherwise the layout must have a single bucket, whose n_partials partials (each over some whole
+// tiles, in order) are at the start of the arrays.
+int quantize_finalize_launch(const qa_layout* L, int which, int64_t n_partials, float* scales,
+                             float* thresholds, void* ws, size_t ws_bytes, hipStream_t stream) {
+  const size_t need = quantize_workspace_bytes(L);
+  if (need == 0 || !ws || ws_bytes < need) return QA_ERR_WORKSPACE;   // (need == 0: a one-pass layout)
+  if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
+  QuantArgs a{};
+  a.d = L->d; a.W = words_of(L->d);
+  a.scales = scales; a.thresholds = thresholds; a.scale_stride = L->scale_stride;
+  a.thr_coef = L->thr_coef;
+  a.ntiles = tiles_of(L->d);
+  a.nb = buckets_of(L->d, L->bucket);
+  quantize_workspace_parts(L, ws, &a.part_sum, &a.part_cnt, &a.thr_ws);
+  a.bucket_len = L->bucket ? L->bucket : L->d;
+  a.tiles_per_bucket = L->bucket ? L->bucket / kTile : a.ntiles;
+  if (n_partials != 0) {
+    if (a.nb != 1 || n_partials < 1 || n_partials > a.ntiles || L->M != 1) return QA_ERR_INVALID_ARG;
+    a.ntiles = n_partials; a.tiles_per_bucket = n_partials;
+  }
+  const dim3 grid_buckets((unsigned)a.nb, (unsigned)L->M), block(kThreads);
+  if (which == 0) hipLaunchKernelGGL(quantize_threshold_finalize_kernel, grid_buckets, block, 0, stream, a);
+  else hipLaunchKernelGGL(quantize_scale_finalize_kernel, grid_buckets, block, 0, stream, a);
   return launch_status();
 }
 

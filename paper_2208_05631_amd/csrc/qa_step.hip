@@ -840,6 +840,128 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   if (MODE == kQrda || TRACK_Z) store_state(a.z, tile_base, lo, hi, full_tile, sz);
 }
 
+// ---- the two sums behind Q(SynQ) with one scale, from messages with one scale each -------------
+//
+// One scale per message (the paper's message) and at most 8 workers: the tables of partial sums
+// are the same for every tile, so a work-group builds them once (no exponent-span test per tile, no
+// barrier per chunk) and walks several tiles, keeping its sums in registers; per tile that leaves
+// the loads, the gather, two look-ups per coordinate and the conversion.  PASS 0: sum of |gbar|;
+// PASS 1: sum and count of the |gbar| above the threshold.  One partial per work-group.
+struct SumArgs {
+  const uint32_t* codes;
+  const float* scales;
+  int64_t code_stride, scale_stride;
+  int64_t d, W, ntiles;
+  int M, tiles_per_group, M_pow2, span_limit;
+  double inv_M;
+  const float* thr;                     // PASS 1: the threshold
+  double* part_sum;
+  uint32_t* part_cnt;
+};
+
+template <int PASS>
+__global__ __launch_bounds__(kThreads) void requant_sums_kernel(SumArgs a) {
+  __shared__ double tab[2 * 256];
+  __shared__ double lds_d[kWaves];
+  __shared__ uint32_t lds_u[kWaves];
+  const int t = threadIdx.x;
+  // the workers' scales, the same for every thread; may the sum over workers be reordered?
+  float sc[8];
+  int emax = 0, emin = 255, bad = 0;
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    sc[m] = m < a.M ? a.scales[(int64_t)m * a.scale_stride] : 0.0f;
+    const uint32_t u = __float_as_uint(sc[m]);
+    if ((u << 1) == 0u) continue;
+    int f = (int)((u >> 23) & 0xFFu);
+    if (f == 255) bad = 1;
+    f = f < 1 ? 1 : f;
+    emax = f > emax ? f : emax;
+    emin = f < emin ? f : emin;
+  }
+  const bool reorder_ok = !bad && (emax - emin) <= a.span_limit;
+  if (reorder_ok) {
+    double dj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dj[j] = ((t >> j) & 1) ? (((t >> (4 + j)) & 1) ? -1.0 : 1.0) : 0.0;
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+      tab[g * 256 + t] = fma(dj[3], (double)sc[4 * g + 3],
+                             fma(dj[2], (double)sc[4 * g + 2],
+                                 fma(dj[1], (double)sc[4 * g + 1], dj[0] * (double)sc[4 * g])));
+    __syncthreads();
+  }
+  const float Delta = PASS == 1 ? a.thr[0] : 0.0f;
+  double s = 0.0;
+  uint32_t cnt = 0;
+  const int64_t tile0 = (int64_t)blockIdx.x * a.tiles_per_group;
+  for (int u = 0; u < a.tiles_per_group && tile0 + u < a.ntiles; ++u) {
+    const int64_t tile = tile0 + u;
+    const int64_t words_here = a.W - tile * kTileWords;
+    const uint32_t row_bytes = 4u * (uint32_t)(words_here >= kTileWords ? kTileWords : words_here);
+    const uint32_t* ctile = a.codes + tile * kTileWords;
+    uint32_t w[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m)                           // words beyond the row read as 0
+      w[m] = m < a.M ? stream_load(ctile + (int64_t)m * a.code_stride, 4u * (uint32_t)t, row_bytes) : 0u;
+    double acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0;
+    if (reorder_ok) {
+      uint32_t zq[8];
+      gather_group(w[0], w[1], w[2], w[3], zq);
+      gather_group(w[4], w[5], w[6], w[7], zq + 4);
+      lookup_indices(zq, tab, acc);
+      if (a.M > 4) lookup_indices(zq + 4, tab + 256, acc);
+    } else {                                              // as the sum is written: worker 0, 1, ...
+      for (int m = 0; m < a.M; ++m) {
+        uint32_t wv = 0u;
+        double sv = 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (k == m) { wv = sanitize(w[k]); sv = (double)sc[k]; }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int c = ((int)(wv << (30 - 2 * j))) >> 30;
+          acc[j] = fma((double)c, sv, acc[j]);
+        }
+      }
+    }
+    float q[16];
+    if (a.M_pow2) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] * a.inv_M);
+    } else {
+      const double Md = (double)a.M;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) q[j] = (float)(acc[j] / Md);
+    }
+    const int64_t live = a.d - (tile * kTile + 16 * (int64_t)t);   // fields at or beyond d are no components
+    if (live < 16) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (j >= live) q[j] = 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float av = fabsf(q[j]);
+      if (PASS == 0) s += (double)av;
+      else if (av > Delta) { s += (double)av; ++cnt; }
+    }
+  }
+  s = block_sum_f64(s, lds_d);
+  if (PASS == 1) {
+    cnt = wave_sum_u32(cnt);
+    if ((t % kWave) == 0) lds_u[t / kWave] = cnt;
+    __syncthreads();
+    cnt = (lds_u[0] + lds_u[1]) + (lds_u[2] + lds_u[3]);
+  }
+  if (t == 0) {
+    a.part_sum[blockIdx.x] = s;
+    if (PASS == 1) a.part_cnt[blockIdx.x] = cnt;
+  }
+}
+
 // ---- host side -------------------------------------------------------------------------------
 
 static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -858,6 +980,8 @@ int quantize_launch(const qa_layout* L, const float* g, int64_t g_stride, uint32
                     hipStream_t stream);
 void quantize_workspace_parts(const qa_layout* L, void* ws, double** part_sum, uint32_t** part_cnt,
                               float** thr);
+int quantize_finalize_launch(const qa_layout* L, int which, int64_t n_partials, float* scales,
+                             float* thresholds, void* ws, size_t ws_bytes, hipStream_t stream);
 
 // Layout of the one-message vector that carries Q(SynQ) when it is formed in separate passes.
 static qa_layout requant_layout(const qa_layout* L, int requant) {
@@ -1018,19 +1142,35 @@ static int requant_sums_from_messages(const StepArgs& messages, const qa_layout*
   if (!qws || qws_bytes == 0 || qws_bytes < quantize_workspace_bytes(R)) return QA_ERR_WORKSPACE;
   double* part_sum; uint32_t* part_cnt; float* thr;
   quantize_workspace_parts(R, qws, &part_sum, &part_cnt, &thr);
+  *thr_out = thr;
+  if (messages.log2b < 0 && R->bucket == 0 && messages.M <= 8) {
+    // one scale per message and one for Q(SynQ): the lean kernel, one partial per work-group
+    SumArgs sa{};
+    sa.codes = messages.codes; sa.scales = messages.scales;
+    sa.code_stride = messages.code_stride; sa.scale_stride = messages.scale_stride;
+    sa.d = messages.d; sa.W = messages.W; sa.ntiles = tiles_of(messages.d);
+    sa.M = messages.M; sa.M_pow2 = messages.M_pow2; sa.inv_M = messages.inv_M;
+    sa.span_limit = messages.span_limit;
+    sa.tiles_per_group = sa.ntiles >= 8192 ? 8 : sa.ntiles >= 1024 ? 4 : 1;
+    sa.thr = thr; sa.part_sum = part_sum; sa.part_cnt = part_cnt;
+    const int64_t groups = (sa.ntiles + sa.tiles_per_group - 1) / sa.tiles_per_group;
+    const dim3 grid((unsigned)groups), block(kThreads);
+    hipLaunchKernelGGL(requant_sums_kernel<0>, grid, block, 0, stream, sa);
+    int rc = quantize_finalize_launch(R, 0, groups, scales, thresholds, qws, qws_bytes, stream);
+    if (rc != QA_OK) return rc;
+    hipLaunchKernelGGL(requant_sums_kernel<1>, grid, block, 0, stream, sa);
+    return quantize_finalize_launch(R, 1, groups, scales, thresholds, qws, qws_bytes, stream);
+  }
   StepArgs ag = messages;
   ag.abs_partials = part_sum;
   launch_mode<kAggregate>(ag, false, false, stream);
-  int rc = quantize_launch(R, nullptr, 0, nullptr, scales, thresholds,
-                           kQuantAbsPartialsGiven | kQuantThresholdsOnly, qws, qws_bytes, stream);
+  int rc = quantize_finalize_launch(R, 0, 0, scales, thresholds, qws, qws_bytes, stream);
   if (rc != QA_OK) return rc;
   ag.abs_partials = nullptr;
   ag.kept_sum = part_sum; ag.kept_cnt = part_cnt; ag.rq_thr = thr;
   ag.rq_tiles = R->bucket ? R->bucket / kTile : tiles_of(R->d);
   launch_mode<kAggregate>(ag, false, false, stream);
-  *thr_out = thr;
-  return quantize_launch(R, nullptr, 0, nullptr, scales, thresholds, kQuantScalesOnly, qws, qws_bytes,
-                         stream);
+  return quantize_finalize_launch(R, 1, 0, scales, thresholds, qws, qws_bytes, stream);
 }
 
 // sparse: `codes` are compact per-bucket streams to be expanded through the indicators `ind`

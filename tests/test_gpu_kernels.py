@@ -480,6 +480,46 @@ AGGQ_CASES = [
 ]
 
 
+@pytest.mark.parametrize("d,M", [(70001, 8), (70001, 6), (9000, 1), (4097, 2), (70001 + 4096 * 1100, 5),
+                                 (4096 * 8200 + 17, 4)])
+@pytest.mark.parametrize("scales", ["close", "wide", "inf"])
+def test_steps_with_one_scale_everywhere_match_oracle(d, M, scales):
+    """One scale per message, one for Q(SynQ), few workers: the two sums behind Q(SynQ) come from a
+    kernel of their own that builds its tables once per work-group and walks 1, 4 or 8 tiles (by
+    the vector's length).  Scales close together take its tables, scales spread over 80 binades
+    its worker-ordered sum, an infinite scale poisons the sums; fields of the last code word beyond
+    d hold garbage and must not count."""
+    if d > 10 ** 6 and scales != "close":
+        pytest.skip("long vectors once")
+    rng = np.random.default_rng(d + M)
+    g = make_grad("laplace_sparse" if d > 10 ** 6 else "gauss", M, d, seed=7 * d + M)
+    if scales != "close":
+        g = g * (2.0 ** rng.integers(-40, 40, (M, 1))).astype(np.float32)
+    oc, osc, _ = oracle.quantize_pack(g, bucket=0)
+    if scales == "inf":
+        osc[M // 2, 0] = np.inf
+    if d % 16:
+        oc[:, -1] |= np.uint32((0xFFFFFFFF << (2 * (d % 16))) & 0xFFFFFFFF)      # garbage past d
+    L = qa.Layout.make(d, M, 0)
+    x0 = (rng.standard_normal(d) * 1e-2 * (rng.random(d) < 0.5)).astype(np.float32)
+    G0 = (rng.random(d) * 1e-4).astype(np.float32)
+    z0 = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+    for method in ("qcmd", "qcmd_z", "qrda"):
+        ox, oG, oz = x0.copy(), G0.copy(), z0.copy()
+        st = GpuState(L, oc, osc, x0, G0, z0)
+        with np.errstate(all="ignore"):
+            if method == "qrda":
+                oracle.step_qrda(oc, osc, d, 0, ox, oG, oz, 3, 0.1, 1e-4, 1e-8, 2)
+                st.qrda(3, 0.1, 1e-4, 1e-8, 2)
+            else:
+                oracle.step_qcmd(oc, osc, d, 0, ox, oG, oz if method == "qcmd_z" else None, 0.1, 1e-4, 1e-8, 2)
+                st.qcmd(0.1, 1e-4, 1e-8, 2, track_z=method == "qcmd_z")
+        x, G, z = st.get()
+        for got, want, name in ((x, ox, "x"), (G, oG, "G"), (z, oz, "z")):
+            same = (got.view(np.uint32) == want.view(np.uint32)) | (np.isnan(got) & np.isnan(want))
+            assert same.all(), (method, name, int((~same).sum()))
+
+
 @pytest.mark.parametrize("d,M,bucket,requant", AGGQ_CASES)
 def test_aggregate_quantize_matches_oracle_and_the_fused_step(d, M, bucket, requant):
     g = make_grad("gauss", M, d, seed=31 * d + M)
