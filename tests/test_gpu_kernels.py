@@ -480,17 +480,18 @@ AGGQ_CASES = [
 ]
 
 
-@pytest.mark.parametrize("d,M", [(70001, 8), (70001, 6), (9000, 1), (4097, 2), (70001 + 4096 * 1100, 5),
-                                 (4096 * 8200 + 17, 4)])
-@pytest.mark.parametrize("scales", ["close", "wide", "inf"])
+ONE_SCALE_CASES = [(d, M, kind) for d, M in ((70001, 8), (70001, 6), (9000, 1), (4097, 2))
+                   for kind in ("close", "wide", "inf")] + \
+                  [(70001 + 4096 * 1100, 5, "close"), (4096 * 8200 + 17, 4, "close")]   # 4 and 8 tiles per group
+
+
+@pytest.mark.parametrize("d,M,scales", ONE_SCALE_CASES)
 def test_steps_with_one_scale_everywhere_match_oracle(d, M, scales):
     """One scale per message, one for Q(SynQ), few workers: the two sums behind Q(SynQ) come from a
     kernel of their own that builds its tables once per work-group and walks 1, 4 or 8 tiles (by
     the vector's length).  Scales close together take its tables, scales spread over 80 binades
     its worker-ordered sum, an infinite scale poisons the sums; fields of the last code word beyond
     d hold garbage and must not count."""
-    if d > 10 ** 6 and scales != "close":
-        pytest.skip("long vectors once")
     rng = np.random.default_rng(d + M)
     g = make_grad("laplace_sparse" if d > 10 ** 6 else "gauss", M, d, seed=7 * d + M)
     if scales != "close":
