@@ -846,7 +846,8 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
 // are the same for every tile, so a work-group builds them once (no exponent-span test per tile, no
 // barrier per chunk) and walks several tiles, keeping its sums in registers; per tile that leaves
 // the loads, the gather, two look-ups per coordinate and the conversion.  PASS 0: sum of |gbar|;
-// PASS 1: sum and count of the |gbar| above the threshold.  One partial per work-group.
+// PASS 1: sum and count of the |gbar| above the threshold (one partial per work-group each);
+// PASS 2: the codes of Q(SynQ) for that threshold, for the server's call.
 struct SumArgs {
   const uint32_t* codes;
   const float* scales;
@@ -854,9 +855,10 @@ struct SumArgs {
   int64_t d, W, ntiles;
   int M, tiles_per_group, M_pow2, span_limit;
   double inv_M;
-  const float* thr;                     // PASS 1: the threshold
+  const float* thr;                     // PASS 1, 2: the threshold
   double* part_sum;
   uint32_t* part_cnt;
+  uint32_t* q_codes;                    // PASS 2
 };
 
 template <int PASS>
@@ -891,7 +893,7 @@ __global__ __launch_bounds__(kThreads) void requant_sums_kernel(SumArgs a) {
                                  fma(dj[1], (double)sc[4 * g + 1], dj[0] * (double)sc[4 * g])));
     __syncthreads();
   }
-  const float Delta = PASS == 1 ? a.thr[0] : 0.0f;
+  const float Delta = PASS >= 1 ? a.thr[0] : 0.0f;
   double s = 0.0;
   uint32_t cnt = 0;
   const int64_t tile0 = (int64_t)blockIdx.x * a.tiles_per_group;
@@ -942,6 +944,13 @@ __global__ __launch_bounds__(kThreads) void requant_sums_kernel(SumArgs a) {
       for (int j = 0; j < 16; ++j)
         if (j >= live) q[j] = 0.0f;
     }
+    if (PASS == 2) {
+      uint32_t word = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) word |= ternary_field(q[j], Delta) << (2 * j);
+      if ((int64_t)t < words_here) a.q_codes[tile * kTileWords + t] = word;
+      continue;
+    }
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const float av = fabsf(q[j]);
@@ -949,6 +958,7 @@ __global__ __launch_bounds__(kThreads) void requant_sums_kernel(SumArgs a) {
       else if (av > Delta) { s += (double)av; ++cnt; }
     }
   }
+  if (PASS == 2) return;
   s = block_sum_f64(s, lds_d);
   if (PASS == 1) {
     cnt = wave_sum_u32(cnt);
@@ -1131,11 +1141,27 @@ static void launch_mode(const StepArgs& a, bool track_z, bool requant, hipStream
 // (4 bytes each).  The sum passes are bound by instructions, not bytes, so the gain ends early:
 // measured at d = 1e8, one scale per vector, QCMD step 0.440 -> 0.400 ms at M = 2,
 // 0.446 -> 0.409 at M = 4, 0.464 -> 0.450 at M = 8, but 0.515 -> 0.600 at M = 12; the server's
-// call, which has no state to read, is faster with the average written out at every M.
+// call, which has no state to read, is faster with the average written out at every M (unless
+// every message has one scale: see requant_sums_kernel).
 constexpr int kRecomputeMaxM = 8;
 
 // The first two of those passes and the two finalize kernels between and after them: leaves the
 // thresholds and scales of Q(SynQ) in thr[] and scales[] (one per bucket of R).
+// Does the kernel above serve these messages and this second quantization?
+static bool one_scale_everywhere(const StepArgs& messages, const qa_layout* R) {
+  return messages.log2b < 0 && R->bucket == 0 && messages.M <= 8;
+}
+static SumArgs sum_args(const StepArgs& messages) {
+  SumArgs sa{};
+  sa.codes = messages.codes; sa.scales = messages.scales;
+  sa.code_stride = messages.code_stride; sa.scale_stride = messages.scale_stride;
+  sa.d = messages.d; sa.W = messages.W; sa.ntiles = tiles_of(messages.d);
+  sa.M = messages.M; sa.M_pow2 = messages.M_pow2; sa.inv_M = messages.inv_M;
+  sa.span_limit = messages.span_limit;
+  sa.tiles_per_group = sa.ntiles >= 8192 ? 8 : sa.ntiles >= 1024 ? 4 : 1;
+  return sa;
+}
+
 static int requant_sums_from_messages(const StepArgs& messages, const qa_layout* R, float* scales,
                                       float* thresholds, void* qws, size_t qws_bytes,
                                       const float** thr_out, hipStream_t stream) {
@@ -1143,15 +1169,9 @@ static int requant_sums_from_messages(const StepArgs& messages, const qa_layout*
   double* part_sum; uint32_t* part_cnt; float* thr;
   quantize_workspace_parts(R, qws, &part_sum, &part_cnt, &thr);
   *thr_out = thr;
-  if (messages.log2b < 0 && R->bucket == 0 && messages.M <= 8) {
+  if (one_scale_everywhere(messages, R)) {
     // one scale per message and one for Q(SynQ): the lean kernel, one partial per work-group
-    SumArgs sa{};
-    sa.codes = messages.codes; sa.scales = messages.scales;
-    sa.code_stride = messages.code_stride; sa.scale_stride = messages.scale_stride;
-    sa.d = messages.d; sa.W = messages.W; sa.ntiles = tiles_of(messages.d);
-    sa.M = messages.M; sa.M_pow2 = messages.M_pow2; sa.inv_M = messages.inv_M;
-    sa.span_limit = messages.span_limit;
-    sa.tiles_per_group = sa.ntiles >= 8192 ? 8 : sa.ntiles >= 1024 ? 4 : 1;
+    SumArgs sa = sum_args(messages);
     sa.thr = thr; sa.part_sum = part_sum; sa.part_cnt = part_cnt;
     const int64_t groups = (sa.ntiles + sa.tiles_per_group - 1) / sa.tiles_per_group;
     const dim3 grid((unsigned)groups), block(kThreads);
@@ -1327,6 +1347,17 @@ static int aggregate_quantize_common(const qa_layout* L, const uint32_t* codes, 
   if (!ws || ws_bytes < align256((size_t)L->d * sizeof(float)) + qws) return QA_ERR_WORKSPACE;
   if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
   char* p = static_cast<char*>(ws);
+  if (!sparse && qws != 0 && one_scale_everywhere(ag, &R)) {
+    // three passes over the messages (sums, kept sums, codes) instead of writing the average out
+    const float* thr = nullptr;
+    rc = requant_sums_from_messages(ag, &R, q_scales, q_thresholds, p, qws, &thr, stream);
+    if (rc != QA_OK) return rc;
+    SumArgs sa = sum_args(ag);
+    sa.thr = thr; sa.q_codes = q_codes;
+    const int64_t groups = (sa.ntiles + sa.tiles_per_group - 1) / sa.tiles_per_group;
+    hipLaunchKernelGGL(requant_sums_kernel<2>, dim3((unsigned)groups), dim3(kThreads), 0, stream, sa);
+    return launch_status();
+  }
   float* gbar = reinterpret_cast<float*>(p);            p += align256((size_t)L->d * sizeof(float));
   ag.gbar = gbar;
   const bool fuse_abs = qws != 0;

@@ -475,6 +475,8 @@ AGGQ_CASES = [
     (70001, 20, 4096, 2), (10000, 3, 64, 1), (10000, 5, 256, 1), (70001, 6, 2048, 1),
     (70001, 4, 16384, 1), (70001, 4, 0, 2), (9000, 48, 4096, 1), (4100, 8, 512, 2),
     (70001, 16, 0, 2), (70001, 8, 8192, 1), (70001, 13, 0, 2), (70001, 24, 16384, 1),
+    # one scale everywhere, up to 8 workers: three passes of the kernel that walks several tiles
+    (70001, 8, 0, 2), (70001, 7, 0, 2), (4096 * 1100 + 5, 3, 0, 2), (4097, 1, 0, 2),
     # complete chunks of 16 and of 8 workers, one to four of them, rows ending inside a 16-byte group
     (70001, 32, 4096, 1), (70001, 64, 4096, 1), (9000, 24, 4096, 1), (8192 + 16 * 7 + 5, 40, 4096, 1),
 ]
