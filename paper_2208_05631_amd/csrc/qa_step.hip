@@ -9,6 +9,9 @@
 // the accumulator + closed-form update, touching x, G (and z) exactly once.
 // The same kernel also takes its code words from sparse-encoded messages (expanded on the fly)
 // and, in aggregate mode with the second quantization, emits q_t as a coded message.
+// A second quantization whose buckets span tiles takes several launches (of this kernel, or of
+// requant_sums_kernel when every message has one scale) with the quantizer's finalize kernels
+// in between: see step_common.
 #include <cmath>
 #include <cstring>
 
@@ -920,7 +923,7 @@ __global__ __launch_bounds__(kThreads) void requant_sums_kernel(SumArgs a) {
         uint32_t wv = 0u;
         double sv = 0.0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
+        for (int k = 0; k < 8; ++k)                       // (selects: w[] and sc[] stay in registers)
           if (k == m) { wv = sanitize(w[k]); sv = (double)sc[k]; }
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
