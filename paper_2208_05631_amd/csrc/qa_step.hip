@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
   }
   const bool reorder_ok = !bad && (emax - emin) <= a.span_limit;
   // may the update use the short sqrt / division? (decided here so that emin, emax die early)
-  const bool try_core = reorder_ok && emin >= a.fast_emin && emax <= a.fast_emax;
+  bool try_core = reorder_ok && emin >= a.fast_emin && emax <= a.fast_emax;
 
   double acc[16];
 #pragma unroll
@@ -717,6 +717,10 @@ __global__ __launch_bounds__(kThreads) void step_lut_kernel(StepArgs a) {
     static_assert(RQ != kRqGiven || MODE != kAggregate, "the server's call writes the average out");
     const int64_t k2 = tile / a.rq_tiles;
     const float Delta = a.rq_thr[k2], s = a.rq_scale[k2];
+    // q = +-s comes from the whole bucket, not from this tile: the short forms of the update also
+    // need s itself inside the window that was checked for the tile's own scales
+    const int es = (int)((__float_as_uint(s) >> 23) & 0xFFu);
+    if (!(s == 0.0f || (es >= a.fast_emin && es <= a.fast_emax))) try_core = false;
 #pragma unroll
     for (int j = 0; j < 16; ++j) q[j] = q[j] > Delta ? s : (q[j] < -Delta ? -s : 0.0f);
   }

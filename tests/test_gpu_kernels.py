@@ -482,6 +482,40 @@ AGGQ_CASES = [
 ]
 
 
+@pytest.mark.parametrize("M", [3, 8, 24])
+@pytest.mark.parametrize("spread", [30, 60, 100])
+def test_one_scale_for_the_average_when_buckets_lie_far_apart(M, spread):
+    """Messages with a scale per 4096-bucket whose magnitudes differ by up to 2^spread from bucket
+    to bucket, and ONE scale for Q(SynQ): that scale is set by the largest buckets, so in most
+    tiles q = +-s lies far outside the range of the tile's own scales (which is what decides
+    whether the update may use the short forms of its division)."""
+    d, bucket = 70001, 4096
+    rng = np.random.default_rng(M * 1000 + spread)
+    nb = (d + bucket - 1) // bucket
+    g = make_grad("gauss", M, d, seed=M + spread)
+    factor = np.exp2(rng.integers(-spread, spread // 3, nb)).astype(np.float32)
+    g = g * np.repeat(factor, bucket)[:d][None, :]
+    oc, osc, _ = oracle.quantize_pack(g, bucket=bucket)
+    L = qa.Layout.make(d, M, bucket)
+    x0 = (rng.standard_normal(d) * 1e-2 * (rng.random(d) < 0.5)).astype(np.float32)
+    G0 = (rng.random(d) * 1e-4).astype(np.float32)
+    z0 = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+    for method in ("qcmd", "qcmd_z", "qrda"):
+        ox, oG, oz = x0.copy(), G0.copy(), z0.copy()
+        st = GpuState(L, oc, osc, x0, G0, z0)
+        with np.errstate(all="ignore"):
+            if method == "qrda":
+                oracle.step_qrda(oc, osc, d, bucket, ox, oG, oz, 2, 0.1, 1e-4, 1e-8, 2)
+                st.qrda(2, 0.1, 1e-4, 1e-8, 2)
+            else:
+                oracle.step_qcmd(oc, osc, d, bucket, ox, oG, oz if method == "qcmd_z" else None, 0.1, 1e-4, 1e-8, 2)
+                st.qcmd(0.1, 1e-4, 1e-8, 2, track_z=method == "qcmd_z")
+        x, G, z = st.get()
+        for got, want, name in ((x, ox, "x"), (G, oG, "G"), (z, oz, "z")):
+            same = (got.view(np.uint32) == want.view(np.uint32)) | (np.isnan(got) & np.isnan(want))
+            assert same.all(), (method, name, int((~same).sum()))
+
+
 ONE_SCALE_CASES = [(d, M, kind) for d, M in ((70001, 8), (70001, 6), (9000, 1), (4097, 2))
                    for kind in ("close", "wide", "inf")] + \
                   [(70001 + 4096 * 1100, 5, "close"), (4096 * 8200 + 17, 4, "close")]   # 4 and 8 tiles per group
