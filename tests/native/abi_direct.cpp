@@ -179,6 +179,36 @@ int main() {
     ok = ok && q_ok;
     (void)hipFree(dws); (void)hipFree(dc2); (void)hipFree(ds1); (void)hipFree(ds2);
   }
+  // one scale per message and one scale for Q(SynQ): the second quantization spans the whole
+  // vector, so the steps run it in separate passes over the caller's workspace
+  {
+    qa_layout L0 = L;
+    L0.bucket = 0; L0.scale_stride = 1;
+    const size_t qwsb = qa_workspace_bytes(&L0, QA_OP_QUANTIZE), wsb = qa_workspace_bytes(&L0, QA_OP_STEP);
+    void *dqws, *dws;
+    float* ds0;
+    HIP_OK(hipMalloc(&dqws, qwsb));
+    HIP_OK(hipMalloc(&dws, wsb));
+    HIP_OK(hipMalloc(&ds0, sizeof(float) * M));
+    QA_CALL(qa_quantize_pack(&L0, dg, gs, dcodes, ds0, nullptr, 0, dqws, qwsb, stream));
+    QA_CALL(qa_step_qcmd(&L0, dcodes, ds0, dx, dG, dz, eta, lambda, delta, QA_REQUANT_GLOBAL, dws, wsb, stream));
+    QA_CALL(qa_step_qrda(&L0, dcodes, ds0, dx, dG, dz, T + 2, eta, lambda, delta, QA_REQUANT_GLOBAL, dws, wsb,
+                         stream));
+    HIP_OK(hipMemcpyAsync(hx.data(), dx, sizeof(float) * d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(hG.data(), dG, sizeof(float) * d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(hz.data(), dz, sizeof(float) * d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipStreamSynchronize(stream));
+    std::vector<float> os0(M);
+    orc_quantize_pack(g.data(), gs, d, M, 0, 0.75f, oc.data(), L.code_stride, os0.data(), nullptr, 1, 0);
+    orc_step_qcmd(oc.data(), L.code_stride, os0.data(), 1, d, M, 0, 0.75f, ox.data(), oG.data(), oz.data(), eta,
+                  lambda, delta, 2);
+    orc_step_qrda(oc.data(), L.code_stride, os0.data(), 1, d, M, 0, 0.75f, ox.data(), oG.data(), oz.data(), T + 2,
+                  eta, lambda, delta, 2);
+    const bool g_ok = same(hx, ox, "x") && same(hG, oG, "G") && same(hz, oz, "z");
+    std::printf("steps with one scale for Q(SynQ): %s\n", g_ok ? "identical" : "DIFFERENT");
+    ok = ok && g_ok;
+    (void)hipFree(dqws); (void)hipFree(dws); (void)hipFree(ds0);
+  }
   // a dense minibatch gradient of the logistic loss (binary64 sums rounded once on both sides, in
   // different orders: values within 1e-6, the loss too)
   {

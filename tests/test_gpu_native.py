@@ -25,4 +25,5 @@ def test_c_program_matches_checker():
     assert sum(line.startswith("step ") and "identical" in line for line in out.splitlines()) == 4
     assert "qa_aggregate_unpack: identical" in out
     assert "qa_quantize_pack_static: identical" in out
+    assert "steps with one scale for Q(SynQ): identical" in out
     assert "qa_local_grad: within 1e-6" in out
