@@ -223,7 +223,10 @@ int qa_aggregate_unpack(const qa_layout* layout, const uint32_t* codes, const fl
  * x, G (and z) are read and written in place.  eta > 0, lambda >= 0, delta > 0.
  * ws: qa_workspace_bytes(layout, QA_OP_STEP); only used when the second quantization cannot
  * be done in one pass (QA_REQUANT_GLOBAL, or QA_REQUANT_BUCKET with bucket > 4096); may be
- * NULL with ws_bytes 0 otherwise. */
+ * NULL with ws_bytes 0 otherwise.  In that case the call enqueues several kernels (the two sums
+ * behind the threshold and the scale of q, each followed by a small finalize kernel, then the
+ * update); otherwise exactly one.  Nothing is copied or waited for: the call can be recorded
+ * into a HIP graph. */
 int qa_step_qcmd(const qa_layout* layout, const uint32_t* codes, const float* scales, float* x,
                  float* G, float* z_or_null, float eta, float lambda, float delta, int requant,
                  void* ws, size_t ws_bytes, void* stream);
