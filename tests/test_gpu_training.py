@@ -284,3 +284,51 @@ def test_training_steps_replay_identically_from_a_hip_graph(tiny_problem, method
         got = [host(v) for v in (tr.x, tr.G, tr.z, tr.codes, tr.scales)]
         for name, a, b in zip(("x", "G", "z", "codes", "scales"), got, want):
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (replay, name)
+
+
+@pytest.mark.parametrize("M,bucket,requant", [(8, 0, 2), (4, 4096, 2), (24, 0, 2), (6, 16384, 1)])
+def test_steps_whose_second_quantization_takes_several_launches_replay_from_a_hip_graph(M, bucket, requant):
+    """A second quantization over buckets that span tiles is several kernels on the caller's stream
+    (sums, finalize, kept sums, finalize, update; or the written-out average for many workers) and
+    nothing else, so it can be captured: quantize + QCMD + QRDA, replayed three times with eager
+    work in between, against the eager run, bit for bit."""
+    d = 70001
+    rng = np.random.default_rng(M + bucket)
+    g = dev((rng.standard_normal((M, (d + 3) // 4 * 4)) * 1e-2).astype(np.float32))
+    L = qa.Layout.make(d, M, bucket)
+    gs = g.shape[1]
+    codes = torch.zeros((M, L.code_stride), dtype=torch.int32, device=DEV)
+    scales = torch.zeros((M, L.scale_stride), dtype=torch.float32, device=DEV)
+    x, G, z = (torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(3))
+    ws_q = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_QUANTIZE))
+    ws_s = workspace(qa.qa_workspace_bytes(L, qa.QA_OP_STEP))
+
+    def run_steps():
+        qa.qa_quantize_pack(L, g, gs, codes, scales, None, 0, ws_q)
+        qa.qa_step_qcmd(L, codes, scales, x, G, z, 0.1, 1e-4, 1e-8, requant, ws_s)
+        qa.qa_step_qrda(L, codes, scales, x, G, z, 2, 0.1, 1e-4, 1e-8, requant, ws_s)
+        qa.qa_step_qcmd(L, codes, scales, x, G, None, 0.1, 1e-4, 1e-8, requant, ws_s)
+
+    def reset():
+        for v in (x, G, z):
+            v.zero_()
+
+    reset()
+    run_steps()
+    torch.cuda.synchronize()
+    want = [host(v).copy() for v in (x, G, z)]
+    assert np.count_nonzero(want[1]) > 0
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_steps()
+    for replay in range(3):
+        reset()
+        codes.fill_(-1)                         # eager work between the replays
+        ws_s.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("x", "G", "z"), (host(v) for v in (x, G, z)), want):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (replay, name)
