@@ -1165,7 +1165,8 @@ static SumArgs sum_args(const StepArgs& messages) {
   sa.d = messages.d; sa.W = messages.W; sa.ntiles = tiles_of(messages.d);
   sa.M = messages.M; sa.M_pow2 = messages.M_pow2; sa.inv_M = messages.inv_M;
   sa.span_limit = messages.span_limit;
-  sa.tiles_per_group = sa.ntiles >= 8192 ? 8 : sa.ntiles >= 1024 ? 4 : 1;
+  // several tiles per work-group only while that leaves a few thousand work-groups
+  sa.tiles_per_group = sa.ntiles >= 16384 ? 8 : sa.ntiles >= 8192 ? 4 : sa.ntiles >= 4096 ? 2 : 1;
   return sa;
 }
 
@@ -1354,8 +1355,9 @@ static int aggregate_quantize_common(const qa_layout* L, const uint32_t* codes, 
   if (!ws || ws_bytes < align256((size_t)L->d * sizeof(float)) + qws) return QA_ERR_WORKSPACE;
   if (!aligned(ws, 256)) return QA_ERR_ALIGNMENT;
   char* p = static_cast<char*>(ws);
-  if (!sparse && qws != 0 && one_scale_everywhere(ag, &R)) {
+  if (!sparse && qws != 0 && one_scale_everywhere(ag, &R) && tiles_of(L->d) >= 16384) {
     // three passes over the messages (sums, kept sums, codes) instead of writing the average out
+    // (long vectors only: five launches against four, d = 2^24 and M = 8: 0.044 against 0.039 ms)
     const float* thr = nullptr;
     rc = requant_sums_from_messages(ag, &R, q_scales, q_thresholds, p, qws, &thr, stream);
     if (rc != QA_OK) return rc;

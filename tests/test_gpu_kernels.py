@@ -476,7 +476,7 @@ AGGQ_CASES = [
     (70001, 4, 16384, 1), (70001, 4, 0, 2), (9000, 48, 4096, 1), (4100, 8, 512, 2),
     (70001, 16, 0, 2), (70001, 8, 8192, 1), (70001, 13, 0, 2), (70001, 24, 16384, 1),
     # one scale everywhere, up to 8 workers: three passes of the kernel that walks several tiles
-    (70001, 8, 0, 2), (70001, 7, 0, 2), (4096 * 1100 + 5, 3, 0, 2), (4097, 1, 0, 2),
+    (70001, 8, 0, 2), (70001, 7, 0, 2), (4096 * 16400 + 5, 2, 0, 2), (4097, 1, 0, 2),
     # complete chunks of 16 and of 8 workers, one to four of them, rows ending inside a 16-byte group
     (70001, 32, 4096, 1), (70001, 64, 4096, 1), (9000, 24, 4096, 1), (8192 + 16 * 7 + 5, 40, 4096, 1),
 ]
@@ -518,13 +518,14 @@ def test_one_scale_for_the_average_when_buckets_lie_far_apart(M, spread):
 
 ONE_SCALE_CASES = [(d, M, kind) for d, M in ((70001, 8), (70001, 6), (9000, 1), (4097, 2))
                    for kind in ("close", "wide", "inf")] + \
-                  [(70001 + 4096 * 1100, 5, "close"), (4096 * 8200 + 17, 4, "close")]   # 4 and 8 tiles per group
+                  [(4096 * 4100 + 3, 5, "close"), (4096 * 8200 + 17, 4, "close"),
+                   (4096 * 16400 + 5, 2, "close")]                             # 2, 4 and 8 tiles per group
 
 
 @pytest.mark.parametrize("d,M,scales", ONE_SCALE_CASES)
 def test_steps_with_one_scale_everywhere_match_oracle(d, M, scales):
     """One scale per message, one for Q(SynQ), few workers: the two sums behind Q(SynQ) come from a
-    kernel of their own that builds its tables once per work-group and walks 1, 4 or 8 tiles (by
+    kernel of their own that builds its tables once per work-group and walks 1, 2, 4 or 8 tiles (by
     the vector's length).  Scales close together take its tables, scales spread over 80 binades
     its worker-ordered sum, an infinite scale poisons the sums; fields of the last code word beyond
     d hold garbage and must not count."""
