@@ -33,19 +33,26 @@
 
 namespace qa {
 
+// Key = (bucket index << 31) | (0x7fffffff - bits(|v|)); with a single bucket (one threshold for
+// the whole vector) the bucket index is 0 and the key type is 32 bits wide: half the bytes in
+// every pass of the sort.
+template <typename K>
 struct SortKeyOf {
   const float* g;
   int shift;                                             // log2(bucket); 62 for one bucket
-  __host__ __device__ uint64_t operator()(int64_t i) const {
+  __host__ __device__ K operator()(int64_t i) const {
     uint32_t u;
     const float v = g[i];
     memcpy(&u, &v, 4);
-    return ((uint64_t)(i >> shift) << 31) | (uint64_t)(0x7fffffffu - (u & 0x7fffffffu));
+    const uint32_t low = 0x7fffffffu - (u & 0x7fffffffu);
+    if (sizeof(K) == 4) return (K)low;
+    return (K)(((uint64_t)(i >> shift) << 31) | (uint64_t)low);
   }
 };
 
+template <typename K>
 struct ExactArgs {
-  const uint64_t* keys;                                  // sorted
+  const K* keys;                                         // sorted
   int64_t d, ntiles, nb, tiles_per_bucket, bucket_len;   // bucket_len = d for one bucket
   double* tsum;                                          // per tile: sum of its magnitudes
   double* tbase;                                         // per tile: sum of the bucket's magnitudes before it
@@ -54,8 +61,9 @@ struct ExactArgs {
   float* thresholds;                                     // this worker's row
 };
 
-__device__ __forceinline__ float magnitude_of(uint64_t key) {
-  return __uint_as_float(0x7fffffffu - (uint32_t)(key & 0x7fffffffu));
+template <typename K>
+__device__ __forceinline__ float magnitude_of(K key) {
+  return __uint_as_float(0x7fffffffu - ((uint32_t)key & 0x7fffffffu));
 }
 
 // every thread receives the sum over the threads before it; *total = sum over the work-group
@@ -99,7 +107,8 @@ __device__ __forceinline__ void block_argmax(double& obj, int64_t& k, double* ld
     if (better(lds_o[w], lds_k[w], obj, k)) { obj = lds_o[w]; k = lds_k[w]; }
 }
 
-__global__ __launch_bounds__(kThreads) void exact_tile_sum_kernel(ExactArgs a) {
+template <typename K>
+__global__ __launch_bounds__(kThreads) void exact_tile_sum_kernel(ExactArgs<K> a) {
   __shared__ double lds_d[kWaves];
   const int64_t tile = blockIdx.x;
   const int64_t i0 = tile * kTile + 16 * (int64_t)threadIdx.x;
@@ -112,7 +121,8 @@ __global__ __launch_bounds__(kThreads) void exact_tile_sum_kernel(ExactArgs a) {
 }
 
 // one work-group per bucket: tbase[tile] = sum of tsum over the bucket's earlier tiles, in tile order
-__global__ __launch_bounds__(kThreads) void exact_scan_kernel(ExactArgs a) {
+template <typename K>
+__global__ __launch_bounds__(kThreads) void exact_scan_kernel(ExactArgs<K> a) {
   __shared__ double lds_d[kWaves];
   const int64_t t0 = (int64_t)blockIdx.x * a.tiles_per_bucket;
   const int64_t t1 = t0 + a.tiles_per_bucket < a.ntiles ? t0 + a.tiles_per_bucket : a.ntiles;
@@ -138,7 +148,8 @@ __global__ __launch_bounds__(kThreads) void exact_scan_kernel(ExactArgs a) {
 }
 
 // per tile: the best candidate k among its positions
-__global__ __launch_bounds__(kThreads) void exact_objective_kernel(ExactArgs a) {
+template <typename K>
+__global__ __launch_bounds__(kThreads) void exact_objective_kernel(ExactArgs<K> a) {
   __shared__ double lds_d[kWaves];
   __shared__ double lds_o[kWaves];
   __shared__ int64_t lds_k[kWaves];
@@ -176,7 +187,8 @@ __global__ __launch_bounds__(kThreads) void exact_objective_kernel(ExactArgs a) 
 }
 
 // per bucket: the best tile's k, and the largest magnitude not kept
-__global__ __launch_bounds__(kThreads) void exact_pick_kernel(ExactArgs a) {
+template <typename K>
+__global__ __launch_bounds__(kThreads) void exact_pick_kernel(ExactArgs<K> a) {
   __shared__ double lds_o[kWaves];
   __shared__ int64_t lds_k[kWaves];
   const int64_t kb = blockIdx.x;
@@ -215,15 +227,13 @@ size_t exact_sort_workspace_bytes(const qa_layout* L) {
   return xalign(d * 8) + 4 * xalign(nt * 8) + xalign(d * 8 + d + (size_t(4) << 20));
 }
 
-int exact_thresholds_sorted(const qa_layout* L, const float* g, int64_t g_stride, float* thresholds,
+template <typename K>
+static int exact_sorted_run(const qa_layout* L, const float* g, int64_t g_stride, float* thresholds,
                             void* ws, size_t ws_bytes, hipStream_t stream) {
-  if (!bucket_spans_tiles(L)) return QA_ERR_INVALID_ARG;
-  if (L->d >= (int64_t(1) << 32)) return QA_ERR_TOO_LARGE;
-  if (!ws || ws_bytes < exact_sort_workspace_bytes(L) || !aligned(ws, 256)) return QA_ERR_WORKSPACE;
   const size_t d = (size_t)L->d, nt = (size_t)tiles_of(L->d);
   char* p = static_cast<char*>(ws);
-  uint64_t* keys = reinterpret_cast<uint64_t*>(p);  p += xalign(d * 8);
-  ExactArgs a{};
+  K* keys = reinterpret_cast<K*>(p);  p += xalign(d * 8);
+  ExactArgs<K> a{};
   a.keys = keys; a.d = L->d; a.ntiles = (int64_t)nt; a.nb = buckets_of(L->d, L->bucket);
   a.bucket_len = L->bucket ? L->bucket : L->d;
   a.tiles_per_bucket = L->bucket ? L->bucket / kTile : (int64_t)nt;
@@ -238,7 +248,7 @@ int exact_thresholds_sorted(const qa_layout* L, const float* g, int64_t g_stride
   const dim3 block(kThreads);
   for (int m = 0; m < L->M; ++m) {
     auto in = rocprim::make_transform_iterator(rocprim::counting_iterator<int64_t>(0),
-                                               SortKeyOf{g + (int64_t)m * g_stride, shift});
+                                               SortKeyOf<K>{g + (int64_t)m * g_stride, shift});
     size_t temp_need = 0;
     if (rocprim::radix_sort_keys(nullptr, temp_need, in, keys, d, 0u, end_bit, stream) != hipSuccess)
       return QA_ERR_LAUNCH;
@@ -246,12 +256,22 @@ int exact_thresholds_sorted(const qa_layout* L, const float* g, int64_t g_stride
     if (rocprim::radix_sort_keys(temp, temp_need, in, keys, d, 0u, end_bit, stream) != hipSuccess)
       return QA_ERR_LAUNCH;
     a.thresholds = thresholds + (int64_t)m * L->scale_stride;
-    hipLaunchKernelGGL(exact_tile_sum_kernel, dim3((unsigned)nt), block, 0, stream, a);
-    hipLaunchKernelGGL(exact_scan_kernel, dim3((unsigned)a.nb), block, 0, stream, a);
-    hipLaunchKernelGGL(exact_objective_kernel, dim3((unsigned)nt), block, 0, stream, a);
-    hipLaunchKernelGGL(exact_pick_kernel, dim3((unsigned)a.nb), block, 0, stream, a);
+    hipLaunchKernelGGL(exact_tile_sum_kernel<K>, dim3((unsigned)nt), block, 0, stream, a);
+    hipLaunchKernelGGL(exact_scan_kernel<K>, dim3((unsigned)a.nb), block, 0, stream, a);
+    hipLaunchKernelGGL(exact_objective_kernel<K>, dim3((unsigned)nt), block, 0, stream, a);
+    hipLaunchKernelGGL(exact_pick_kernel<K>, dim3((unsigned)a.nb), block, 0, stream, a);
   }
   return launch_status();
+}
+
+int exact_thresholds_sorted(const qa_layout* L, const float* g, int64_t g_stride, float* thresholds,
+                            void* ws, size_t ws_bytes, hipStream_t stream) {
+  if (!bucket_spans_tiles(L)) return QA_ERR_INVALID_ARG;
+  if (L->d >= (int64_t(1) << 32)) return QA_ERR_TOO_LARGE;
+  if (!ws || ws_bytes < exact_sort_workspace_bytes(L) || !aligned(ws, 256)) return QA_ERR_WORKSPACE;
+  if (buckets_of(L->d, L->bucket) == 1)
+    return exact_sorted_run<uint32_t>(L, g, g_stride, thresholds, ws, ws_bytes, stream);
+  return exact_sorted_run<uint64_t>(L, g, g_stride, thresholds, ws, ws_bytes, stream);
 }
 
 }  // namespace qa
