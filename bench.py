@@ -364,6 +364,9 @@ def main():
                          "the default from d = 2^26 on), or simply as one contiguous [3][d] block "
                          "(block).  The record carries the probe's table and, for spread, the "
                          "step times of a fresh block measured after the timed steps")
+    ap.add_argument("--placement-probe", choices=("all", "first"), default="all",
+                    help="spread placement: time every combination of three candidate rows and take the "
+                         "fastest (default), or stop at the first that reaches the rate of a plain copy")
     ap.add_argument("--placement-rows", default=None,
                     help="with spread placement: take these three of the eight candidate rows as "
                          "x, G, z (e.g. 0,1,4) instead of probing, and skip the block's measurement: "
@@ -503,9 +506,10 @@ def main():
             assert len(best) == 3 and len(set(best)) == 3 and all(0 <= v < len(cand) for v in best)
             placement.update(chosen=list(best), probe_ms_per_step=None)
         else:
-            # Good enough = the step's bytes at 101 % of the rate a plain copy reaches in this
-            # process; the combinations are tried in index order (separate rows first) until one
-            # gets there, else the fastest of all 56 is taken.
+            # All 56 combinations are timed (four steps each, under two seconds in all) and the
+            # fastest is taken; with --placement-probe first the search stops at the first one
+            # that is good enough = the step's bytes at 101 % of the rate a plain copy reaches
+            # in this process (combinations in index order, separate rows first).
             pa = torch.empty(min(d, 1 << 30), dtype=torch.float32, device=dev).fill_(1.0)
             pb = torch.empty_like(pa)
             for _ in range(2):
@@ -521,8 +525,10 @@ def main():
             sched = [kind_of(2 + s_) for s_ in range(4)]
             step_bytes = sum(algorithmic_bytes_per_coord(k_, M) for k_ in sched) / len(sched) * d
             target_ms = step_bytes / (1.01 * copy_rate) * 1e3
-            best, table = qa_placement.choose_rows(cand, 3, probe_ms, good_enough_ms=target_ms)
-            placement.update(chosen=list(best), good_enough_ms=round(target_ms, 3), tried=len(table),
+            best, table = qa_placement.choose_rows(
+                cand, 3, probe_ms, good_enough_ms=target_ms if args.placement_probe == "first" else None)
+            placement.update(chosen=list(best), probe=args.placement_probe,
+                             good_enough_ms=round(target_ms, 3), tried=len(table),
                              probe_ms_per_step={str(c): round(v, 3) for c, v in table.items()})
         placement["row_ptrs"] = [hex(r.data_ptr()) for r in cand]
         keep = [cand[i] for i in best]
